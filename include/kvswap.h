@@ -1,0 +1,237 @@
+/*
+ * kvswap.h — C ABI of the paged KV-cache swap library for one MI355X (gfx950).
+ *
+ * The operations are the two the paper's hierarchical memory manager is built
+ * on (Section 5, first paragraph): "preempt" moves the KV cache of a preempted
+ * request out of GPU memory into host memory, "resume" reloads it when the
+ * request runs again; plus the incremental write-through of Section 5.1, where
+ * only KV produced since the previous offload is written to the host.  The
+ * paper works at request granularity above a token-level pool (Section 3.1,
+ * "Request Offload Manager" and "Hierarchical KV Cache Manager"), batches its
+ * transfers and runs them on dedicated eviction / loading streams ordered by
+ * events (Section 6, "KV Cache Manager").  This header fixes the byte-level
+ * contract the paper leaves open.
+ *
+ * ---------------------------------------------------------------------------
+ * Geometry
+ *   L = num_layers, H = num_kv_heads, D = head_dim, B = block_size (tokens),
+ *   e = bytes per element (2 for f16/bf16, 1 for fp8), N = num_blocks.
+ *   chunk       = B*H*D*e bytes: the K *or* V data of one block in one layer.
+ *                 A chunk is contiguous in the device pool.
+ *   block_bytes = 2*L*chunk.
+ *   With scales (fp8): scale_chunk = H*4 bytes per (block, layer, K|V),
+ *                 block_scale_bytes = 2*L*H*4.
+ *   S           = block_bytes + block_scale_bytes : one staging slot.
+ *
+ * Device pool addressing (bytes, all strides caller-given):
+ *   chunk(l, c, p)  at pool_dev  + l*layer_stride + c*kv_stride + p*block_stride
+ *   scales(l, c, p) at scale_dev + l*scale_layer_stride + c*scale_kv_stride
+ *                                + p*scale_block_stride
+ *   l in [0,L), c in {0 = K, 1 = V}, p in [0,N).
+ *
+ * Staging arena: staging_bytes / S slots of S bytes.  A request owns a
+ * contiguous extent of slots [base, base+cap).  Logical block j of the request
+ * lives in slot base+j:
+ *   data   of (l, c) at slot_offset + (2*l + c)*chunk
+ *   scales of (l, c) at slot_offset + block_bytes + (2*l + c)*H*4
+ * Inside a chunk the byte order of the pool is preserved.
+ * Extents are placed first-fit at the lowest free slot index, so placement is
+ * a deterministic function of the call history.
+ *
+ * Per-request state kept by the library, keyed by request id:
+ *   base, cap     staging extent
+ *   staged        number of leading logical blocks whose staging copy is valid
+ *   wm            watermark: number of leading FULL blocks already written
+ *                 through (Section 5.1: only newer blocks need writing)
+ *   swapped       set by kv_swap_out, cleared by kv_swap_in
+ *
+ * Conventions
+ *   - Every entry point returns 0 (KV_OK) or a negative KV_E* code.  No C++
+ *     exception crosses the boundary.
+ *   - All-or-nothing: a call checks every request and every block id before it
+ *     changes any state or enqueues any work.
+ *   - Calls are asynchronous.  Swap-out / delta work is enqueued on the evict
+ *     stream, swap-in work on the load stream, in issue order.  The library
+ *     inserts the cross-stream waits needed when a swap-in reads staging slots
+ *     an unfinished swap-out writes, and when a swap-out reuses slots an
+ *     unfinished swap-in still reads.  It does NOT track device blocks: the
+ *     caller must not pass destination blocks that in-flight work still reads.
+ *   - wait_event (nullable) is a hipEvent_t; the call's stream waits for it
+ *     before touching the pool (ordering after the caller's compute stream).
+ *   - Argument arrays are HOST pointers, read during the call, free on return.
+ *   - pool_dev, scale_dev, bounce_dev are DEVICE pointers; staging_host is a
+ *     pinned, device-mapped HOST pointer (hipHostMalloc / torch pin_memory),
+ *     or a device pointer when KV_STAGING_DEVICE is set.  All are owned by the
+ *     caller and must outlive the pool handle.  Base pointers and strides must
+ *     be multiples of 16 bytes (scale pointers/strides: multiples of 4).
+ *   - A handle is used by one thread at a time.
+ */
+#ifndef KVSWAP_H
+#define KVSWAP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct kv_pool kv_pool; /* opaque */
+
+typedef enum { KV_F16 = 0, KV_BF16 = 1, KV_FP8_E4M3 = 2 } kv_dtype;
+
+/* status codes */
+enum {
+  KV_OK = 0,
+  KV_EINVAL = -1, /* null/misaligned pointer, bad geometry, bad CSR, repeated request id,
+                     row length not matching the token count */
+  KV_ERANGE = -2, /* physical block id outside [0, N) */
+  KV_EDUP = -3,   /* the same destination block listed twice in one kv_swap_in / kv_move_blocks */
+  KV_ENOENT = -4, /* request id unknown */
+  KV_EEXIST = -5, /* request already swapped out (kv_swap_out twice, or delta after swap-out) */
+  KV_ENOSPC = -6, /* staging arena cannot hold the extent (or cannot grow it in place) */
+  KV_EHIP = -7,   /* a HIP runtime call failed; kv_last_hip_error() returns its code */
+  KV_ESTATE = -8  /* token count below the watermark (a request never shrinks) */
+};
+
+/* kv_pool_config.flags */
+enum {
+  KV_PATH_AUTO = 0u,      /* library picks the transfer path per direction */
+  KV_PATH_DMA = 1u,       /* gather into bounce_dev, then hipMemcpyAsync (needs bounce_dev) */
+  KV_PATH_ZEROCOPY = 2u,  /* kernels store to / load from the mapped host arena directly */
+  KV_STAGING_DEVICE = 4u, /* staging_host is device memory: the on-device gather/scatter */
+  KV_PLAN_ONLY = 8u       /* no HIP call is ever made: bookkeeping and descriptor lists only
+                             (host-logic tests on machines without a GPU) */
+};
+
+/* kv_swap_out_delta flags */
+enum { KV_DELTA_INCLUDE_TAIL = 1u };
+/* kv_swap_in flags */
+enum { KV_KEEP_STAGING = 1u };
+
+typedef struct {
+  uint32_t struct_size; /* sizeof(kv_pool_config), checked */
+  int32_t num_layers, num_kv_heads, head_dim, block_size; /* L, H, D, B */
+  int32_t dtype;      /* kv_dtype; only the element size matters to the copy */
+  int64_t num_blocks; /* N */
+  void* pool_dev;
+  int64_t layer_stride, kv_stride, block_stride; /* bytes */
+  void* scale_dev; /* NULL unless per-(block, layer, K|V, head) fp32 scales exist */
+  int64_t scale_layer_stride, scale_kv_stride, scale_block_stride; /* bytes */
+  void* staging_host;
+  int64_t staging_bytes;
+  void* bounce_dev; /* optional, for KV_PATH_DMA; first half serves swap-out, second swap-in */
+  int64_t bounce_bytes;
+  void* evict_stream; /* hipStream_t; NULL: the library creates and owns one */
+  void* load_stream;  /* hipStream_t; NULL: the library creates and owns one */
+  uint32_t flags;
+} kv_pool_config;
+
+/* Figures of the most recent swap call on a handle. */
+typedef struct {
+  uint32_t struct_size;
+  int32_t op;       /* 1 swap_out, 2 swap_out_delta, 3 swap_in, 4 move_blocks */
+  int32_t path;     /* KV_PATH_DMA or KV_PATH_ZEROCOPY (the latter also for device staging) */
+  int32_t launches; /* kernel launches enqueued */
+  int32_t copies;   /* hipMemcpyAsync calls enqueued (descriptor upload not counted) */
+  int32_t grid;     /* workgroups of the (last) data kernel */
+  int64_t blocks;   /* blocks moved */
+  int64_t bytes;    /* payload bytes = blocks * S */
+  double plan_us;   /* host time spent validating and building descriptors */
+  double enqueue_us; /* host time spent inside HIP enqueue calls */
+  float ms_total;   /* first enqueue to last completion on the stream (HIP events) */
+  float ms_kernel;  /* summed duration of the data kernels (HIP events around each launch) */
+} kv_stats;
+
+/* Create a handle over caller-owned memory.  Validates geometry, alignment and
+ * capacity; allocates only the library's own descriptor rings and events.
+ * Section 3.1 (separate CPU and GPU pools), Section 6 (dedicated streams). */
+int kv_pool_create(const kv_pool_config* cfg, kv_pool** out);
+
+/* Waits for all enqueued work, then frees the handle.  Caller memory untouched. */
+int kv_pool_destroy(kv_pool* p);
+
+/* Preempt (Section 5, operation (a)).  Block tables are CSR: request i owns
+ * block_ids[offsets[i] .. offsets[i+1]) in logical order; the row length must
+ * equal ceil(num_tokens[i] / B).  For every request: reserve an extent of that
+ * many slots if it has none (grow it in place if it is too small), copy every
+ * block — all layers, K and V, scales — into slots base+j, then staged = row
+ * length, wm = floor(num_tokens/B), swapped = 1.  The partial tail block is
+ * copied whole.  Repeated physical ids in a table are legal (read twice).
+ * Device blocks are left untouched.
+ * Errors: KV_EINVAL, KV_ERANGE, KV_EEXIST (already swapped), KV_ENOSPC, KV_EHIP. */
+int kv_swap_out(kv_pool* p, int32_t n, const uint64_t* req_ids, const int32_t* offsets,
+                const int32_t* block_ids, const int32_t* num_tokens, void* wait_event);
+
+/* Incremental write-through (Section 5.1; sized, ordered writes: Section 5.2).
+ * Requests are served in the order given (the caller's priority order).  For
+ * each: hi = floor(num_tokens/B), or ceil with KV_DELTA_INCLUDE_TAIL;
+ * m = min(hi, wm + budget left) (budget 0 = unlimited; if hi <= wm nothing
+ * moves); logical blocks [wm, m) are copied to slots base+wm.. ; the budget is
+ * charged m - wm; staged = max(staged, m); wm = min(m, floor(num_tokens/B));
+ * blocks_moved[i] (nullable) = m - old wm.  A block is never split.  The row
+ * length must be >= ceil(num_tokens/B).  An unknown request gets an extent of
+ * row-length slots; a known one is grown in place when the row is longer than
+ * its capacity.
+ * Errors: as kv_swap_out, plus KV_ESTATE when num_tokens < wm*B. */
+int kv_swap_out_delta(kv_pool* p, int32_t n, const uint64_t* req_ids, const int32_t* offsets,
+                      const int32_t* block_ids, const int32_t* num_tokens, int64_t block_budget,
+                      uint32_t flags, int32_t* blocks_moved, void* wait_event);
+
+/* Resume (Section 5, operation (b)).  Row i lists the freshly allocated
+ * destination blocks of request i; its length must equal staged.  Slot base+j
+ * is copied into block new_block_ids[offsets[i]+j] for all layers, K and V,
+ * scales.  No other pool byte is written.  All destination ids of one call
+ * must be distinct.  Afterwards the request is forgotten and its extent freed,
+ * unless KV_KEEP_STAGING: then the extent, staged and wm stay (the host copy
+ * remains a valid write-through image, Section 5.3) and swapped = 0.
+ * Errors: KV_EINVAL, KV_ERANGE, KV_EDUP, KV_ENOENT, KV_EHIP. */
+int kv_swap_in(kv_pool* p, int32_t n, const uint64_t* req_ids, const int32_t* offsets,
+               const int32_t* new_block_ids, uint32_t flags, void* wait_event);
+
+/* Blocks the calling thread until everything enqueued on this handle is done
+ * (Section 6: completion is signalled through events). */
+int kv_sync(kv_pool* p);
+
+/* On-device move of whole blocks inside the pool: block src_ids[i] is copied to
+ * dst_ids[i] (all layers, K, V, scales).  Destinations must be distinct and
+ * must not appear among the sources.  Runs on the evict stream.  This is the
+ * pool-to-pool form of the gather/scatter whose both ends are in HBM. */
+int kv_move_blocks(kv_pool* p, int64_t n, const int32_t* src_ids, const int32_t* dst_ids,
+                   void* wait_event);
+
+/* ---- helpers (bookkeeping, statistics, tuning) ---- */
+
+/* Reserve an extent of max_blocks slots for a request before its first delta
+ * (write-through appends, so the extent must be able to hold the final length).
+ * KV_EEXIST if the request is known. */
+int kv_req_reserve(kv_pool* p, uint64_t req_id, int32_t max_blocks);
+/* Forget a request and free its extent.  KV_ENOENT if unknown. */
+int kv_req_release(kv_pool* p, uint64_t req_id);
+/* Any out pointer may be NULL.  staging_offset is in bytes from staging_host. */
+int kv_req_query(kv_pool* p, uint64_t req_id, int64_t* staging_offset, int32_t* cap_blocks,
+                 int32_t* blocks_staged, int32_t* watermark, int32_t* swapped);
+/* Waits for the most recent swap call to finish, then reports it. */
+int kv_last_stats(kv_pool* p, kv_stats* out);
+/* Bytes of one staging slot (S) for this geometry. */
+int64_t kv_slot_bytes(const kv_pool* p);
+/* Descriptor list of the most recent swap call: pairs (phys_block, staging_slot)
+ * in launch order.  Copies at most cap pairs; returns the number the call
+ * produced.  Meant for host-logic tests under KV_PLAN_ONLY. */
+int64_t kv_last_plan(kv_pool* p, int32_t* phys, int64_t* slot, int64_t cap);
+
+/* Launch-shape knobs: value 0 restores the default. */
+enum {
+  KV_TUNE_MAX_WGS_DEVICE = 1, /* workgroup cap when both ends are in HBM */
+  KV_TUNE_MAX_WGS_LINK = 2,   /* workgroup cap when one end is host memory (CU budget) */
+  KV_TUNE_KERNEL_VARIANT = 3, /* 0 default; other values select experimental kernels */
+  KV_TUNE_DMA_SLICE_BLOCKS = 4 /* blocks per gather+copy slice on the DMA path */
+};
+int kv_pool_tune(kv_pool* p, int32_t what, int64_t value);
+
+int kv_last_hip_error(const kv_pool* p);
+const char* kv_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVSWAP_H */
