@@ -1,0 +1,852 @@
+// C ABI of the paged KV-cache swap for MI355X (declared in include/kvswap.h).
+//
+// Host side of each call: plan (planner.hpp) -> descriptor list -> one batched
+// launch per direction on the evict or load stream (paper Section 6: dedicated
+// streams for eviction and loading, batched transfers, event-based completion).
+// Two transfer paths exist for the host link:
+//   zero-copy  the gather/scatter kernel addresses the pinned host arena itself;
+//   DMA        gather into a device bounce buffer, then hipMemcpyAsync of each
+//              run of consecutive staging slots (and the mirror image for loads).
+// With KV_STAGING_DEVICE the arena is HBM and the same kernels give the
+// on-device gather/scatter.
+#include <hip/hip_runtime.h>
+
+#include <chrono>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <deque>
+#include <mutex>
+#include <new>
+#include <vector>
+
+#include "planner.hpp"
+
+#include "kernels.hip.inc"
+
+using kvswap::Desc;
+using kvswap::Plan;
+
+namespace {
+
+constexpr int kEvict = 0, kLoad = 1;
+
+struct Call {
+  uint64_t seq = 0;
+  int stream = kEvict;
+  hipEvent_t start = nullptr, end = nullptr;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> kev;
+  kv_stats st{};
+};
+
+struct RingSeg {
+  size_t begin, end;
+  uint64_t seq;
+};
+
+struct PendingRelease {
+  int64_t lo, hi;
+  uint64_t seq;  // load-stream call that still reads these slots
+};
+
+// KVSWAP_DEBUG=1 in the environment makes rejected configurations say why on stderr.
+bool debug_on() {
+  static const bool on = [] {
+    const char* e = std::getenv("KVSWAP_DEBUG");
+    return e && *e && *e != '0';
+  }();
+  return on;
+}
+#define KVDBG(...)                                   \
+  do {                                               \
+    if (debug_on()) {                                \
+      std::fprintf(stderr, "[kvswap] " __VA_ARGS__); \
+      std::fputc('\n', stderr);                      \
+    }                                                \
+  } while (0)
+
+double now_us() {
+  using namespace std::chrono;
+  return duration<double, std::micro>(steady_clock::now().time_since_epoch()).count();
+}
+
+}  // namespace
+
+struct kv_pool {
+  kv_pool_config cfg{};
+  int64_t chunk = 0, block_bytes = 0, scale_chunk = 0, block_scale_bytes = 0, S = 0, slots = 0;
+  bool plan_only = false, dev_staging = false;
+  char* arena_dev = nullptr;  // the arena as the kernels address it
+  kvswap::Planner planner;
+  std::mutex mu;
+
+  hipStream_t stream[2] = {nullptr, nullptr};
+  bool own_stream[2] = {false, false};
+
+  Desc* ring_host = nullptr;
+  Desc* ring_dev = nullptr;
+  size_t ring_cap = 0, ring_head = 0;
+  std::deque<RingSeg> ring_inflight;
+
+  std::vector<hipEvent_t> ev_free;
+  std::deque<Call> calls;  // oldest first; the newest is kept for kv_last_stats
+  uint64_t seq = 0;
+  std::vector<PendingRelease> pending;
+  std::vector<Desc> last_plan;
+  kv_stats plan_stats{};  // figures of a call that enqueued nothing
+  bool last_instant = false;
+  int last_hip = 0;
+
+  int64_t max_wgs_device = 0, max_wgs_link = 0, variant = 0, dma_slice = 0;
+  int cu_count = 256;
+};
+
+#define HIPCHK(p, expr)                         \
+  do {                                          \
+    hipError_t e_ = (expr);                     \
+    if (e_ != hipSuccess) {                     \
+      (p)->last_hip = (int)e_;                  \
+      return KV_EHIP;                           \
+    }                                           \
+  } while (0)
+
+namespace {
+
+int elem_bytes(int dtype) {
+  switch (dtype) {
+    case KV_F16:
+    case KV_BF16:
+      return 2;
+    case KV_FP8_E4M3:
+      return 1;
+    default:
+      return 0;
+  }
+}
+
+// true unless HIP knows the allocation and [ptr, ptr+need) leaves it
+bool range_ok(const void* ptr, int64_t need) {
+  hipDeviceptr_t base = nullptr;
+  size_t size = 0;
+  if (hipMemGetAddressRange(&base, &size, (hipDeviceptr_t)ptr) != hipSuccess) {
+    (void)hipGetLastError();
+    return true;
+  }
+  return (const char*)ptr + need <= (const char*)base + size;
+}
+
+int get_event(kv_pool* p, hipEvent_t* out) {
+  if (!p->ev_free.empty()) {
+    *out = p->ev_free.back();
+    p->ev_free.pop_back();
+    return KV_OK;
+  }
+  HIPCHK(p, hipEventCreate(out));
+  return KV_OK;
+}
+
+void recycle(kv_pool* p, Call& c) {
+  if (c.start) p->ev_free.push_back(c.start);
+  if (c.end) p->ev_free.push_back(c.end);
+  for (auto& k : c.kev) {
+    p->ev_free.push_back(k.first);
+    p->ev_free.push_back(k.second);
+  }
+  c.kev.clear();
+  c.start = c.end = nullptr;
+}
+
+Call* find_call(kv_pool* p, uint64_t seq) {
+  for (auto& c : p->calls)
+    if (c.seq == seq) return &c;
+  return nullptr;
+}
+
+// Is the call with this sequence number finished?  Retired calls are.
+bool seq_done(kv_pool* p, uint64_t seq) {
+  if (seq == 0) return true;
+  Call* c = find_call(p, seq);
+  if (!c || !c->end) return true;
+  hipError_t e = hipEventQuery(c->end);
+  if (e == hipSuccess) return true;
+  (void)hipGetLastError();
+  return false;
+}
+
+// Drop finished calls from the front, always keeping the newest for the statistics.
+void retire(kv_pool* p) {
+  while (p->calls.size() > 1) {
+    Call& c = p->calls.front();
+    if (c.end && hipEventQuery(c.end) != hipSuccess) {
+      (void)hipGetLastError();
+      break;
+    }
+    recycle(p, c);
+    p->calls.pop_front();
+  }
+  while (!p->ring_inflight.empty() && !find_call(p, p->ring_inflight.front().seq)) p->ring_inflight.pop_front();
+  size_t w = 0;
+  for (size_t i = 0; i < p->pending.size(); i++)
+    if (find_call(p, p->pending[i].seq)) p->pending[w++] = p->pending[i];
+  p->pending.resize(w);
+}
+
+int wait_seq_on_host(kv_pool* p, uint64_t seq) {
+  Call* c = find_call(p, seq);
+  if (c && c->end) HIPCHK(p, hipEventSynchronize(c->end));
+  return KV_OK;
+}
+
+int grow_ring(kv_pool* p, size_t need) {
+  for (int s = 0; s < 2; s++) HIPCHK(p, hipStreamSynchronize(p->stream[s]));
+  p->ring_inflight.clear();
+  if (p->ring_host) HIPCHK(p, hipHostFree(p->ring_host));
+  if (p->ring_dev) HIPCHK(p, hipFree(p->ring_dev));
+  p->ring_host = nullptr;
+  p->ring_dev = nullptr;
+  size_t cap = p->ring_cap ? p->ring_cap : (size_t)1 << 16;
+  while (cap < need) cap *= 2;
+  HIPCHK(p, hipHostMalloc((void**)&p->ring_host, cap * sizeof(Desc), hipHostMallocDefault));
+  HIPCHK(p, hipMalloc((void**)&p->ring_dev, cap * sizeof(Desc)));
+  p->ring_cap = cap;
+  p->ring_head = 0;
+  return KV_OK;
+}
+
+// Reserve n consecutive descriptors in both rings; waits (on the host) for
+// earlier calls whose descriptors still occupy that part.
+int ring_reserve(kv_pool* p, size_t n, uint64_t seq, size_t* at) {
+  if (n > p->ring_cap / 2) {
+    int rc = grow_ring(p, n * 4);
+    if (rc) return rc;
+  }
+  if (p->ring_head + n > p->ring_cap) p->ring_head = 0;
+  const size_t b = p->ring_head, e = b + n;
+  for (auto& s : p->ring_inflight)
+    if (s.begin < e && b < s.end && s.seq != seq) {
+      int rc = wait_seq_on_host(p, s.seq);
+      if (rc) return rc;
+    }
+  p->ring_inflight.push_back({b, e, seq});
+  p->ring_head = e;
+  *at = b;
+  return KV_OK;
+}
+
+template <int MODE>
+void launch_move(int u, int grid, hipStream_t st, const MoveArgs& a) {
+  switch (u) {
+    case 1:
+      hipLaunchKernelGGL((kv_move_kernel<MODE, 1>), dim3(grid), dim3(256), 0, st, a);
+      break;
+    case 2:
+      hipLaunchKernelGGL((kv_move_kernel<MODE, 2>), dim3(grid), dim3(256), 0, st, a);
+      break;
+    case 8:
+      hipLaunchKernelGGL((kv_move_kernel<MODE, 8>), dim3(grid), dim3(256), 0, st, a);
+      break;
+    default:
+      hipLaunchKernelGGL((kv_move_kernel<MODE, 4>), dim3(grid), dim3(256), 0, st, a);
+      break;
+  }
+}
+
+int pick_unroll(const kv_pool* p) {
+  if (p->variant == 1 || p->variant == 2 || p->variant == 4 || p->variant == 8) return (int)p->variant;
+  if (p->chunk >= 16384) return 4;
+  if (p->chunk >= 8192) return 2;
+  return 1;
+}
+
+// Upload n descriptors and launch one data kernel over them on stream `st`.
+// mode 0 gather, 1 scatter, 2 move.  `contig` is the contiguous side.
+int enqueue_kernel(kv_pool* p, Call& call, int mode, const Desc* desc, size_t n, char* contig, bool link) {
+  if (n == 0) return KV_OK;
+  hipStream_t st = p->stream[call.stream];
+  size_t at = 0;
+  int rc = ring_reserve(p, n, call.seq, &at);
+  if (rc) return rc;
+  std::memcpy(p->ring_host + at, desc, n * sizeof(Desc));
+  HIPCHK(p, hipMemcpyAsync(p->ring_dev + at, p->ring_host + at, n * sizeof(Desc), hipMemcpyHostToDevice, st));
+
+  const int u = pick_unroll(p);
+  const int64_t piece = 256 * 16 * (int64_t)u;
+  MoveArgs a;
+  a.pool = (char*)p->cfg.pool_dev;
+  a.ls = p->cfg.layer_stride;
+  a.ks = p->cfg.kv_stride;
+  a.bs = p->cfg.block_stride;
+  a.scale = (char*)p->cfg.scale_dev;
+  a.sls = p->cfg.scale_layer_stride;
+  a.sks = p->cfg.scale_kv_stride;
+  a.sbs = p->cfg.scale_block_stride;
+  a.contig = contig;
+  a.S = p->S;
+  a.block_bytes = p->block_bytes;
+  a.desc = p->ring_dev + at;
+  a.chunk = (int32_t)p->chunk;
+  a.ppc = (int32_t)((p->chunk + piece - 1) / piece);
+  a.jobs_per_block = 2 * p->cfg.num_layers * a.ppc;
+  a.H = p->cfg.num_kv_heads;
+  a.scale_words = p->cfg.scale_dev ? 2 * p->cfg.num_layers * p->cfg.num_kv_heads : 0;
+  a.n_data_jobs = (int64_t)n * a.jobs_per_block;
+  a.n_jobs = a.n_data_jobs + (a.scale_words ? (int64_t)n : 0);
+
+  int64_t cap = link ? (p->max_wgs_link ? p->max_wgs_link : 2 * (int64_t)p->cu_count)
+                     : (p->max_wgs_device ? p->max_wgs_device : 8 * (int64_t)p->cu_count);
+  const int grid = (int)std::min<int64_t>(a.n_jobs, cap);
+
+  hipEvent_t k0, k1;
+  if ((rc = get_event(p, &k0)) || (rc = get_event(p, &k1))) return rc;
+  HIPCHK(p, hipEventRecord(k0, st));
+  if (mode == 0)
+    launch_move<0>(u, grid, st, a);
+  else if (mode == 1)
+    launch_move<1>(u, grid, st, a);
+  else
+    launch_move<2>(u, grid, st, a);
+  HIPCHK(p, hipGetLastError());
+  HIPCHK(p, hipEventRecord(k1, st));
+  call.kev.push_back({k0, k1});
+  call.st.launches++;
+  call.st.grid = grid;
+  return KV_OK;
+}
+
+bool use_dma(const kv_pool* p) {
+  if (p->dev_staging) return false;
+  return (p->cfg.flags & KV_PATH_DMA) != 0;
+}
+
+// Move the planned blocks between pool and arena.  out = true: pool -> arena.
+int enqueue_transfer(kv_pool* p, Call& call, const std::vector<Desc>& desc, bool out) {
+  char* arena = (char*)p->cfg.staging_host;
+  const size_t n = desc.size();
+  if (!use_dma(p)) {
+    call.st.path = KV_PATH_ZEROCOPY;
+    return enqueue_kernel(p, call, out ? 0 : 1, desc.data(), n, p->arena_dev, !p->dev_staging);
+  }
+  call.st.path = KV_PATH_DMA;
+  hipStream_t st = p->stream[call.stream];
+  const int64_t half_slots = (p->cfg.bounce_bytes / 2) / p->S;
+  char* bounce = (char*)p->cfg.bounce_dev + (out ? 0 : (p->cfg.bounce_bytes / 2 / 16) * 16);
+  int64_t slice = half_slots;
+  if (p->dma_slice > 0) slice = std::min<int64_t>(slice, p->dma_slice);
+  std::vector<Desc> kd;
+  for (size_t a0 = 0; a0 < n; a0 += (size_t)slice) {
+    const size_t a1 = std::min(n, a0 + (size_t)slice);
+    kd.resize(a1 - a0);
+    for (size_t i = a0; i < a1; i++) kd[i - a0] = {desc[i].a, (int32_t)(i - a0)};
+    if (out) {
+      int rc = enqueue_kernel(p, call, 0, kd.data(), kd.size(), bounce, false);
+      if (rc) return rc;
+    }
+    // one copy per run of consecutive staging slots
+    for (size_t i = a0; i < a1;) {
+      size_t j = i + 1;
+      while (j < a1 && (uint32_t)desc[j].b == (uint32_t)desc[j - 1].b + 1) j++;
+      char* h = arena + (int64_t)(uint32_t)desc[i].b * p->S;
+      char* d = bounce + (int64_t)(i - a0) * p->S;
+      const size_t bytes = (j - i) * (size_t)p->S;
+      if (out)
+        HIPCHK(p, hipMemcpyAsync(h, d, bytes, hipMemcpyDeviceToHost, st));
+      else
+        HIPCHK(p, hipMemcpyAsync(d, h, bytes, hipMemcpyHostToDevice, st));
+      call.st.copies++;
+      i = j;
+    }
+    if (!out) {
+      int rc = enqueue_kernel(p, call, 1, kd.data(), kd.size(), bounce, false);
+      if (rc) return rc;
+    }
+  }
+  return KV_OK;
+}
+
+// Open a call record: cross-stream waits, caller's event, start event.
+int open_call(kv_pool* p, int stream, int op, uint64_t wait_seq, void* wait_event, Call** out) {
+  retire(p);
+  p->last_instant = false;
+  p->calls.emplace_back();
+  Call& c = p->calls.back();
+  c.seq = ++p->seq;
+  c.stream = stream;
+  c.st.struct_size = sizeof(kv_stats);
+  c.st.op = op;
+  hipStream_t st = p->stream[stream];
+  if (wait_seq) {
+    Call* dep = find_call(p, wait_seq);
+    if (dep && dep->stream != stream && dep->end) HIPCHK(p, hipStreamWaitEvent(st, dep->end, 0));
+  }
+  if (wait_event) HIPCHK(p, hipStreamWaitEvent(st, (hipEvent_t)wait_event, 0));
+  int rc;
+  if ((rc = get_event(p, &c.start)) || (rc = get_event(p, &c.end))) return rc;
+  HIPCHK(p, hipEventRecord(c.start, st));
+  *out = &c;
+  return KV_OK;
+}
+
+int close_call(kv_pool* p, Call& c) {
+  HIPCHK(p, hipEventRecord(c.end, p->stream[c.stream]));
+  return KV_OK;
+}
+
+// Newest unfinished load-stream call that still reads any slot in the given runs.
+uint64_t pending_reader(kv_pool* p, const std::vector<std::pair<int64_t, int64_t>>& runs) {
+  uint64_t s = 0;
+  for (auto& r : runs)
+    for (auto& q : p->pending)
+      if (q.lo < r.first + r.second && r.first < q.hi) s = std::max(s, q.seq);
+  return s;
+}
+
+void fill_plan_stats(kv_pool* p, kv_stats* st, int op, size_t blocks, double plan_us) {
+  st->struct_size = sizeof(kv_stats);
+  st->op = op;
+  st->blocks = (int64_t)blocks;
+  st->bytes = (int64_t)blocks * p->S;
+  st->plan_us = plan_us;
+}
+
+}  // namespace
+
+extern "C" {
+
+int kv_pool_create(const kv_pool_config* cfg, kv_pool** out) {
+#define REJECT(why)          \
+  do {                       \
+    KVDBG("rejected: " why); \
+    return KV_EINVAL;        \
+  } while (0)
+  if (!cfg || !out) return KV_EINVAL;
+  *out = nullptr;
+  if (cfg->struct_size != sizeof(kv_pool_config)) REJECT("struct_size does not match this library");
+  const int e = elem_bytes(cfg->dtype);
+  if (e == 0 || cfg->num_layers <= 0 || cfg->num_kv_heads <= 0 || cfg->head_dim <= 0 || cfg->block_size <= 0 ||
+      cfg->num_blocks <= 0 || cfg->num_blocks > INT32_MAX)
+    REJECT("bad dtype or non-positive geometry");
+  const bool plan_only = (cfg->flags & KV_PLAN_ONLY) != 0;
+  const int64_t chunk = (int64_t)cfg->block_size * cfg->num_kv_heads * cfg->head_dim * e;
+  if (chunk % 16 || chunk > (1 << 30)) REJECT("chunk (B*H*D*e) must be a multiple of 16 bytes and at most 1 GiB");
+  if (cfg->layer_stride <= 0 || cfg->kv_stride <= 0 || cfg->block_stride <= 0 || cfg->layer_stride % 16 ||
+      cfg->kv_stride % 16 || cfg->block_stride % 16)
+    REJECT("pool strides must be positive multiples of 16 bytes");
+  if (!plan_only && (!cfg->pool_dev || !cfg->staging_host)) REJECT("pool_dev and staging_host are required");
+  if (((uintptr_t)cfg->pool_dev | (uintptr_t)cfg->staging_host | (uintptr_t)cfg->bounce_dev) % 16)
+    REJECT("pool_dev, staging_host and bounce_dev must be 16-byte aligned");
+  if (cfg->staging_bytes < 0 || cfg->bounce_bytes < 0) REJECT("negative size");
+  const bool scales = cfg->scale_dev != nullptr || (plan_only && cfg->scale_block_stride > 0);
+  int64_t scale_chunk = 0;
+  if (scales) {
+    scale_chunk = (int64_t)cfg->num_kv_heads * 4;
+    if (cfg->scale_layer_stride <= 0 || cfg->scale_kv_stride <= 0 || cfg->scale_block_stride <= 0 ||
+        cfg->scale_layer_stride % 4 || cfg->scale_kv_stride % 4 || cfg->scale_block_stride % 4 ||
+        (uintptr_t)cfg->scale_dev % 4)
+      REJECT("scale pointer and strides must be positive multiples of 4 bytes");
+    // keeps every staging slot 16-byte aligned
+    if ((2 * cfg->num_layers * scale_chunk) % 16) REJECT("2*L*H*4 must be a multiple of 16 bytes");
+  }
+  if ((cfg->flags & KV_PATH_DMA) && (cfg->flags & KV_PATH_ZEROCOPY)) REJECT("both transfer paths forced");
+  if ((cfg->flags & KV_PATH_DMA) && (cfg->flags & KV_STAGING_DEVICE)) REJECT("DMA path with a device arena");
+#undef REJECT
+
+  kv_pool* p = new (std::nothrow) kv_pool;
+  if (!p) return KV_EINVAL;
+  p->cfg = *cfg;
+  p->plan_only = plan_only;
+  p->dev_staging = (cfg->flags & KV_STAGING_DEVICE) != 0;
+  p->chunk = chunk;
+  p->block_bytes = 2 * (int64_t)cfg->num_layers * chunk;
+  p->scale_chunk = scale_chunk;
+  p->block_scale_bytes = 2 * (int64_t)cfg->num_layers * scale_chunk;
+  p->S = p->block_bytes + p->block_scale_bytes;
+  p->slots = cfg->staging_bytes / p->S;
+  if (p->slots > INT32_MAX) p->slots = INT32_MAX;
+  if (!scales) p->cfg.scale_dev = nullptr;
+  p->planner.init(cfg->num_blocks, cfg->block_size, p->slots);
+  if ((cfg->flags & KV_PATH_DMA) && (!cfg->bounce_dev || (cfg->bounce_bytes / 2) / p->S < 1)) {
+    KVDBG("rejected: the DMA path needs a bounce buffer of at least two slots");
+    delete p;
+    return KV_EINVAL;
+  }
+  if (plan_only) {
+    *out = p;
+    return KV_OK;
+  }
+
+  // The kernels trust these extents: refuse a pool whose strides leave its allocation.
+  const int64_t pool_need = (cfg->num_layers - 1) * cfg->layer_stride + cfg->kv_stride +
+                            (cfg->num_blocks - 1) * cfg->block_stride + chunk;
+  bool ok = range_ok(cfg->pool_dev, pool_need);
+  if (!ok) KVDBG("pool strides reach %lld bytes, past the end of the allocation", (long long)pool_need);
+  if (ok && scales) {
+    ok = range_ok(cfg->scale_dev, (cfg->num_layers - 1) * cfg->scale_layer_stride + cfg->scale_kv_stride +
+                                      (cfg->num_blocks - 1) * cfg->scale_block_stride + scale_chunk);
+    if (!ok) KVDBG("scale strides reach past the end of the allocation");
+  }
+  if (ok && !range_ok(cfg->staging_host, cfg->staging_bytes)) {
+    ok = false;
+    KVDBG("staging_bytes reaches past the end of the arena allocation");
+  }
+  if (ok && cfg->bounce_dev && !range_ok(cfg->bounce_dev, cfg->bounce_bytes)) {
+    ok = false;
+    KVDBG("bounce_bytes reaches past the end of the bounce allocation");
+  }
+  if (ok) {
+    hipPointerAttribute_t at;
+    hipError_t er = hipPointerGetAttributes(&at, cfg->pool_dev);
+    if (er != hipSuccess || at.type != hipMemoryTypeDevice) {
+      ok = false;
+      KVDBG("pool_dev is not device memory (hip error %d, memory type %d)", (int)er, er == hipSuccess ? (int)at.type : -1);
+    }
+    (void)hipGetLastError();
+    if (ok) {
+      er = hipPointerGetAttributes(&at, cfg->staging_host);
+      if (er != hipSuccess) {
+        ok = false;  // pageable or unknown memory cannot be a staging arena
+        KVDBG("staging_host is unknown to HIP (error %d): it must be pinned memory", (int)er);
+      } else if (p->dev_staging ? at.type != hipMemoryTypeDevice : at.type != hipMemoryTypeHost) {
+        ok = false;
+        KVDBG("staging_host has memory type %d, expected %s memory", (int)at.type, p->dev_staging ? "device" : "pinned host");
+      } else {
+        p->arena_dev = (char*)(at.devicePointer ? at.devicePointer : cfg->staging_host);
+      }
+      (void)hipGetLastError();
+    }
+  }
+  if (!ok) {
+    delete p;
+    return KV_EINVAL;
+  }
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+    p->cu_count = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  void* given[2] = {cfg->evict_stream, cfg->load_stream};
+  int rc = KV_OK;
+  for (int s = 0; s < 2 && !rc; s++) {
+    if (given[s]) {
+      p->stream[s] = (hipStream_t)given[s];
+    } else {
+      hipError_t er = hipStreamCreateWithFlags(&p->stream[s], hipStreamNonBlocking);
+      if (er != hipSuccess) {
+        p->last_hip = (int)er;
+        rc = KV_EHIP;
+      } else {
+        p->own_stream[s] = true;
+      }
+    }
+  }
+  if (!rc) rc = grow_ring(p, (size_t)1 << 16);
+  if (rc) {
+    kv_pool_destroy(p);
+    return rc;
+  }
+  *out = p;
+  return KV_OK;
+}
+
+int kv_pool_destroy(kv_pool* p) {
+  if (!p) return KV_EINVAL;
+  int rc = KV_OK;
+  if (!p->plan_only) {
+    for (int s = 0; s < 2; s++)
+      if (p->stream[s] && hipStreamSynchronize(p->stream[s]) != hipSuccess) rc = KV_EHIP;
+    for (auto& c : p->calls) recycle(p, c);
+    for (auto ev : p->ev_free) (void)hipEventDestroy(ev);
+    if (p->ring_host) (void)hipHostFree(p->ring_host);
+    if (p->ring_dev) (void)hipFree(p->ring_dev);
+    for (int s = 0; s < 2; s++)
+      if (p->own_stream[s]) (void)hipStreamDestroy(p->stream[s]);
+  }
+  delete p;
+  return rc;
+}
+
+static int swap_out_common(kv_pool* p, int op, Plan& plan, double t0, void* wait_event) {
+  p->last_plan = plan.desc;
+  const double t1 = now_us();
+  if (p->plan_only) {
+    p->plan_stats = kv_stats{};
+    fill_plan_stats(p, &p->plan_stats, op, plan.desc.size(), t1 - t0);
+    return KV_OK;
+  }
+  // slots this call writes may still be read by an unfinished swap-in
+  uint64_t dep = std::max(plan.wait_in_seq, pending_reader(p, plan.fresh));
+  if (dep && seq_done(p, dep)) dep = 0;
+  if (plan.desc.empty() && !wait_event) {  // nothing to enqueue
+    p->plan_stats = kv_stats{};
+    fill_plan_stats(p, &p->plan_stats, op, 0, t1 - t0);
+    p->last_instant = true;
+    return KV_OK;
+  }
+  Call* c = nullptr;
+  int rc = open_call(p, kEvict, op, dep, wait_event, &c);
+  if (rc) return rc;
+  fill_plan_stats(p, &c->st, op, plan.desc.size(), t1 - t0);
+  rc = enqueue_transfer(p, *c, plan.desc, true);
+  if (rc) return rc;
+  rc = close_call(p, *c);
+  if (rc) return rc;
+  for (uint64_t id : plan.touched)
+    if (kvswap::Req* r = p->planner.find_mut(id)) r->out_seq = c->seq;
+  c->st.enqueue_us = now_us() - t1;
+  return KV_OK;
+}
+
+int kv_swap_out(kv_pool* p, int32_t n, const uint64_t* req_ids, const int32_t* offsets, const int32_t* block_ids,
+                const int32_t* num_tokens, void* wait_event) {
+  if (!p) return KV_EINVAL;
+  std::lock_guard<std::mutex> g(p->mu);
+  const double t0 = now_us();
+  Plan plan;
+  int rc = p->planner.plan_swap_out(n, req_ids, offsets, block_ids, num_tokens, &plan);
+  if (rc) return rc;
+  return swap_out_common(p, 1, plan, t0, wait_event);
+}
+
+int kv_swap_out_delta(kv_pool* p, int32_t n, const uint64_t* req_ids, const int32_t* offsets,
+                      const int32_t* block_ids, const int32_t* num_tokens, int64_t block_budget, uint32_t flags,
+                      int32_t* blocks_moved, void* wait_event) {
+  if (!p) return KV_EINVAL;
+  std::lock_guard<std::mutex> g(p->mu);
+  const double t0 = now_us();
+  Plan plan;
+  int rc = p->planner.plan_delta(n, req_ids, offsets, block_ids, num_tokens, block_budget, flags, blocks_moved,
+                                 &plan);
+  if (rc) return rc;
+  return swap_out_common(p, 2, plan, t0, wait_event);
+}
+
+int kv_swap_in(kv_pool* p, int32_t n, const uint64_t* req_ids, const int32_t* offsets,
+               const int32_t* new_block_ids, uint32_t flags, void* wait_event) {
+  if (!p) return KV_EINVAL;
+  std::lock_guard<std::mutex> g(p->mu);
+  const double t0 = now_us();
+  Plan plan;
+  int rc = p->planner.plan_swap_in(n, req_ids, offsets, new_block_ids, flags, &plan);
+  if (rc) return rc;
+  p->last_plan = plan.desc;
+  const double t1 = now_us();
+  if (p->plan_only) {
+    p->plan_stats = kv_stats{};
+    fill_plan_stats(p, &p->plan_stats, 3, plan.desc.size(), t1 - t0);
+    return KV_OK;
+  }
+  uint64_t dep = plan.wait_out_seq;
+  if (dep && seq_done(p, dep)) dep = 0;
+  if (plan.desc.empty() && !wait_event) {
+    p->plan_stats = kv_stats{};
+    fill_plan_stats(p, &p->plan_stats, 3, 0, t1 - t0);
+    p->last_instant = true;
+    return KV_OK;
+  }
+  Call* c = nullptr;
+  rc = open_call(p, kLoad, 3, dep, wait_event, &c);
+  if (rc) return rc;
+  fill_plan_stats(p, &c->st, 3, plan.desc.size(), t1 - t0);
+  rc = enqueue_transfer(p, *c, plan.desc, false);
+  if (rc) return rc;
+  rc = close_call(p, *c);
+  if (rc) return rc;
+  for (uint64_t id : plan.touched)
+    if (kvswap::Req* r = p->planner.find_mut(id)) r->in_seq = c->seq;
+  for (auto& f : plan.freed) p->pending.push_back({f.first, f.first + f.second, c->seq});
+  c->st.enqueue_us = now_us() - t1;
+  return KV_OK;
+}
+
+int kv_move_blocks(kv_pool* p, int64_t n, const int32_t* src_ids, const int32_t* dst_ids, void* wait_event) {
+  if (!p) return KV_EINVAL;
+  std::lock_guard<std::mutex> g(p->mu);
+  const double t0 = now_us();
+  Plan plan;
+  int rc = p->planner.plan_move(n, src_ids, dst_ids, &plan);
+  if (rc) return rc;
+  p->last_plan = plan.desc;
+  const double t1 = now_us();
+  if (p->plan_only || (plan.desc.empty() && !wait_event)) {
+    p->plan_stats = kv_stats{};
+    fill_plan_stats(p, &p->plan_stats, 4, plan.desc.size(), t1 - t0);
+    p->last_instant = true;
+    return KV_OK;
+  }
+  Call* c = nullptr;
+  rc = open_call(p, kEvict, 4, 0, wait_event, &c);
+  if (rc) return rc;
+  fill_plan_stats(p, &c->st, 4, plan.desc.size(), t1 - t0);
+  c->st.path = KV_PATH_ZEROCOPY;
+  rc = enqueue_kernel(p, *c, 2, plan.desc.data(), plan.desc.size(), nullptr, false);
+  if (rc) return rc;
+  rc = close_call(p, *c);
+  if (rc) return rc;
+  c->st.enqueue_us = now_us() - t1;
+  return KV_OK;
+}
+
+int kv_sync(kv_pool* p) {
+  if (!p) return KV_EINVAL;
+  std::lock_guard<std::mutex> g(p->mu);
+  if (p->plan_only) return KV_OK;
+  for (int s = 0; s < 2; s++) HIPCHK(p, hipStreamSynchronize(p->stream[s]));
+  retire(p);
+  return KV_OK;
+}
+
+int kv_req_reserve(kv_pool* p, uint64_t req_id, int32_t max_blocks) {
+  if (!p) return KV_EINVAL;
+  std::lock_guard<std::mutex> g(p->mu);
+  return p->planner.reserve(req_id, max_blocks);
+}
+
+int kv_req_release(kv_pool* p, uint64_t req_id) {
+  if (!p) return KV_EINVAL;
+  std::lock_guard<std::mutex> g(p->mu);
+  kvswap::Req was;
+  int rc = p->planner.release(req_id, &was);
+  if (rc || p->plan_only) return rc;
+  // the slots may still be in use by unfinished work of either stream: later writers wait for it
+  const uint64_t s = std::max(was.in_seq, was.out_seq);
+  if (s && was.cap && !seq_done(p, s)) p->pending.push_back({was.base, was.base + was.cap, s});
+  return KV_OK;
+}
+
+int kv_req_query(kv_pool* p, uint64_t req_id, int64_t* staging_offset, int32_t* cap_blocks, int32_t* blocks_staged,
+                 int32_t* watermark, int32_t* swapped) {
+  if (!p) return KV_EINVAL;
+  std::lock_guard<std::mutex> g(p->mu);
+  const kvswap::Req* r = p->planner.find(req_id);
+  if (!r) return KV_ENOENT;
+  if (staging_offset) *staging_offset = r->base * p->S;
+  if (cap_blocks) *cap_blocks = r->cap;
+  if (blocks_staged) *blocks_staged = r->staged;
+  if (watermark) *watermark = r->wm;
+  if (swapped) *swapped = r->swapped ? 1 : 0;
+  return KV_OK;
+}
+
+int kv_last_stats(kv_pool* p, kv_stats* out) {
+  if (!p || !out) return KV_EINVAL;
+  std::lock_guard<std::mutex> g(p->mu);
+  if (p->plan_only || p->last_instant || p->calls.empty()) {
+    *out = p->plan_stats;
+    out->struct_size = sizeof(kv_stats);
+    return KV_OK;
+  }
+  Call& c = p->calls.back();
+  if (c.end) {
+    HIPCHK(p, hipEventSynchronize(c.end));
+    float ms = 0.f;
+    HIPCHK(p, hipEventElapsedTime(&ms, c.start, c.end));
+    c.st.ms_total = ms;
+    float ks = 0.f;
+    for (auto& k : c.kev) {
+      HIPCHK(p, hipEventElapsedTime(&ms, k.first, k.second));
+      ks += ms;
+    }
+    c.st.ms_kernel = ks;
+  }
+  *out = c.st;
+  return KV_OK;
+}
+
+int64_t kv_slot_bytes(const kv_pool* p) { return p ? p->S : 0; }
+
+int64_t kv_last_plan(kv_pool* p, int32_t* phys, int64_t* slot, int64_t cap) {
+  if (!p) return KV_EINVAL;
+  std::lock_guard<std::mutex> g(p->mu);
+  const int64_t n = (int64_t)p->last_plan.size();
+  for (int64_t i = 0; i < n && i < cap; i++) {
+    if (phys) phys[i] = p->last_plan[(size_t)i].a;
+    if (slot) slot[i] = (int64_t)(uint32_t)p->last_plan[(size_t)i].b;
+  }
+  return n;
+}
+
+int kv_pool_tune(kv_pool* p, int32_t what, int64_t value) {
+  if (!p || value < 0) return KV_EINVAL;
+  std::lock_guard<std::mutex> g(p->mu);
+  switch (what) {
+    case KV_TUNE_MAX_WGS_DEVICE:
+      p->max_wgs_device = std::min<int64_t>(value, 1 << 30);
+      return KV_OK;
+    case KV_TUNE_MAX_WGS_LINK:
+      p->max_wgs_link = std::min<int64_t>(value, 1 << 30);
+      return KV_OK;
+    case KV_TUNE_KERNEL_VARIANT:
+      if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8) return KV_EINVAL;
+      p->variant = value;
+      return KV_OK;
+    case KV_TUNE_DMA_SLICE_BLOCKS:
+      p->dma_slice = value;
+      return KV_OK;
+    default:
+      return KV_EINVAL;
+  }
+}
+
+int kv_last_hip_error(const kv_pool* p) { return p ? p->last_hip : 0; }
+
+const char* kv_strerror(int code) {
+  switch (code) {
+    case KV_OK: return "ok";
+    case KV_EINVAL: return "invalid argument";
+    case KV_ERANGE: return "block id out of range";
+    case KV_EDUP: return "duplicate destination block";
+    case KV_ENOENT: return "unknown request";
+    case KV_EEXIST: return "request already swapped out or already known";
+    case KV_ENOSPC: return "staging arena full";
+    case KV_EHIP: return "HIP runtime error";
+    case KV_ESTATE: return "token count below the watermark";
+    default: return "unknown status";
+  }
+}
+
+// ---- measurement helpers: ceilings the swap is compared against ----
+
+// Contiguous device-to-device copy of `bytes` (multiple of 16 KiB) with the same lane shape as
+// the gather.  Runs `iters` times on `stream`; returns the mean milliseconds per copy, or < 0.
+double kv_bench_copy(void* dst_dev, const void* src_dev, int64_t bytes, int32_t grid, int32_t iters, void* stream) {
+  if (!dst_dev || !src_dev || bytes <= 0 || bytes % 16384 || grid <= 0 || iters <= 0) return -1.0;
+  if (!range_ok(dst_dev, bytes) || !range_ok(src_dev, bytes)) return -1.0;
+  hipStream_t st = (hipStream_t)stream;
+  hipEvent_t a, b;
+  if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return -2.0;
+  const int64_t pieces = bytes / 16384;
+  const int g = (int)std::min<int64_t>(pieces, grid);
+  hipLaunchKernelGGL((kv_copy_kernel<4>), dim3(g), dim3(256), 0, st, (const char*)src_dev, (char*)dst_dev, pieces);
+  (void)hipEventRecord(a, st);
+  for (int i = 0; i < iters; i++)
+    hipLaunchKernelGGL((kv_copy_kernel<4>), dim3(g), dim3(256), 0, st, (const char*)src_dev, (char*)dst_dev, pieces);
+  (void)hipEventRecord(b, st);
+  float ms = -1.f;
+  if (hipEventSynchronize(b) != hipSuccess || hipEventElapsedTime(&ms, a, b) != hipSuccess) ms = -3.f * iters;
+  (void)hipEventDestroy(a);
+  (void)hipEventDestroy(b);
+  return (double)ms / iters;
+}
+
+// One contiguous hipMemcpyAsync between pinned host and device memory, timed with events:
+// the host-link ceiling.  dir 0: device -> host, 1: host -> device.  Returns mean ms per copy.
+double kv_bench_link(void* host_pinned, void* dev, int64_t bytes, int32_t dir, int32_t iters, void* stream) {
+  if (!host_pinned || !dev || bytes <= 0 || iters <= 0 || (dir != 0 && dir != 1)) return -1.0;
+  if (!range_ok(dev, bytes) || !range_ok(host_pinned, bytes)) return -1.0;
+  hipStream_t st = (hipStream_t)stream;
+  hipEvent_t a, b;
+  if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return -2.0;
+  auto once = [&]() {
+    return dir == 0 ? hipMemcpyAsync(host_pinned, dev, (size_t)bytes, hipMemcpyDeviceToHost, st)
+                    : hipMemcpyAsync(dev, host_pinned, (size_t)bytes, hipMemcpyHostToDevice, st);
+  };
+  (void)once();
+  (void)hipEventRecord(a, st);
+  for (int i = 0; i < iters; i++) (void)once();
+  (void)hipEventRecord(b, st);
+  float ms = -1.f;
+  if (hipEventSynchronize(b) != hipSuccess || hipEventElapsedTime(&ms, a, b) != hipSuccess) ms = -3.f * iters;
+  (void)hipEventDestroy(a);
+  (void)hipEventDestroy(b);
+  return (double)ms / iters;
+}
+
+}  // extern "C"

@@ -40,6 +40,10 @@ class HostPool:
         self.staging = np.full(self.slots * geom.S + min(40, geom.S // 2), CANARY, dtype=np.uint8)
 
     def oracle(self, lib=None):
+        """The C oracle over these arrays; `lib` may name another build of it, or be a
+        factory (HostPool -> object with the Oracle methods) to put something else under the pins."""
+        if callable(lib):
+            return lib(self)
         from oracle.kv_oracle import Oracle
         g = self.geom
         return Oracle(g.L, g.H, g.D, g.B, g.e, g.N, self.pool, self.strides, self.staging,

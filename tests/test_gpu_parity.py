@@ -1,0 +1,214 @@
+"""GPU parity: the HIP library against the CPU oracle, byte for byte, through the C ABI.
+
+Integer/byte work: the bar is bit-exact (np.array_equal on raw bytes), no tolerance.
+Every case runs on all three transfer paths: zero-copy kernels into the pinned arena,
+bounce buffer + hipMemcpyAsync, and the on-device arena.
+"""
+import numpy as np
+import pytest
+
+import test_oracle_pins as T
+from adapters import GpuAdapter
+from hostpool import CANARY, HostPool
+from oracle import kv_oracle as ko
+from paper_2510_02758_amd import kvswap as kv
+from paper_2510_02758_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+PATHS = {"zerocopy": kv.KV_PATH_ZEROCOPY, "dma": kv.KV_PATH_DMA, "device": kv.KV_STAGING_DEVICE}
+
+
+def adapter(path, **kw):
+    return lambda hp: GpuAdapter(hp, PATHS[path], **kw)
+
+
+# ---- the oracle's own pins, with the GPU library underneath ---------------------
+@pytest.mark.parametrize("path", list(PATHS))
+@pytest.mark.parametrize("layout", T.LAYOUTS)
+@pytest.mark.parametrize("gname", list(T.GEOMS))
+def test_pins_closed_form(gpu, gname, layout, path):
+    T.pin_closed_form(gname, layout, lib=adapter(path))
+
+
+@pytest.mark.parametrize("path", list(PATHS))
+@pytest.mark.parametrize("gname", list(T.GEOMS))
+def test_pins_round_trip(gpu, gname, path):
+    T.pin_round_trip(gname, "padded", lib=adapter(path))
+
+
+@pytest.mark.parametrize("path", list(PATHS))
+@pytest.mark.parametrize("gname", list(T.GEOMS))
+def test_pins_delta(gpu, gname, path):
+    T.pin_delta_equals_full(gname, 2, lib=adapter(path))
+
+
+@pytest.mark.parametrize("path", list(PATHS))
+def test_pins_rest(gpu, path):
+    T.pin_memcpy_case("tiny", lib=adapter(path))
+    T.pin_errors(lib=adapter(path))
+    T.pin_move_blocks(lib=adapter(path))
+    T.pin_first_fit(lib=adapter(path))
+    T.pin_cycles(lib=adapter(path))
+
+
+# ---- oracle vs GPU, element by element ------------------------------------------
+def run_both(g, seed, layout, path, n_req, lo, hi, n_victims, tune=(), bounce_slots=3, slots=None):
+    """Same seeded inputs through the oracle (host arrays) and the library (device);
+    returns nothing, asserts equality of arena and pool after each phase."""
+    lens = W.request_lengths(seed, n_req, ("uniform", lo, hi))
+    off, ids, free = W.block_tables(seed, g.N, W.blocks_for(lens, g.B))
+    victims = np.sort(W.pick(seed, n_req, n_victims))
+    voff, vids = W.csr_take(off, ids, victims)
+    rid = (1000 + victims).astype(np.uint64)
+    vlen = lens[victims]
+    nslots = (len(vids) + 5) if slots is None else slots
+
+    a = HostPool(g, seed, layout, slots=nslots)
+    ora = a.oracle()
+    b = HostPool(g, seed, layout, slots=nslots)
+    gpu = GpuAdapter(b, PATHS[path], bounce_slots=bounce_slots, tune=tune)
+
+    assert ora.swap_out(rid, voff, vids, vlen) == ko.OK
+    assert gpu.swap_out(rid, voff, vids, vlen) == kv.KV_OK
+    assert np.array_equal(a.staging, b.staging), "arena differs after swap-out"
+    assert np.array_equal(a.pool, b.pool)
+    st = gpu.kp.stats()
+    assert st["blocks"] == len(vids) and st["bytes"] == len(vids) * g.S
+
+    # the allocator reuses the victims' blocks for something else
+    for hp in (a, b):
+        hp.pool[hp.data_index(vids).reshape(-1)] = 0x3C
+    assert len(free) >= len(vids), "test geometry too small for its requests"
+    new = free[: len(vids)]
+    assert ora.swap_in(rid, voff, new) == ko.OK
+    assert gpu.swap_in(rid, voff, new) == kv.KV_OK
+    assert np.array_equal(a.pool, b.pool), "pool differs after swap-in"
+    if g.scales:
+        assert np.array_equal(a.scale, b.scale), "scales differ after swap-in"
+    assert np.array_equal(a.staging, b.staging)
+    for r in rid:
+        assert gpu.query(r)[0] == kv.KV_ENOENT
+    gpu.close()
+
+
+@pytest.mark.parametrize("path", list(PATHS))
+def test_config1_tiny_fp16(gpu, path):
+    """BASELINE config 1: fp16, L=2, H=4, D=64, B=16, 1024 blocks; 8 requests of 16-256 tokens;
+    3 swapped out, then swapped into different free blocks."""
+    wl = W.config(1)
+    run_both(wl.geom, wl.seed, "layer", path, wl.n_requests, 16, 256, wl.n_preempt)
+
+
+@pytest.mark.parametrize("path", list(PATHS))
+@pytest.mark.parametrize("layout", ["layer", "padded"])
+def test_ragged_pieces_and_grid_stride(gpu, path, layout):
+    """chunk = 20 KiB + 48 B: one full 16 KiB piece and a ragged one whose last lane group is
+    partly idle; a 3-workgroup cap makes every workgroup loop over many jobs; the DMA path is
+    cut into slices of 2 blocks."""
+    g = W.Geometry(3, 1, 5132, 2, "bf16", 96)  # chunk = 2*1*5132*2 = 20528 bytes
+    assert g.chunk == 20528 and g.chunk % 16 == 0 and g.chunk % 16384 != 0
+    tune = ((kv.KV_TUNE_MAX_WGS_DEVICE, 3), (kv.KV_TUNE_MAX_WGS_LINK, 3), (kv.KV_TUNE_DMA_SLICE_BLOCKS, 2))
+    run_both(g, 0xA11CE, layout, path, 6, 2, 24, 4, tune=tune)
+
+
+@pytest.mark.parametrize("path", list(PATHS))
+@pytest.mark.parametrize("unroll", [1, 2, 4, 8])
+def test_every_piece_size(gpu, path, unroll):
+    g = W.Geometry(2, 2, 1160, 8, "bf16", 80)  # chunk = 37120 B = 2320 x 16: ragged for every piece size
+    assert g.chunk == 37120
+    tune = ((kv.KV_TUNE_KERNEL_VARIANT, unroll),)
+    run_both(g, 0xBEE + unroll, "layer", path, 5, 4, 40, 3, tune=tune)
+
+
+@pytest.mark.parametrize("path", list(PATHS))
+def test_fp8_with_scales(gpu, path):
+    """fp8 values and fp32 scales travel together (BASELINE config 5 shape, scaled down):
+    H=32, D=128, B=32 -> chunk 128 KiB, scale chunk 128 B."""
+    g = W.Geometry(4, 32, 128, 32, "fp8_e4m3", 128, scales=True)
+    run_both(g, 0x5EED0005, "layer", path, 6, 32, 256, 4)
+    g2 = W.Geometry(3, 6, 16, 4, "fp8_e4m3", 160, scales=True)  # 24-byte scale pieces, padded strides
+    run_both(g2, 0xF8, "padded", path, 7, 1, 40, 5)
+
+
+@pytest.mark.parametrize("path", list(PATHS))
+def test_small_chunks(gpu, path):
+    """Token-level pool (B=1) and a tensor-parallel shard with one KV head: chunks of 256 B / 4 KiB."""
+    run_both(W.Geometry(4, 1, 128, 1, "bf16", 512), 0x701, "layer", path, 12, 1, 40, 7)
+    run_both(W.Geometry(5, 1, 128, 16, "bf16", 256), 0x702, "layer", path, 10, 16, 300, 6)
+
+
+def test_back_to_back_without_sync(gpu):
+    """Stream ordering: swap-out then swap-in of the same requests with no kv_sync in between;
+    then a second swap-out that reuses the slots the first swap-in is still reading."""
+    g = W.Geometry(4, 8, 128, 16, "bf16", 600)
+    import torch
+    seed = 0x0DE2
+    lens = W.request_lengths(seed, 10, ("uniform", 100, 700))
+    off, ids, free = W.block_tables(seed, g.N, W.blocks_for(lens, g.B))
+    rid = np.arange(1, 11, dtype=np.uint64)
+    nslots = int(off[-1]) + 2
+    a = HostPool(g, seed, slots=nslots)
+    ora = a.oracle()
+    pool = torch.from_numpy(a.pool.copy()).cuda()
+    staging = torch.full((len(a.staging),), CANARY, dtype=torch.uint8).pin_memory()
+    kp = kv.KVPool(g, pool, staging, flags=kv.KV_PATH_ZEROCOPY)
+    new = free[: len(ids)]
+    # library: three calls in a row, no sync; the third reuses the arena slots of the first, so
+    # the evict stream has to wait for the swap-in that still reads them
+    assert kp.swap_out(rid, off, ids, lens) == kv.KV_OK
+    assert kp.swap_in(rid, off, new) == kv.KV_OK
+    rid2 = rid + 100
+    assert kp.swap_out(rid2[::-1], *W.csr_take(off, new, np.arange(10)[::-1]), lens[::-1]) == kv.KV_OK
+    assert kp.sync() == kv.KV_OK
+    # oracle: the same three calls
+    assert ora.swap_out(rid, off, ids, lens) == ko.OK
+    assert ora.swap_in(rid, off, new) == ko.OK
+    o2, i2 = W.csr_take(off, new, np.arange(10)[::-1])
+    assert ora.swap_out(rid2[::-1], o2, i2, lens[::-1]) == ko.OK
+    assert np.array_equal(pool.cpu().numpy(), a.pool)
+    assert np.array_equal(staging.numpy(), a.staging)
+    kp.close()
+
+
+def test_wait_event_orders_after_producer(gpu):
+    """The caller's compute stream fills the blocks; kv_swap_out must wait for its event."""
+    import torch
+    g = W.Geometry(2, 8, 128, 16, "bf16", 2048)
+    n = 1024
+    pool = torch.zeros(g.pool_bytes, dtype=torch.uint8, device="cuda")
+    staging = torch.zeros(n * g.S, dtype=torch.uint8).pin_memory()
+    kp = kv.KVPool(g, pool, staging)
+    big = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
+    compute = torch.cuda.Stream()
+    ev = torch.cuda.Event()
+    compute.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(compute):
+        for _ in range(20):
+            big.add_(1)  # keeps the stream busy so that a missing wait would be visible
+        pool.fill_(7)
+        ev.record(compute)
+    ids = np.arange(n, dtype=np.int32)
+    assert kp.swap_out([1], [0, n], ids, [n * g.B], wait_event=ev.cuda_event) == kv.KV_OK
+    assert kp.sync() == kv.KV_OK
+    assert int(staging.min()) == 7 and int(staging.max()) == 7
+    kp.close()
+
+
+def test_create_checks_memory_kinds(gpu):
+    import torch
+    g = W.Geometry(2, 4, 64, 16, "f16", 64)
+    pool = torch.zeros(g.pool_bytes, dtype=torch.uint8, device="cuda")
+    pinned = torch.zeros(8 * g.S, dtype=torch.uint8).pin_memory()
+    pageable = torch.zeros(8 * g.S, dtype=torch.uint8)
+    with pytest.raises(kv.KVSwapError):
+        kv.KVPool(g, pool, pageable)                       # arena must be pinned
+    with pytest.raises(kv.KVSwapError):
+        kv.KVPool(g, pinned, pinned)                       # pool must be device memory
+    with pytest.raises(kv.KVSwapError):
+        kv.KVPool(g, pool, pinned, flags=kv.KV_STAGING_DEVICE)  # device arena flag, host pointer
+    small = torch.zeros(g.pool_bytes // 2, dtype=torch.uint8, device="cuda")
+    big_geom = W.Geometry(2, 4, 64, 16, "f16", 1 << 20)     # strides run far past the allocation
+    with pytest.raises(kv.KVSwapError):
+        kv.KVPool(big_geom, small, pinned)
+    kv.KVPool(g, pool, pinned).close()

@@ -1,0 +1,197 @@
+"""CPU tests of the GPU library's host side: the shared object loads, exports what
+include/kvswap.h declares, and — under KV_PLAN_ONLY, where it never touches HIP —
+its request table, extent allocator, validation and descriptor lists satisfy the
+same pins as the oracle and agree with the oracle on random operation sequences.
+"""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import test_oracle_pins as T
+from adapters import PlanOnlyAdapter
+from hostpool import HostPool
+from oracle import kv_oracle as ko
+from paper_2510_02758_amd import kvswap as kv
+from paper_2510_02758_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "kvswap.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(kv_[a-z_]+)\s*\(", hdr))
+    assert {"kv_pool_create", "kv_swap_out", "kv_swap_out_delta", "kv_swap_in", "kv_sync"} <= declared
+    lib = ctypes.CDLL(kv.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(lib, name), "libkvswap.so does not export %s" % name
+    assert set(kv.EXPORTS) == declared
+
+
+def test_status_codes_match_header():
+    hdr = open(os.path.join(ROOT, "include", "kvswap.h")).read()
+    for name, val in re.findall(r"\b(KV_E[A-Z]+) = (-\d+)", hdr):
+        assert getattr(kv, name) == int(val)
+    # the oracle types the same numbers out on its own
+    assert (ko.EINVAL, ko.ERANGE, ko.EDUP, ko.ENOENT, ko.EEXIST, ko.ENOSPC, ko.ESTATE) == \
+        (kv.KV_EINVAL, kv.KV_ERANGE, kv.KV_EDUP, kv.KV_ENOENT, kv.KV_EEXIST, kv.KV_ENOSPC, kv.KV_ESTATE)
+    assert kv.kv_strerror(kv.KV_EDUP) == "duplicate destination block"
+
+
+def test_create_rejects_bad_configs():
+    g = W.Geometry(2, 4, 64, 16, "f16", 64)
+
+    def make(**kw):
+        cfg = kv.kv_pool_config()
+        cfg.num_layers, cfg.num_kv_heads, cfg.head_dim, cfg.block_size = g.L, g.H, g.D, g.B
+        cfg.dtype, cfg.num_blocks = 0, g.N
+        cfg.layer_stride, cfg.kv_stride, cfg.block_stride = g.strides
+        cfg.staging_bytes = 10 * g.S
+        cfg.flags = kv.KV_PLAN_ONLY
+        for k, v in kw.items():
+            setattr(cfg, k, v)
+        rc, h = kv.kv_pool_create(cfg)
+        if rc == kv.KV_OK:
+            kv.kv_pool_destroy(h)
+        return rc
+
+    assert make() == kv.KV_OK
+    assert make(num_layers=0) == kv.KV_EINVAL
+    assert make(dtype=7) == kv.KV_EINVAL
+    assert make(head_dim=3, block_size=1) == kv.KV_EINVAL  # chunk not a multiple of 16 bytes
+    assert make(block_stride=g.chunk + 8) == kv.KV_EINVAL
+    assert make(kv_stride=0) == kv.KV_EINVAL
+    assert make(flags=kv.KV_PLAN_ONLY | kv.KV_PATH_DMA | kv.KV_PATH_ZEROCOPY) == kv.KV_EINVAL
+    assert make(flags=kv.KV_PLAN_ONLY | kv.KV_PATH_DMA) == kv.KV_EINVAL  # DMA path without a bounce buffer
+    assert make(scale_layer_stride=2 * 64 * 16, scale_kv_stride=64 * 16, scale_block_stride=16) == kv.KV_OK
+    assert make(scale_layer_stride=2 * 64 * 16, scale_kv_stride=64 * 16, scale_block_stride=18) == kv.KV_EINVAL
+    # a real (non plan-only) pool needs memory
+    assert make(flags=0) == kv.KV_EINVAL
+
+
+# ---- the oracle's pins, run against planner + descriptor lists -----------------
+@pytest.mark.parametrize("layout", T.LAYOUTS)
+@pytest.mark.parametrize("gname", list(T.GEOMS))
+def test_pins_closed_form(gname, layout):
+    T.pin_closed_form(gname, layout, lib=PlanOnlyAdapter)
+
+
+@pytest.mark.parametrize("gname", list(T.GEOMS))
+def test_pins_round_trip(gname):
+    T.pin_round_trip(gname, "padded", lib=PlanOnlyAdapter)
+
+
+@pytest.mark.parametrize("gname", list(T.GEOMS))
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_pins_delta(gname, seed):
+    T.pin_delta_equals_full(gname, seed, lib=PlanOnlyAdapter)
+
+
+def test_pins_rest():
+    T.pin_brute_force(2, 2, lib=PlanOnlyAdapter, D=8)
+    T.pin_memcpy_case("tiny", lib=PlanOnlyAdapter)
+    T.pin_errors(lib=PlanOnlyAdapter)
+    T.pin_move_blocks(lib=PlanOnlyAdapter)
+    T.pin_first_fit(lib=PlanOnlyAdapter)
+    T.pin_cycles(lib=PlanOnlyAdapter)
+
+
+# ---- random operation sequences: library bookkeeping == oracle bookkeeping ------
+@pytest.mark.parametrize("seed", range(6))
+def test_random_sequences_agree_with_oracle(seed):
+    g = W.Geometry(2, 2, 8, 4, "bf16", 48, scales=(seed % 2 == 1))
+    a = HostPool(g, 77 + seed, slots=26)
+    b = HostPool(g, 77 + seed, slots=26)
+    ora, lib = a.oracle(), PlanOnlyAdapter(b)
+    rng = np.random.default_rng(seed)
+    ids = list(range(1, 9))
+    length = {r: 0 for r in ids}
+    table = {r: [] for r in ids}
+    free = list(rng.permutation(g.N))
+    resident = {r: True for r in ids}
+    codes = {}
+    for step in range(400):
+        op = rng.choice(["grow", "out", "delta", "delta_tail", "in", "in_keep", "reserve", "release", "bad"])
+        k = int(rng.integers(1, 4))
+        rs = [int(x) for x in rng.choice(ids, size=k, replace=False)]
+        if op == "grow":
+            for r in rs:
+                if resident[r]:
+                    length[r] += int(rng.integers(1, 3 * g.B))
+                    while len(table[r]) * g.B < length[r] and free:
+                        table[r].append(int(free.pop()))
+                    length[r] = min(length[r], len(table[r]) * g.B)
+            continue
+        off = np.zeros(len(rs) + 1, np.int32)
+        off[1:] = np.cumsum([len(table[r]) for r in rs])
+        flat = [x for r in rs for x in table[r]]
+        lens = [length[r] for r in rs]
+        if op == "out":
+            ra, rb = ora.swap_out(rs, off, flat, lens), lib.swap_out(rs, off, flat, lens)
+        elif op in ("delta", "delta_tail"):
+            bud = int(rng.integers(0, 5))
+            fl = ko.DELTA_INCLUDE_TAIL if op == "delta_tail" else 0
+            (ra, ma), (rb, mb) = ora.swap_out_delta(rs, off, flat, lens, bud, fl), \
+                lib.swap_out_delta(rs, off, flat, lens, bud, fl)
+            assert np.array_equal(ma, mb)
+        elif op in ("in", "in_keep"):
+            staged = [ora.query(r)[1]["staged"] if ora.query(r)[0] == 0 else 1 for r in rs]
+            need = sum(staged)
+            if need > len(free):
+                continue
+            dest = [int(free.pop()) for _ in range(need)]
+            off = np.zeros(len(rs) + 1, np.int32)
+            off[1:] = np.cumsum(staged)
+            fl = ko.KEEP_STAGING if op == "in_keep" else 0
+            ra, rb = ora.swap_in(rs, off, dest, fl), lib.swap_in(rs, off, dest, fl)
+            if ra == 0:
+                at = 0
+                for r, n in zip(rs, staged):
+                    free = table[r] + free
+                    table[r] = dest[at:at + n]
+                    at += n
+                    if not fl:
+                        pass
+            else:
+                free = dest + free
+        elif op == "reserve":
+            n = int(rng.integers(0, 6))
+            ra, rb = ora.reserve(rs[0], n), lib.reserve(rs[0], n)
+        elif op == "release":
+            ra, rb = ora.release(rs[0]), lib.release(rs[0])
+        else:  # a call with one bad block id somewhere
+            if not flat:
+                continue
+            flat = list(flat)
+            flat[int(rng.integers(len(flat)))] = g.N + 3
+            ra, rb = ora.swap_out(rs, off, flat, lens), lib.swap_out(rs, off, flat, lens)
+        assert ra == rb, (step, op, ra, rb)
+        codes[ra] = codes.get(ra, 0) + 1
+        for r in ids:
+            assert ora.query(r) == lib.query(r), (step, op, r)
+        assert np.array_equal(a.staging, b.staging), (step, op)
+        assert np.array_equal(a.pool, b.pool), (step, op)
+        if g.scales:
+            assert np.array_equal(a.scale, b.scale)
+    assert codes.get(0, 0) > 50 and len(codes) >= 4, codes  # successes and several error kinds were hit
+
+
+def test_plan_is_in_call_order():
+    g = W.Geometry(1, 1, 8, 2, "f16", 32)
+    kp = kv.KVPool(g, flags=kv.KV_PLAN_ONLY, staging_bytes=16 * g.S)
+    assert kp.swap_out([7, 3], [0, 2, 5], [9, 4, 1, 0, 30], [4, 5]) == kv.KV_OK
+    phys, slot = kp.last_plan()
+    assert phys.tolist() == [9, 4, 1, 0, 30] and slot.tolist() == [0, 1, 2, 3, 4]
+    st = kp.stats()
+    assert st["blocks"] == 5 and st["bytes"] == 5 * g.S and st["op"] == 1
+    rc, moved = kp.swap_out_delta([5], [0, 3], [11, 12, 13], [5], flags=kv.KV_DELTA_INCLUDE_TAIL)
+    assert rc == kv.KV_OK and moved.tolist() == [3]
+    phys, slot = kp.last_plan()
+    assert phys.tolist() == [11, 12, 13] and slot.tolist() == [5, 6, 7]
+    assert kp.swap_in([3], [0, 3], [20, 21, 22]) == kv.KV_OK
+    phys, slot = kp.last_plan()
+    assert phys.tolist() == [20, 21, 22] and slot.tolist() == [2, 3, 4]
+    kp.close()

@@ -237,15 +237,16 @@ def _pool_to_dict(hp):
         for c in range(2):
             for p in range(g.N):
                 for t in range(g.B):
-                    o = l * ls + c * ks + p * bs + t * g.e
-                    d[(l, c, p, t)] = bytes(hp.pool[o:o + g.e])
+                    tok = g.H * g.D * g.e
+                    o = l * ls + c * ks + p * bs + t * tok
+                    d[(l, c, p, t)] = bytes(hp.pool[o:o + tok])
     return d
 
 
 @pytest.mark.parametrize("L,B", [(1, 1), (2, 1), (1, 2), (2, 2)])
-def pin_brute_force(L, B, lib=None):
+def pin_brute_force(L, B, lib=None, D=1):
     N = 5
-    g = W.Geometry(L, 1, 1, B, "f16", N)  # H = D = 1: one element per token
+    g = W.Geometry(L, 1, D, B, "f16", N)  # H = D = 1: one element per token
     cases = 0
     # every way to give two requests disjoint ordered tables of sizes (2,1) and (1,2) out of
     # 5 blocks, every subset of them swapped out, every placement of the swap-in destinations
