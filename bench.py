@@ -1,0 +1,279 @@
+#!/usr/bin/env python3
+"""Benchmark of the paged KV-cache swap on one MI355X.
+
+Workload: the Llama-3-8B-shaped burst (bf16, 32 layers, 8 KV heads, head_dim 128,
+block_size 16, 40 000-block pool = 78 GiB; 64 requests of 512-4096 tokens on
+random block tables), synthetic and seeded.
+
+One step = one pass of the whole hot path over that burst:
+  1. kv_swap_out  of all 64 requests (plan, gather, device->host)      -> kv_sync
+  2. kv_swap_in   into fresh random blocks, staging kept (host->device, scatter) -> kv_sync
+  3. every request generates one more block of tokens; kv_swap_out_delta writes
+     through only what is new (its former tail block and the new block)  -> kv_sync
+  4. on-device leg: the same blocks are gathered into an HBM arena and scattered
+     back to their original ids (both ends in HBM)                       -> kv_sync
+  5. the requests are released, so the next step starts from the same state.
+`value` = host-link payload bytes of the step (legs 1-3) / wall time of the whole
+step.  Per-leg figures, the HBM roofline of the on-device kernels, the fraction of
+the measured host-link ceiling, isolated per-request preempt/resume latency and
+the CPU oracle's rate are reported in the same JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def pct(xs, q):
+    return float(np.percentile(np.asarray(xs, dtype=np.float64), q))
+
+
+def cpu_baseline(W, wl, lens, off, ids, n_sample):
+    """The oracle, as it stands, on the first n_sample requests of the burst: swap-out then
+    swap-in against a compact host mirror holding only the blocks involved."""
+    from oracle import kv_oracle as ko
+    g0 = wl.geom
+    rows = list(range(n_sample))
+    soff, sids = W.csr_take(off, ids, rows)
+    total = int(soff[-1])
+    g = W.Geometry(g0.L, g0.H, g0.D, g0.B, g0.dtype, 2 * total)
+    unit = W.fill_buffer_np(wl.seed, 1 << 24, g.dtype)
+    pool = np.resize(unit, g.pool_bytes)
+    staging = np.zeros(total * g.S, dtype=np.uint8)
+    ora = ko.Oracle(g.L, g.H, g.D, g.B, g.e, g.N, pool, g.strides, staging)
+    rid = np.arange(1, n_sample + 1, dtype=np.uint64)
+    src = np.arange(total, dtype=np.int32)          # compact ids, same order as the real tables
+    dst = np.arange(total, 2 * total, dtype=np.int32)
+    t0 = time.perf_counter()
+    assert ora.swap_out(rid, soff, src, lens[:n_sample]) == ko.OK
+    t1 = time.perf_counter()
+    assert ora.swap_in(rid, soff, dst) == ko.OK
+    t2 = time.perf_counter()
+    nbytes = total * g.S
+    return {
+        "value": round(2 * nbytes / (t2 - t0) / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+        "sample": "first %d of the 64 requests (%d blocks, %.2f GiB each way), swap-out then swap-in on a "
+                  "compact host mirror; %.1f s of CPU time" % (n_sample, total, nbytes / 2**30, t2 - t0),
+        "swap_out_gbps": round(nbytes / (t1 - t0) / 1e9, 3), "swap_in_gbps": round(nbytes / (t2 - t1) / 1e9, 3),
+        "ms_per_request": round((t2 - t0) * 1e3 / n_sample, 2),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=8)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--path", choices=["auto", "zerocopy", "dma"], default="auto")
+    ap.add_argument("--cpu-sample", type=int, default=16, help="requests the CPU oracle is timed on (0: skip)")
+    ap.add_argument("--blocks", type=int, default=0, help="override the pool size (debugging on small boxes)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is a one-GPU library (no sharding, no collectives); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2510_02758_amd import kvswap as kv
+    from paper_2510_02758_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    wl = W.config(2, num_blocks=args.blocks or None)
+    g = wl.geom
+    lens = W.request_lengths(wl.seed, wl.n_requests, wl.length_dist)
+    nb = W.blocks_for(lens, g.B)
+    off, ids, free = W.block_tables(wl.seed, g.N, nb)
+    n = wl.n_requests
+    total = int(off[-1])
+    rid = np.arange(1, n + 1, dtype=np.uint64)
+    new = free[:total].copy()                     # fresh blocks for the swap-in
+    extra = free[total:total + n].copy()          # one more block per request for the write-through leg
+    # tables after the requests grew by one block
+    off2 = off + np.arange(n + 1, dtype=np.int32)
+    ids2 = np.concatenate([np.append(new[off[i]:off[i + 1]], extra[i]) for i in range(n)]).astype(np.int32)
+    lens2 = ((nb + 1) * g.B).astype(np.int32)
+
+    # ---- memory: PyTorch only allocates ----
+    pool = torch.empty(g.pool_bytes, dtype=torch.uint8, device=dev)
+    W.fill_buffer_torch(wl.seed, pool, g.dtype)
+    staging = torch.empty((total + n) * g.S, dtype=torch.uint8, pin_memory=True)
+    staging.view(torch.int64)[::512] = 0          # touch every page before timing
+    dev_arena = torch.empty(total * g.S, dtype=torch.uint8, device=dev)
+    flags = {"auto": kv.KV_PATH_AUTO, "zerocopy": kv.KV_PATH_ZEROCOPY, "dma": kv.KV_PATH_DMA}[args.path]
+    bounce = torch.empty(2 << 30, dtype=torch.uint8, device=dev) if args.path == "dma" else None
+    evict, load = torch.cuda.Stream(), torch.cuda.Stream()
+    kp = kv.KVPool(g, pool, staging, bounce=bounce, flags=flags, evict_stream=evict, load_stream=load)
+    kd = kv.KVPool(g, pool, dev_arena, flags=kv.KV_STAGING_DEVICE, evict_stream=evict, load_stream=load)
+    torch.cuda.synchronize()
+
+    # ---- ceilings, measured in this run ----
+    one = 1 << 30
+    scratch = dev_arena[:4 * one] if dev_arena.numel() >= 8 * one else None
+    link_d2h = one / kv.kv_bench_link(staging.data_ptr(), dev_arena.data_ptr(), one, 0, 4, evict.cuda_stream) / 1e6
+    link_h2d = one / kv.kv_bench_link(staging.data_ptr(), dev_arena.data_ptr(), one, 1, 4, evict.cuda_stream) / 1e6
+    copy_gbs = None
+    if scratch is not None:
+        ms = kv.kv_bench_copy(dev_arena[4 * one:].data_ptr(), scratch.data_ptr(), 4 * one, 1 << 18, 5,
+                              evict.cuda_stream)
+        copy_gbs = 2 * 4 * one / ms / 1e6
+
+    def ok(rc, what):
+        if rc != kv.KV_OK:
+            raise kv.KVSwapError(rc, what)
+
+    acc = {k: [] for k in ("out", "in", "delta", "dev", "gather_k", "scatter_k", "out_k", "in_k", "plan_us")}
+    delta_blocks = [0]
+
+    def step(record):
+        t = [time.perf_counter()]
+        for i in range(n):
+            ok(kp.reserve(rid[i], int(nb[i]) + 1), "kv_req_reserve")
+        ok(kp.swap_out(rid, off, ids, lens), "kv_swap_out")
+        so = kp.stats() if record else None
+        ok(kp.sync(), "kv_sync")
+        t.append(time.perf_counter())
+        ok(kp.swap_in(rid, off, new, kv.KV_KEEP_STAGING), "kv_swap_in")
+        si = kp.stats() if record else None
+        ok(kp.sync(), "kv_sync")
+        t.append(time.perf_counter())
+        rc, moved = kp.swap_out_delta(rid, off2, ids2, lens2)
+        ok(rc, "kv_swap_out_delta")
+        ok(kp.sync(), "kv_sync")
+        t.append(time.perf_counter())
+        delta_blocks[0] = int(moved.sum())
+        ok(kd.swap_out(rid, off, new, lens), "kv_swap_out(device arena)")
+        go = kd.stats() if record else None
+        ok(kd.swap_in(rid, off, ids), "kv_swap_in(device arena)")
+        gi = kd.stats() if record else None
+        ok(kd.sync(), "kv_sync")
+        t.append(time.perf_counter())
+        for i in range(n):
+            ok(kp.release(rid[i]), "kv_req_release")
+        if record:
+            acc["out"].append(t[1] - t[0])
+            acc["in"].append(t[2] - t[1])
+            acc["delta"].append(t[3] - t[2])
+            acc["dev"].append(t[4] - t[3])
+            acc["out_k"].append(so["ms_kernel"] if so["path"] == kv.KV_PATH_ZEROCOPY else so["ms_total"])
+            acc["in_k"].append(si["ms_kernel"] if si["path"] == kv.KV_PATH_ZEROCOPY else si["ms_total"])
+            acc["gather_k"].append(go["ms_kernel"])
+            acc["scatter_k"].append(gi["ms_kernel"])
+            acc["plan_us"].append(so["plan_us"])
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    elapsed = t1 - t0
+    path_used = {kv.KV_PATH_DMA: "dma", kv.KV_PATH_ZEROCOPY: "zerocopy"}
+
+    # ---- check that nothing was skipped: the pool is back where it started ----
+    # (block new[j] holds what block ids[j] was filled with; untouched blocks hold their own fill)
+    rng = np.random.default_rng(1)
+    ls, ks, bs = g.strides
+    bad = 0
+    js = rng.choice(total, size=12, replace=False).tolist()
+    pairs = [(int(new[j]), int(ids[j])) for j in js] + [(int(ids[j]), int(ids[j])) for j in js[:4]]
+    pairs += [(int(p), int(p)) for p in rng.choice(free[total + n:], size=4)]
+    for holder, origin in pairs:
+        for l in (0, g.L // 2, g.L - 1):
+            for c in (0, 1):
+                want = W.fill_bytes_torch(wl.seed, l * ls + c * ks + origin * bs, g.chunk, g.dtype, dev)
+                o = l * ls + c * ks + holder * bs
+                bad += int((pool[o:o + g.chunk] != want).any())
+    if bad:
+        print("bench.py: pool content check FAILED on %d chunks" % bad, file=sys.stderr)
+        sys.exit(3)
+
+    # ---- isolated per-request preempt / resume latency (call -> kv_sync), outside the timed steps ----
+    pre, res = [], []
+    for i in range(n):
+        o1 = np.array([0, nb[i]], dtype=np.int32)
+        a = time.perf_counter()
+        ok(kp.swap_out(rid[i:i + 1], o1, ids[off[i]:off[i + 1]], lens[i:i + 1]), "kv_swap_out")
+        ok(kp.sync(), "kv_sync")
+        b = time.perf_counter()
+        ok(kp.swap_in(rid[i:i + 1], o1, ids[off[i]:off[i + 1]]), "kv_swap_in")
+        ok(kp.sync(), "kv_sync")
+        c = time.perf_counter()
+        pre.append((b - a) * 1e3)
+        res.append((c - b) * 1e3)
+    sstat = kp.stats()
+
+    P = total * g.S                              # payload of the burst, bytes
+    Pd = delta_blocks[0] * g.S
+    m = {k: float(np.mean(v)) for k, v in acc.items()}
+    d2h = P / m["out"] / 1e9
+    h2d = P / m["in"] / 1e9
+    link_payload = 2 * P + Pd
+    value = link_payload * args.steps / elapsed / 1e9
+    gather_ms, scatter_ms = m["gather_k"], m["scatter_k"]
+    scatter_gbs = 2 * P / scatter_ms / 1e6
+    gather_gbs = 2 * P / gather_ms / 1e6
+
+    out = {
+        "metric": "swap GB/s (D2H, H2D, on-device) + p50 preempt/resume latency per request",
+        "value": round(value, 2), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(elapsed * 1e3 / args.steps, 2),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {"workload": "configs[1]: Llama-3-8B-shaped KV bf16 L32 H8 D128 B16, %d-block pool, burst of %d "
+                               "requests 512-4096 tokens (%d blocks, %.2f GiB per direction), random block tables"
+                               % (g.N, n, total, P / 2**30),
+                   "path": path_used.get(sstat["path"], str(sstat["path"])),
+                   "value_def": "host-link payload (swap-out + swap-in + write-through delta) per step / step wall "
+                                "time, step = swap-out, swap-in, delta, on-device gather+scatter, release"},
+        "legs": {
+            "d2h_gbps": round(d2h, 2), "h2d_gbps": round(h2d, 2),
+            "d2h_frac_of_measured_link": round(d2h / link_d2h, 3), "h2d_frac_of_measured_link": round(h2d / link_h2d, 3),
+            "delta_blocks": delta_blocks[0], "delta_ms": round(m["delta"] * 1e3, 3),
+            "delta_gbps": round(Pd / m["delta"] / 1e9, 2),
+            "ondevice_payload_gbps": round(2 * P / m["dev"] / 1e9, 1),
+            "ondevice_gather_traffic_gbps": round(gather_gbs, 1), "ondevice_scatter_traffic_gbps": round(scatter_gbs, 1),
+            "plan_us_burst": round(m["plan_us"], 1),
+            "burst_preempt_ms_per_request": round(m["out"] * 1e3 / n, 3),
+            "burst_resume_ms_per_request": round(m["in"] * 1e3 / n, 3),
+        },
+        "latency": {"p50_preempt_ms": round(pct(pre, 50), 3), "p90_preempt_ms": round(pct(pre, 90), 3),
+                    "p50_resume_ms": round(pct(res, 50), 3), "p90_resume_ms": round(pct(res, 90), 3),
+                    "def": "isolated single-request call -> kv_sync, over the 64 requests (mean %.0f MiB each)"
+                           % (P / n / 2**20)},
+        "link": {"bound": "host-link", "measured_peak_d2h_gbps": round(link_d2h, 2),
+                 "measured_peak_h2d_gbps": round(link_h2d, 2),
+                 "kernel_out_ms": round(m["out_k"], 2), "kernel_in_ms": round(m["in_k"], 2),
+                 "how": "one 1 GiB contiguous pinned hipMemcpyAsync per direction, in this run"},
+        "roofline": {"bound": "hbm", "kernel": "kv_move_kernel<1,U,false> (scatter, both ends in HBM)",
+                     "achieved": round(scatter_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(scatter_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "launch_ms": round(scatter_ms, 3), "bytes_per_launch": 2 * P,
+                     "measured_copy_ceiling_gbps": None if copy_gbs is None else round(copy_gbs, 1)},
+        "roofline_gather": {"bound": "hbm", "kernel": "kv_move_kernel<0,U,false> (gather, both ends in HBM)",
+                            "achieved": round(gather_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                            "frac": round(gather_gbs / HBM_PEAK_GBS, 4), "launch_ms": round(gather_ms, 3),
+                            "bytes_per_launch": 2 * P},
+    }
+    kp.close()
+    kd.close()
+    del pool, dev_arena
+    if args.cpu_sample > 0:
+        out["cpu_baseline"] = cpu_baseline(W, wl, lens, off, ids, min(args.cpu_sample, n))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

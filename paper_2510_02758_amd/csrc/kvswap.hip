@@ -233,22 +233,30 @@ int ring_reserve(kv_pool* p, size_t n, uint64_t seq, size_t* at) {
   return KV_OK;
 }
 
-template <int MODE>
-void launch_move(int u, int grid, hipStream_t st, const MoveArgs& a) {
+template <int MODE, bool LINK>
+void launch_move_u(int u, int grid, hipStream_t st, const MoveArgs& a) {
   switch (u) {
     case 1:
-      hipLaunchKernelGGL((kv_move_kernel<MODE, 1>), dim3(grid), dim3(256), 0, st, a);
+      hipLaunchKernelGGL((kv_move_kernel<MODE, 1, LINK>), dim3(grid), dim3(256), 0, st, a);
       break;
     case 2:
-      hipLaunchKernelGGL((kv_move_kernel<MODE, 2>), dim3(grid), dim3(256), 0, st, a);
+      hipLaunchKernelGGL((kv_move_kernel<MODE, 2, LINK>), dim3(grid), dim3(256), 0, st, a);
       break;
     case 8:
-      hipLaunchKernelGGL((kv_move_kernel<MODE, 8>), dim3(grid), dim3(256), 0, st, a);
+      hipLaunchKernelGGL((kv_move_kernel<MODE, 8, LINK>), dim3(grid), dim3(256), 0, st, a);
       break;
     default:
-      hipLaunchKernelGGL((kv_move_kernel<MODE, 4>), dim3(grid), dim3(256), 0, st, a);
+      hipLaunchKernelGGL((kv_move_kernel<MODE, 4, LINK>), dim3(grid), dim3(256), 0, st, a);
       break;
   }
+}
+
+template <int MODE>
+void launch_move(int u, int grid, bool link, hipStream_t st, const MoveArgs& a) {
+  if (link)
+    launch_move_u<MODE, true>(u, grid, st, a);
+  else
+    launch_move_u<MODE, false>(u, grid, st, a);
 }
 
 int pick_unroll(const kv_pool* p) {
@@ -300,11 +308,11 @@ int enqueue_kernel(kv_pool* p, Call& call, int mode, const Desc* desc, size_t n,
   if ((rc = get_event(p, &k0)) || (rc = get_event(p, &k1))) return rc;
   HIPCHK(p, hipEventRecord(k0, st));
   if (mode == 0)
-    launch_move<0>(u, grid, st, a);
+    launch_move<0>(u, grid, link, st, a);
   else if (mode == 1)
-    launch_move<1>(u, grid, st, a);
+    launch_move<1>(u, grid, link, st, a);
   else
-    launch_move<2>(u, grid, st, a);
+    launch_move_u<2, false>(u, grid, st, a);
   HIPCHK(p, hipGetLastError());
   HIPCHK(p, hipEventRecord(k1, st));
   call.kev.push_back({k0, k1});
