@@ -259,8 +259,13 @@ void launch_move(int u, int grid, bool link, hipStream_t st, const MoveArgs& a) 
     launch_move_u<MODE, false>(u, grid, st, a);
 }
 
-int pick_unroll(const kv_pool* p) {
+// Loads in flight per lane.  Both ends in HBM: one 16-byte load per lane and one workgroup per
+// 4 KiB piece measured fastest on MI355X (the hardware dispatcher keeps every CU fed and the
+// job order stays the address order of the contiguous side).  Host link: fewer, fatter
+// workgroups, since the link and not the CUs is the limit.
+int pick_unroll(const kv_pool* p, bool link) {
   if (p->variant == 1 || p->variant == 2 || p->variant == 4 || p->variant == 8) return (int)p->variant;
+  if (!link) return 1;
   if (p->chunk >= 16384) return 4;
   if (p->chunk >= 8192) return 2;
   return 1;
@@ -277,7 +282,7 @@ int enqueue_kernel(kv_pool* p, Call& call, int mode, const Desc* desc, size_t n,
   std::memcpy(p->ring_host + at, desc, n * sizeof(Desc));
   HIPCHK(p, hipMemcpyAsync(p->ring_dev + at, p->ring_host + at, n * sizeof(Desc), hipMemcpyHostToDevice, st));
 
-  const int u = pick_unroll(p);
+  const int u = pick_unroll(p, link);
   const int64_t piece = 256 * 16 * (int64_t)u;
   MoveArgs a;
   a.pool = (char*)p->cfg.pool_dev;
@@ -300,8 +305,9 @@ int enqueue_kernel(kv_pool* p, Call& call, int mode, const Desc* desc, size_t n,
   a.n_data_jobs = (int64_t)n * a.jobs_per_block;
   a.n_jobs = a.n_data_jobs + (a.scale_words ? (int64_t)n : 0);
 
+  // default caps: host link 2 workgroups per CU (grid-stride); HBM to HBM one workgroup per job
   int64_t cap = link ? (p->max_wgs_link ? p->max_wgs_link : 2 * (int64_t)p->cu_count)
-                     : (p->max_wgs_device ? p->max_wgs_device : 8 * (int64_t)p->cu_count);
+                     : (p->max_wgs_device ? p->max_wgs_device : (int64_t)1 << 30);
   const int grid = (int)std::min<int64_t>(a.n_jobs, cap);
 
   hipEvent_t k0, k1;

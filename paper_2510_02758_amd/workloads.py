@@ -284,6 +284,15 @@ def fill_bytes_torch(seed, byte_offset, nbytes, dtype, device):
     return _fold_nan_torch(raw, dtype)
 
 
+def fill_words_torch(seed, word_index, dtype):
+    """Content of the 64-bit words `word_index` (int64 tensor, any shape) of a buffer filled
+    with `seed` -> uint8 tensor of shape word_index.shape + (8,), on the same device."""
+    raw = _mix_torch(seed, word_index.contiguous()).view(word_index.dtype)
+    import torch
+    out = raw.view(torch.uint8).view(*word_index.shape, 8)
+    return _fold_nan_torch(out, dtype)
+
+
 def fill_buffer_torch(seed, buf, dtype, piece=1 << 28):
     """Fill a uint8 tensor in place, `piece` bytes at a time."""
     n = buf.numel()
