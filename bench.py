@@ -32,6 +32,12 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
+# HBM bytes per on-device launch of the default workload, from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs of this script (summary and scale factors: profiles/kv_move_kernel_llama8b_burst64.md):
+# (18 602 598 + 18 601 986) KiB for the scatter, against 2 x 18 601 984 KiB algorithmic.
+MEASURED_TRAFFIC = {("configs[1]", 9083, "scatter"): (18602598 + 18601986) * 1024,
+                    ("configs[1]", 9083, "gather"): (18602592 + 18601984) * 1024}
+
 
 def pct(xs, q):
     return float(np.percentile(np.asarray(xs, dtype=np.float64), q))
@@ -259,12 +265,15 @@ def main():
                  "how": "one 1 GiB contiguous pinned hipMemcpyAsync per direction, in this run"},
         "roofline": {"bound": "hbm", "kernel": "kv_move_kernel<1,U,false> (scatter, both ends in HBM)",
                      "achieved": round(scatter_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(scatter_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(scatter_gbs / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_TRAFFIC.get(("configs[1]", total, "scatter")) if not args.blocks else None,
                      "launch_ms": round(scatter_ms, 3), "bytes_per_launch": 2 * P,
                      "measured_copy_ceiling_gbps": None if copy_gbs is None else round(copy_gbs, 1)},
         "roofline_gather": {"bound": "hbm", "kernel": "kv_move_kernel<0,U,false> (gather, both ends in HBM)",
                             "achieved": round(gather_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                            "frac": round(gather_gbs / HBM_PEAK_GBS, 4), "launch_ms": round(gather_ms, 3),
+                            "frac": round(gather_gbs / HBM_PEAK_GBS, 4),
+                            "traffic": MEASURED_TRAFFIC.get(("configs[1]", total, "gather")) if not args.blocks else None,
+                            "launch_ms": round(gather_ms, 3),
                             "bytes_per_launch": 2 * P},
     }
     kp.close()
