@@ -305,8 +305,9 @@ int enqueue_kernel(kv_pool* p, Call& call, int mode, const Desc* desc, size_t n,
   a.n_data_jobs = (int64_t)n * a.jobs_per_block;
   a.n_jobs = a.n_data_jobs + (a.scale_words ? (int64_t)n : 0);
 
-  // default caps: host link 2 workgroups per CU (grid-stride); HBM to HBM one workgroup per job
-  int64_t cap = link ? (p->max_wgs_link ? p->max_wgs_link : 2 * (int64_t)p->cu_count)
+  // default caps: host link 64 workgroups, grid-stride (the link saturates there and three
+  // quarters of the CUs stay free for the model); HBM to HBM one workgroup per job
+  int64_t cap = link ? (p->max_wgs_link ? p->max_wgs_link : 64)
                      : (p->max_wgs_device ? p->max_wgs_device : (int64_t)1 << 30);
   const int grid = (int)std::min<int64_t>(a.n_jobs, cap);
 
