@@ -116,9 +116,11 @@ def main():
     staging.view(torch.int64)[::512] = 0          # touch every page before timing
     dev_arena = torch.empty(total * g.S, dtype=torch.uint8, device=dev)
     flags = {"auto": kv.KV_PATH_AUTO, "zerocopy": kv.KV_PATH_ZEROCOPY, "dma": kv.KV_PATH_DMA}[args.path]
-    bounce = torch.empty(2 << 30, dtype=torch.uint8, device=dev) if args.path == "dma" else None
+    bounce = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
+    kdma = kv.KVPool(g, pool, staging, bounce=bounce, flags=kv.KV_PATH_DMA)   # the other path, reported beside
     evict, load = torch.cuda.Stream(), torch.cuda.Stream()
-    kp = kv.KVPool(g, pool, staging, bounce=bounce, flags=flags, evict_stream=evict, load_stream=load)
+    kp = kv.KVPool(g, pool, staging, bounce=bounce if args.path == "dma" else None, flags=flags,
+                   evict_stream=evict, load_stream=load)
     kd = kv.KVPool(g, pool, dev_arena, flags=kv.KV_STAGING_DEVICE, evict_stream=evict, load_stream=load)
     torch.cuda.synchronize()
 
@@ -220,6 +222,18 @@ def main():
         res.append((c - b) * 1e3)
     sstat = kp.stats()
 
+    # ---- the copy-engine path on the same burst, for comparison (outside the timed steps) ----
+    dma = {}
+    for rep in range(2):
+        a = time.perf_counter()
+        ok(kdma.swap_out(rid, off, ids, lens), "kv_swap_out(dma)")
+        ok(kdma.sync(), "kv_sync")
+        b = time.perf_counter()
+        ok(kdma.swap_in(rid, off, ids), "kv_swap_in(dma)")
+        ok(kdma.sync(), "kv_sync")
+        c = time.perf_counter()
+        dma = {"d2h_gbps": round(total * g.S / (b - a) / 1e9, 2), "h2d_gbps": round(total * g.S / (c - b) / 1e9, 2)}
+
     P = total * g.S                              # payload of the burst, bytes
     Pd = delta_blocks[0] * g.S
     m = {k: float(np.mean(v)) for k, v in acc.items()}
@@ -254,6 +268,7 @@ def main():
             "plan_us_burst": round(m["plan_us"], 1),
             "burst_preempt_ms_per_request": round(m["out"] * 1e3 / n, 3),
             "burst_resume_ms_per_request": round(m["in"] * 1e3 / n, 3),
+            "other_path_dma": dma,
         },
         "latency": {"p50_preempt_ms": round(pct(pre, 50), 3), "p90_preempt_ms": round(pct(pre, 90), 3),
                     "p50_resume_ms": round(pct(res, 50), 3), "p90_resume_ms": round(pct(res, 90), 3),
@@ -278,6 +293,7 @@ def main():
     }
     kp.close()
     kd.close()
+    kdma.close()
     del pool, dev_arena
     if args.cpu_sample > 0:
         out["cpu_baseline"] = cpu_baseline(W, wl, lens, off, ids, min(args.cpu_sample, n))

@@ -90,6 +90,12 @@ def _u64(a):
     return np.ascontiguousarray(np.asarray(a, dtype=np.uint64))
 
 
+def _csr_ok(n, offsets, block_ids, *per_request):
+    if len(offsets) != n + 1 or any(len(a) != n for a in per_request):
+        return False
+    return n == 0 or int(offsets.max()) <= len(block_ids)
+
+
 class Oracle:
     """Host-memory KV pool + staging arena driven by the C oracle.
 
@@ -130,17 +136,23 @@ class Oracle:
 
     def swap_out(self, req_ids, offsets, block_ids, num_tokens):
         r, o, b, t = _u64(req_ids), _i32(offsets), _i32(block_ids), _i32(num_tokens)
+        if not _csr_ok(len(r), o, b, t):
+            return EINVAL
         return self._lib.ora_swap_out(self._h, len(r), _ptr(r), _ptr(o), _ptr(b), _ptr(t))
 
     def swap_out_delta(self, req_ids, offsets, block_ids, num_tokens, budget=0, flags=0):
         r, o, b, t = _u64(req_ids), _i32(offsets), _i32(block_ids), _i32(num_tokens)
         moved = np.zeros(len(r), dtype=np.int32)
+        if not _csr_ok(len(r), o, b, t):
+            return EINVAL, moved
         rc = self._lib.ora_swap_out_delta(self._h, len(r), _ptr(r), _ptr(o), _ptr(b), _ptr(t),
                                         int(budget), int(flags), _ptr(moved))
         return rc, moved
 
     def swap_in(self, req_ids, offsets, new_block_ids, flags=0):
         r, o, b = _u64(req_ids), _i32(offsets), _i32(new_block_ids)
+        if not _csr_ok(len(r), o, b):
+            return EINVAL
         return self._lib.ora_swap_in(self._h, len(r), _ptr(r), _ptr(o), _ptr(b), int(flags))
 
     def move_blocks(self, src_ids, dst_ids):

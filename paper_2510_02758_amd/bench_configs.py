@@ -1,0 +1,390 @@
+#!/usr/bin/env python3
+"""Per-configuration figures beside bench.py (which times the Llama-3-8B burst).
+
+    python -m paper_2510_02758_amd.bench_configs --config 1|3|4|5
+
+Each run prints one JSON line.  Synthetic seeded inputs (workloads.py); the same
+library entry points as everywhere else; the CPU oracle is timed next to it on a
+bounded sample, single-threaded, and (for context) once more with the sample's
+requests spread over all host cores, one oracle instance per thread.
+
+  1  tiny fp16 pool: per-call latency floor (3 requests out, then in).
+  3  write-through: priming delta, 64 decode steps with one delta per step over 256
+     requests, then 32 requests preempted after write-through (tail flush only)
+     against the same 32 preempted cold (full swap-out), and resumed.
+  4  Llama-3-70B shape, 200 GB pool, fragmented tables, waves through a 40 GiB arena.
+  5  fp8 + fp32 scales: swap-in alone and while a read-modify-write kernel streams
+     through HBM on another stream.
+"""
+import argparse
+import json
+import os
+import sys
+import threading
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def pct(xs, q):
+    return round(float(np.percentile(np.asarray(xs, dtype=np.float64), q)), 3)
+
+
+def oracle_rates(W, g0, lens, nblocks, n_sample, seed):
+    """Oracle swap-out + swap-in of n_sample requests on a compact mirror: 1 thread, then the
+    same requests spread over all cores (one independent oracle instance per thread)."""
+    from oracle import kv_oracle as ko
+    nb = np.asarray(nblocks[:n_sample], dtype=np.int64)
+    total = int(nb.sum())
+    g = W.Geometry(g0.L, g0.H, g0.D, g0.B, g0.dtype, 2 * total, scales=g0.scales)
+    unit = W.fill_buffer_np(seed, 1 << 24, "raw")
+    pool = np.resize(unit, g.pool_bytes)
+    scale = np.resize(unit, g.scale_bytes) if g.scales else None
+    off = np.zeros(n_sample + 1, np.int64)
+    off[1:] = np.cumsum(nb)
+
+    def run(rows, staging):
+        ora = ko.Oracle(g.L, g.H, g.D, g.B, g.e, g.N, pool, g.strides, staging, scale=scale,
+                        scale_strides=g.scale_strides if g.scales else None)
+        o = np.zeros(len(rows) + 1, np.int32)
+        o[1:] = np.cumsum(nb[rows])
+        src = np.concatenate([np.arange(off[r], off[r + 1]) for r in rows]).astype(np.int32)
+        rid = np.asarray(rows, dtype=np.uint64) + 1
+        assert ora.swap_out(rid, o, src, np.asarray(lens)[rows]) == ko.OK
+        assert ora.swap_in(rid, o, src + total) == ko.OK
+
+    staging = np.zeros(total * g.S, np.uint8)
+    t0 = time.perf_counter()
+    run(list(range(n_sample)), staging)
+    t1 = time.perf_counter() - t0
+    cores = len(os.sched_getaffinity(0))
+    nthr = max(1, min(cores, n_sample))
+    parts = [list(range(i, n_sample, nthr)) for i in range(nthr)]
+    stagings = [np.zeros(int(nb[p].sum()) * g.S, np.uint8) for p in parts]
+    threads = [threading.Thread(target=run, args=(p, s)) for p, s in zip(parts, stagings)]
+    t0 = time.perf_counter()
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    tn = time.perf_counter() - t0
+    nbytes = 2 * total * g.S
+    return {"kind": "oracle", "sample": "%d requests, %d blocks, %.2f GiB each way" % (n_sample, total, total * g.S / 2**30),
+            "value": round(nbytes / t1 / 1e9, 3), "unit": "GB/s", "cores": 1,
+            "ms_per_request": round(t1 * 1e3 / n_sample, 2),
+            "all_cores_value": round(nbytes / tn / 1e9, 3), "all_cores": nthr}
+
+
+def ceilings(kv, torch, staging, dev):
+    """Host-link ceiling: one contiguous pinned copy of up to 1 GiB per direction."""
+    one = min(1 << 30, staging.numel())
+    dev_buf = torch.empty(one, dtype=torch.uint8, device=dev)
+    d2h = one / kv.kv_bench_link(staging.data_ptr(), dev_buf.data_ptr(), one, 0, 4) / 1e6
+    h2d = one / kv.kv_bench_link(staging.data_ptr(), dev_buf.data_ptr(), one, 1, 4) / 1e6
+    return round(d2h, 2), round(h2d, 2)
+
+
+def ok(kv, rc, what):
+    if rc != kv.KV_OK:
+        raise kv.KVSwapError(rc, what)
+
+
+def config1(kv, W, torch, dev, args):
+    wl = W.config(1)
+    g = wl.geom
+    lens = W.request_lengths(wl.seed, wl.n_requests, wl.length_dist)
+    off, ids, free = W.block_tables(wl.seed, g.N, W.blocks_for(lens, g.B))
+    victims = np.sort(W.pick(wl.seed, wl.n_requests, wl.n_preempt))
+    voff, vids = W.csr_take(off, ids, victims)
+    rid = (1 + victims).astype(np.uint64)
+    new = free[:len(vids)]
+    pool = torch.from_numpy(W.fill_buffer_np(wl.seed, g.pool_bytes, g.dtype)).to(dev)
+    staging = torch.zeros(64 * g.S, dtype=torch.uint8).pin_memory()
+    kp = kv.KVPool(g, pool, staging)
+    outs, ins, calls = [], [], []
+    for it in range(200):
+        a = time.perf_counter()
+        ok(kv, kp.swap_out(rid, voff, vids, lens[victims]), "kv_swap_out")
+        a1 = time.perf_counter()
+        ok(kv, kp.sync(), "kv_sync")
+        b = time.perf_counter()
+        ok(kv, kp.swap_in(rid, voff, new), "kv_swap_in")
+        ok(kv, kp.sync(), "kv_sync")
+        c = time.perf_counter()
+        if it >= 20:
+            outs.append((b - a) * 1e6)
+            ins.append((c - b) * 1e6)
+            calls.append((a1 - a) * 1e6)
+    nbytes = len(vids) * g.S
+    return {"config": 1, "workload": "tiny fp16 L2 H4 D64 B16, 1024 blocks, 3 of 8 requests (%d blocks, %d KiB)"
+            % (len(vids), nbytes >> 10),
+            "preempt_call_to_sync_us": {"p50": pct(outs, 50), "p99": pct(outs, 99)},
+            "resume_call_to_sync_us": {"p50": pct(ins, 50), "p99": pct(ins, 99)},
+            "host_call_us_p50": pct(calls, 50),
+            "cpu_baseline": oracle_rates(W, g, lens[victims], W.blocks_for(lens[victims], g.B), len(victims), wl.seed)}
+
+
+def config3(kv, W, torch, dev, args):
+    wl = W.config(3)
+    g = wl.geom
+    n, steps = wl.n_requests, 64
+    lens = W.request_lengths(wl.seed, n, wl.length_dist).astype(np.int64)
+    final_nb = W.blocks_for(lens + steps, g.B)
+    off, ids, free = W.block_tables(wl.seed, g.N, final_nb)
+    rid = np.arange(1, n + 1, dtype=np.uint64)
+    total = int(off[-1])
+    pool = torch.empty(g.pool_bytes, dtype=torch.uint8, device=dev)
+    W.fill_buffer_torch(wl.seed, pool, g.dtype)
+    staging = torch.empty(total * g.S, dtype=torch.uint8, pin_memory=True)
+    staging.view(torch.int64)[::512] = 0
+    kp = kv.KVPool(g, pool, staging)
+    link = ceilings(kv, torch, staging, dev)
+    for i in range(n):
+        ok(kv, kp.reserve(rid[i], int(final_nb[i])), "kv_req_reserve")
+
+    def tables(cur, rows=None):
+        rows = range(n) if rows is None else rows
+        nb = W.blocks_for(cur, g.B)
+        o = np.zeros(len(rows) + 1, np.int32)
+        o[1:] = np.cumsum([nb[i] for i in rows])
+        flat = np.concatenate([ids[off[i]:off[i] + nb[i]] for i in rows])
+        return o, flat
+
+    cur = lens.copy()
+    o, flat = tables(cur)
+    t0 = time.perf_counter()
+    rc, moved = kp.swap_out_delta(rid, o, flat, cur)
+    ok(kv, rc, "kv_swap_out_delta")
+    ok(kv, kp.sync(), "kv_sync")
+    prime_s = time.perf_counter() - t0
+    prime_blocks = int(moved.sum())
+    step_us, step_blocks, call_us = [], [], []
+    for s in range(steps):
+        cur += 1
+        o, flat = tables(cur)                      # the serving loop owns its tables; not timed
+        a = time.perf_counter()
+        rc, moved = kp.swap_out_delta(rid, o, flat, cur)
+        a1 = time.perf_counter()
+        ok(kv, rc, "kv_swap_out_delta")
+        ok(kv, kp.sync(), "kv_sync")
+        b = time.perf_counter()
+        step_us.append((b - a) * 1e6)
+        call_us.append((a1 - a) * 1e6)
+        step_blocks.append(int(moved.sum()))
+    victims = np.sort(W.pick(wl.seed, n, wl.n_preempt))
+    vo, vflat = tables(cur, list(victims))
+    # (a) preempt after write-through: only the tail is left
+    a = time.perf_counter()
+    rc, moved = kp.swap_out_delta(rid[victims], vo, vflat, cur[victims], flags=kv.KV_DELTA_INCLUDE_TAIL)
+    ok(kv, rc, "kv_swap_out_delta(tail)")
+    ok(kv, kp.sync(), "kv_sync")
+    warm_ms = (time.perf_counter() - a) * 1e3
+    warm_blocks = int(moved.sum())
+    new = free[:len(vflat)]
+    a = time.perf_counter()
+    ok(kv, kp.swap_in(rid[victims], vo, new), "kv_swap_in")
+    ok(kv, kp.sync(), "kv_sync")
+    resume_ms = (time.perf_counter() - a) * 1e3
+    # (b) the same 32 requests preempted cold: nothing was written through
+    cold_rid = rid[victims] + 100000
+    _, nflat = np.zeros(0), new
+    a = time.perf_counter()
+    ok(kv, kp.swap_out(cold_rid, vo, nflat, cur[victims]), "kv_swap_out")
+    ok(kv, kp.sync(), "kv_sync")
+    cold_ms = (time.perf_counter() - a) * 1e3
+    vbytes = len(vflat) * g.S
+    mean_blocks = float(np.mean(step_blocks))
+    res = {"config": 3, "workload": "8B shape, 256 requests log-normal (median 1k), 64 decode steps, then 32 preempted + resumed",
+           "measured_link_gbps": {"d2h": link[0], "h2d": link[1]},
+           "priming_delta": {"blocks": prime_blocks, "gib": round(prime_blocks * g.S / 2**30, 2),
+                             "gbps": round(prime_blocks * g.S / prime_s / 1e9, 2)},
+           "delta_step": {"requests": n, "blocks_mean": round(mean_blocks, 2), "mib_mean": round(mean_blocks * g.S / 2**20, 1),
+                          "call_to_sync_us_p50": pct(step_us, 50), "call_to_sync_us_p99": pct(step_us, 99),
+                          "host_call_us_p50": pct(call_us, 50),
+                          "gbps_mean": round(sum(step_blocks) * g.S / (sum(step_us) * 1e-6) / 1e9, 2)},
+           "preempt_32_after_write_through": {"blocks": warm_blocks, "ms": round(warm_ms, 3),
+                                              "ms_per_request": round(warm_ms / len(victims), 4)},
+           "preempt_32_cold": {"blocks": len(vflat), "ms": round(cold_ms, 3),
+                               "ms_per_request": round(cold_ms / len(victims), 3),
+                               "gbps": round(vbytes / cold_ms / 1e6, 2)},
+           "resume_32": {"blocks": len(vflat), "ms": round(resume_ms, 3), "ms_per_request": round(resume_ms / len(victims), 3),
+                         "gbps": round(vbytes / resume_ms / 1e6, 2)}}
+    kp.close()
+    del pool, staging
+    res["cpu_baseline"] = oracle_rates(W, g, cur[victims][:12], W.blocks_for(cur[victims], g.B)[:12], 12, wl.seed)
+    return res
+
+
+def config4(kv, W, torch, dev, args):
+    wl = W.config(4)
+    g = wl.geom
+    lens = W.request_lengths(wl.seed, wl.n_requests, wl.length_dist)
+    nb = W.blocks_for(lens, g.B)
+    pool = torch.empty(g.pool_bytes, dtype=torch.uint8, device=dev)
+    W.fill_buffer_torch(wl.seed, pool, g.dtype)
+    arena_slots = (40 << 30) // g.S      # a wave's blocks and their destinations must both fit the free half
+    staging = torch.empty(arena_slots * g.S, dtype=torch.uint8, pin_memory=True)
+    staging.view(torch.int64)[::512] = 0
+    kp = kv.KVPool(g, pool, staging)
+    link = ceilings(kv, torch, staging, dev)
+    done, waves = 0, []
+    pre, res = [], []
+    while done < wl.n_requests and len(waves) < args.max_waves:
+        k = done
+        while k < wl.n_requests and int(nb[done:k + 1].sum()) <= arena_slots:
+            k += 1
+        rows = np.arange(done, k)
+        off, ids, free = W.fragmented_tables(wl.seed + len(waves), g.N, nb[rows], 0.5)
+        rid = (rows + 1).astype(np.uint64)
+        new = free[:len(ids)]
+        assert len(new) == len(ids), "the free half cannot hold this wave twice"
+        a = time.perf_counter()
+        ok(kv, kp.swap_out(rid, off, ids, lens[rows]), "kv_swap_out")
+        ok(kv, kp.sync(), "kv_sync")
+        b = time.perf_counter()
+        ok(kv, kp.swap_in(rid, off, new), "kv_swap_in")
+        ok(kv, kp.sync(), "kv_sync")
+        c = time.perf_counter()
+        nbytes = len(ids) * g.S
+        waves.append({"requests": len(rows), "gib": round(nbytes / 2**30, 2), "d2h_gbps": round(nbytes / (b - a) / 1e9, 2),
+                      "h2d_gbps": round(nbytes / (c - b) / 1e9, 2)})
+        if len(waves) == 1:      # isolated per-request latency on the first wave's requests
+            for i in range(len(rows)):
+                o1 = np.array([0, nb[rows[i]]], np.int32)
+                blk = new[off[i]:off[i + 1]]
+                a = time.perf_counter()
+                ok(kv, kp.swap_out(rid[i:i + 1], o1, blk, lens[rows[i]:rows[i] + 1]), "kv_swap_out")
+                ok(kv, kp.sync(), "kv_sync")
+                b = time.perf_counter()
+                ok(kv, kp.swap_in(rid[i:i + 1], o1, blk), "kv_swap_in")
+                ok(kv, kp.sync(), "kv_sync")
+                pre.append((b - a) * 1e3)
+                res.append((time.perf_counter() - b) * 1e3)
+        done = k
+    tot = sum(w["gib"] for w in waves)
+    out = {"config": 4, "workload": "70B shape L80 H8 D128 B16, 38146-block (200 GB) pool, 50% fragmented tables, 40 GiB arena",
+           "measured_link_gbps": {"d2h": link[0], "h2d": link[1]},
+           "waves_run": len(waves), "requests_run": done, "gib_each_way": round(tot, 1), "waves": waves,
+           "d2h_gbps_mean": round(float(np.mean([w["d2h_gbps"] for w in waves])), 2),
+           "h2d_gbps_mean": round(float(np.mean([w["h2d_gbps"] for w in waves])), 2),
+           "p50_preempt_ms": pct(pre, 50), "p50_resume_ms": pct(res, 50),
+           "mean_request_gib": round(float(np.mean(nb[:done])) * g.S / 2**30, 2)}
+    # on-device: one wave's blocks through an HBM arena
+    kp.close()
+    del staging
+    rows = np.arange(0, 16)
+    off, ids, free = W.fragmented_tables(wl.seed, g.N, nb[rows], 0.5)
+    arena = torch.empty(len(ids) * g.S, dtype=torch.uint8, device=dev)
+    kd = kv.KVPool(g, pool, arena, flags=kv.KV_STAGING_DEVICE)
+    rid = (rows + 1).astype(np.uint64)
+    gk, sk = [], []
+    for it in range(4):
+        ok(kv, kd.swap_out(rid, off, ids, lens[rows]), "kv_swap_out")
+        so = kd.stats()
+        ok(kv, kd.swap_in(rid, off, free[:len(ids)]), "kv_swap_in")
+        si = kd.stats()
+        ok(kv, kd.sync(), "kv_sync")
+        if it:
+            gk.append(2 * so["bytes"] / so["ms_kernel"] / 1e6)
+            sk.append(2 * si["bytes"] / si["ms_kernel"] / 1e6)
+    out["ondevice_traffic_gbps"] = {"gather": round(float(np.mean(gk)), 1), "scatter": round(float(np.mean(sk)), 1),
+                                    "frac_of_8TBps": [round(float(np.mean(gk)) / 8000, 3), round(float(np.mean(sk)) / 8000, 3)]}
+    kd.close()
+    del pool, arena
+    out["cpu_baseline"] = oracle_rates(W, g, lens, nb, 3, wl.seed)
+    return out
+
+
+def config5(kv, W, torch, dev, args):
+    wl = W.config(5)
+    g = wl.geom
+    lens = W.request_lengths(wl.seed, wl.n_requests, wl.length_dist)
+    nb = W.blocks_for(lens, g.B)
+    pool = torch.empty(g.pool_bytes, dtype=torch.uint8, device=dev)
+    scale = torch.empty(g.scale_bytes, dtype=torch.uint8, device=dev)
+    W.fill_buffer_torch(wl.seed, pool, g.dtype)
+    W.fill_buffer_torch(wl.seed ^ 0x5CA1E, scale, "raw")
+    arena_slots = (32 << 30) // g.S
+    k = 0
+    while int(nb[:k + 1].sum()) <= arena_slots:
+        k += 1
+    rows = np.arange(k)
+    off, ids, free = W.block_tables(wl.seed, g.N, nb[rows])
+    total = int(off[-1])
+    new = free[:total]
+    rid = (rows + 1).astype(np.uint64)
+    staging = torch.empty(total * g.S, dtype=torch.uint8, pin_memory=True)
+    staging.view(torch.int64)[::512] = 0
+    kp = kv.KVPool(g, pool, staging, scale=scale)
+    link = ceilings(kv, torch, staging, dev)
+    noise = torch.empty(16 << 30, dtype=torch.uint8, device=dev).view(torch.int32)
+    side = torch.cuda.Stream()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    nbytes = total * g.S
+
+    def stream_kernel(iters):
+        with torch.cuda.stream(side):
+            e0.record(side)
+            for _ in range(iters):
+                noise.add_(1)          # read-modify-write over 16 GiB: 32 GiB of HBM traffic per pass
+            e1.record(side)
+
+    def swap_in_once():
+        a = time.perf_counter()
+        ok(kv, kp.swap_in(rid, off, new, kv.KV_KEEP_STAGING), "kv_swap_in")
+        ok(kv, kp.sync(), "kv_sync")
+        return time.perf_counter() - a
+
+    ok(kv, kp.swap_out(rid, off, ids, lens[rows]), "kv_swap_out")
+    ok(kv, kp.sync(), "kv_sync")
+    t_out = kp.stats()["ms_total"]
+    swap_in_once()
+    alone = [swap_in_once() for _ in range(3)]
+    torch.cuda.synchronize()
+    stream_kernel(4)
+    torch.cuda.synchronize()
+    stream_kernel(40)
+    torch.cuda.synchronize()
+    stream_alone = 40 * 2 * noise.numel() * 4 / e0.elapsed_time(e1) / 1e6
+    iters = 200
+    stream_kernel(iters)
+    cont = [swap_in_once() for _ in range(3)]
+    still_running = not e1.query()
+    torch.cuda.synchronize()
+    stream_cont = iters * 2 * noise.numel() * 4 / e0.elapsed_time(e1) / 1e6
+    out = {"config": 5, "workload": "fp8 e4m3 + fp32 scales, L32 H32 D128 B32 (8 MiB + 8 KiB per block), %d-block pool; first wave: "
+                                    "%d requests, %d blocks, %.1f GiB" % (g.N, k, total, nbytes / 2**30),
+           "measured_link_gbps": {"d2h": link[0], "h2d": link[1]},
+           "swap_out_gbps": round(nbytes / t_out / 1e6, 2),
+           "swap_in_gbps_alone": round(nbytes / float(np.mean(alone)) / 1e9, 2),
+           "swap_in_gbps_contended": round(nbytes / float(np.mean(cont)) / 1e9, 2),
+           "stream_kernel_traffic_gbps_alone": round(stream_alone, 1),
+           "stream_kernel_traffic_gbps_while_swapping": round(stream_cont, 1),
+           "stream_kernel_outlasted_the_swaps": bool(still_running),
+           "note": "the contended streaming figure averages over the whole 200-pass run, of which the three swap-ins cover a part"}
+    kp.close()
+    del pool, staging, noise
+    out["cpu_baseline"] = oracle_rates(W, g, lens, nb, 4, wl.seed)
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--config", type=int, required=True, choices=[1, 3, 4, 5])
+    ap.add_argument("--max-waves", type=int, default=4)
+    args = ap.parse_args()
+    import torch
+    from paper_2510_02758_amd import kvswap as kv
+    from paper_2510_02758_amd import workloads as W
+    assert torch.cuda.is_available(), "needs a GPU"
+    dev = torch.device("cuda:0")
+    fn = {1: config1, 3: config3, 4: config4, 5: config5}[args.config]
+    print(json.dumps(fn(kv, W, torch, dev, args)))
+
+
+if __name__ == "__main__":
+    main()

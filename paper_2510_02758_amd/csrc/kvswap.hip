@@ -328,16 +328,27 @@ int enqueue_kernel(kv_pool* p, Call& call, int mode, const Desc* desc, size_t n,
   return KV_OK;
 }
 
-bool use_dma(const kv_pool* p) {
+// Path choice.  Alone, the zero-copy kernels are the fastest way over the link in both directions
+// and the only one that needs no bounce traffic.  Next to a kernel that saturates HBM and the CUs
+// they lose up to a fifth of their rate and make that kernel stall, while gather + copy engine
+// keeps its rate and leaves the other kernel alone.  So KV_PATH_AUTO uses the copy engines when
+// the caller supplied a bounce buffer (a serving loop that overlaps swaps with compute) and the
+// transfer is large enough for the extra launches not to matter, and zero-copy otherwise.
+constexpr int64_t kAutoDmaMinBytes = 32ll << 20;
+
+bool use_dma(const kv_pool* p, size_t blocks) {
   if (p->dev_staging) return false;
-  return (p->cfg.flags & KV_PATH_DMA) != 0;
+  if (p->cfg.flags & KV_PATH_DMA) return true;
+  if (p->cfg.flags & KV_PATH_ZEROCOPY) return false;
+  const int64_t half_slots = p->cfg.bounce_dev ? (p->cfg.bounce_bytes / 2) / p->S : 0;
+  return half_slots >= 1 && (int64_t)blocks * p->S >= kAutoDmaMinBytes;
 }
 
 // Move the planned blocks between pool and arena.  out = true: pool -> arena.
 int enqueue_transfer(kv_pool* p, Call& call, const std::vector<Desc>& desc, bool out) {
   char* arena = (char*)p->cfg.staging_host;
   const size_t n = desc.size();
-  if (!use_dma(p)) {
+  if (!use_dma(p, n)) {
     call.st.path = KV_PATH_ZEROCOPY;
     return enqueue_kernel(p, call, out ? 0 : 1, desc.data(), n, p->arena_dev, !p->dev_staging);
   }

@@ -97,6 +97,13 @@ def _u64a(a):
     return np.ascontiguousarray(np.asarray(a, dtype=np.uint64))
 
 
+def _csr_ok(n, offsets, block_ids, *per_request):
+    """The C side trusts the array lengths the CSR implies: check them here, where they are known."""
+    if len(offsets) != n + 1 or any(len(a) != n for a in per_request):
+        return False
+    return n == 0 or int(offsets.max()) <= len(block_ids)
+
+
 def kv_strerror(code):
     return _lib.kv_strerror(int(code)).decode()
 
@@ -115,6 +122,8 @@ def kv_pool_destroy(h):
 
 def kv_swap_out(h, req_ids, offsets, block_ids, num_tokens, wait_event=None):
     r, o, b, t = _u64a(req_ids), _i32a(offsets), _i32a(block_ids), _i32a(num_tokens)
+    if not _csr_ok(len(r), o, b, t):
+        return KV_EINVAL
     return _lib.kv_swap_out(h, len(r), _p(r), _p(o), _p(b), _p(t), wait_event)
 
 
@@ -122,6 +131,8 @@ def kv_swap_out_delta(h, req_ids, offsets, block_ids, num_tokens, block_budget=0
     """-> (rc, blocks_moved int32[n])"""
     r, o, b, t = _u64a(req_ids), _i32a(offsets), _i32a(block_ids), _i32a(num_tokens)
     moved = np.zeros(len(r), dtype=np.int32)
+    if not _csr_ok(len(r), o, b, t):
+        return KV_EINVAL, moved
     rc = _lib.kv_swap_out_delta(h, len(r), _p(r), _p(o), _p(b), _p(t), int(block_budget), int(flags),
                                 _p(moved), wait_event)
     return rc, moved
@@ -129,6 +140,8 @@ def kv_swap_out_delta(h, req_ids, offsets, block_ids, num_tokens, block_budget=0
 
 def kv_swap_in(h, req_ids, offsets, new_block_ids, flags=0, wait_event=None):
     r, o, b = _u64a(req_ids), _i32a(offsets), _i32a(new_block_ids)
+    if not _csr_ok(len(r), o, b):
+        return KV_EINVAL
     return _lib.kv_swap_in(h, len(r), _p(r), _p(o), _p(b), int(flags), wait_event)
 
 

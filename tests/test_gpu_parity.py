@@ -195,6 +195,44 @@ def test_wait_event_orders_after_producer(gpu):
     kp.close()
 
 
+def test_auto_path_choice(gpu):
+    """KV_PATH_AUTO: zero-copy without a bounce buffer; with one, transfers of 32 MiB and more go
+    through the copy engines.  Either way the bytes are the oracle's."""
+    import torch
+    g = W.Geometry(8, 8, 128, 16, "bf16", 400)             # block = 512 KiB
+    seed = 0xA070
+    a = HostPool(g, seed, slots=200)
+    ora = a.oracle()
+    pool = torch.from_numpy(a.pool.copy()).cuda()
+    staging = torch.full((len(a.staging),), CANARY, dtype=torch.uint8).pin_memory()
+    bounce = torch.zeros(2 * 40 * g.S, dtype=torch.uint8, device="cuda")
+    kp = kv.KVPool(g, pool, staging, bounce=bounce)         # flags = KV_PATH_AUTO
+    rng = np.random.default_rng(3)
+    perm = rng.permutation(g.N).astype(np.int32)
+    small, big = perm[:8], perm[8:8 + 100]                  # 4 MiB and 50 MiB
+    assert kp.swap_out([1], [0, 8], small, [8 * g.B]) == kv.KV_OK
+    assert kp.stats()["path"] == kv.KV_PATH_ZEROCOPY
+    assert kp.swap_out([2], [0, 100], big, [100 * g.B]) == kv.KV_OK
+    st = kp.stats()
+    assert st["path"] == kv.KV_PATH_DMA and st["copies"] == 3 and st["launches"] == 3   # slices of 40 blocks
+    assert kp.swap_in([2], [0, 100], perm[200:300]) == kv.KV_OK
+    assert kp.stats()["path"] == kv.KV_PATH_DMA
+    assert kp.swap_in([1], [0, 8], perm[300:308]) == kv.KV_OK
+    assert kp.stats()["path"] == kv.KV_PATH_ZEROCOPY
+    assert kp.sync() == kv.KV_OK
+    assert ora.swap_out([1], [0, 8], small, [8 * g.B]) == ko.OK
+    assert ora.swap_out([2], [0, 100], big, [100 * g.B]) == ko.OK
+    assert ora.swap_in([2], [0, 100], perm[200:300]) == ko.OK
+    assert ora.swap_in([1], [0, 8], perm[300:308]) == ko.OK
+    assert np.array_equal(pool.cpu().numpy(), a.pool)
+    assert np.array_equal(staging.numpy(), a.staging)
+    kp.close()
+    kp2 = kv.KVPool(g, pool, staging)                       # no bounce buffer: always zero-copy
+    assert kp2.swap_out([2], [0, 100], big, [100 * g.B]) == kv.KV_OK
+    assert kp2.stats()["path"] == kv.KV_PATH_ZEROCOPY
+    kp2.close()
+
+
 def test_create_checks_memory_kinds(gpu):
     import torch
     g = W.Geometry(2, 4, 64, 16, "f16", 64)
