@@ -220,6 +220,28 @@ int64_t kv_slot_bytes(const kv_pool* p);
  * produced.  Meant for host-logic tests under KV_PLAN_ONLY. */
 int64_t kv_last_plan(kv_pool* p, int32_t* phys, int64_t* slot, int64_t cap);
 
+/* I/O telemetry for a scheduler (Section 4.3: the memory manager exposes queue lengths and
+ * transfer rates so that t_IO = evict queueing + evict + load queueing + load can be estimated;
+ * Section 5.2: writes are sized to fit the next compute interval).  Index 0 = evict stream
+ * (swap-out, delta), 1 = load stream (swap-in). */
+typedef struct {
+  uint32_t struct_size;
+  int32_t inflight_calls[2]; /* calls enqueued and not yet finished */
+  int64_t inflight_bytes[2]; /* their payload */
+  int64_t total_calls[2];    /* finished calls accounted so far */
+  int64_t total_bytes[2];
+  double ewma_gbps[2];       /* payload rate of finished calls of 4 MiB and more (0: none yet) */
+  double ewma_small_us[2];   /* stream time of finished calls below 4 MiB: the fixed cost (0: none yet) */
+} kv_io_stats;
+int kv_io_stats_get(kv_pool* p, kv_io_stats* out);
+
+/* Blocks that a transfer enqueued now on stream `dir` (0 evict, 1 load) can move so that it
+ * finishes within interval_us: floor((interval_us - fixed - inflight_bytes/rate) * rate / S),
+ * never negative, with rate = ewma_gbps (32 GB/s until measured) and fixed = ewma_small_us
+ * (50 us until measured).  Feed it to kv_swap_out_delta as block_budget; a result of 0 means
+ * "nothing fits": do not pass it on, since a budget of 0 means unlimited there. */
+int64_t kv_budget_blocks(kv_pool* p, int32_t dir, double interval_us);
+
 /* Launch-shape knobs: value 0 restores the default. */
 enum {
   KV_TUNE_MAX_WGS_DEVICE = 1, /* workgroup cap when both ends are in HBM */

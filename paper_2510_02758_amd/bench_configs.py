@@ -15,6 +15,8 @@ requests spread over all host cores, one oracle instance per thread.
   4  Llama-3-70B shape, 200 GB pool, fragmented tables, waves through a 40 GiB arena.
   5  fp8 + fp32 scales: swap-in alone and while a read-modify-write kernel streams
      through HBM on another stream.
+  6  load-evict overlap (paper Section 5.3) on the 8B shape: 32 requests evicted while 32
+     others are loaded, serial (sync in between) against both streams at once.
 """
 import argparse
 import json
@@ -372,9 +374,59 @@ def config5(kv, W, torch, dev, args):
     return out
 
 
+def config6(kv, W, torch, dev, args):
+    wl = W.config(2)
+    g = wl.geom
+    lens = W.request_lengths(wl.seed, wl.n_requests, wl.length_dist)
+    nb = W.blocks_for(lens, g.B)
+    off, ids, free = W.block_tables(wl.seed, g.N, nb)
+    A, B = np.arange(0, 32), np.arange(32, 64)
+    oa, ia = W.csr_take(off, ids, A)
+    ob, ib = W.csr_take(off, ids, B)
+    rid = np.arange(1, 65, dtype=np.uint64)
+    pool = torch.empty(g.pool_bytes, dtype=torch.uint8, device=dev)
+    staging = torch.empty(int(off[-1]) * g.S, dtype=torch.uint8, pin_memory=True)
+    staging.view(torch.int64)[::512] = 0
+    bounce = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
+    link = ceilings(kv, torch, staging, dev)
+    bytes_a, bytes_b = len(ia) * g.S, len(ib) * g.S
+    res = {"config": 6, "workload": "8B shape: evict 32 requests (%.1f GiB) while loading 32 others (%.1f GiB)"
+           % (bytes_a / 2**30, bytes_b / 2**30), "measured_link_gbps": {"d2h": link[0], "h2d": link[1]}}
+    for name, flags, bb in (("zerocopy", kv.KV_PATH_ZEROCOPY, None), ("dma", kv.KV_PATH_DMA, bounce)):
+        kp = kv.KVPool(g, pool, staging, bounce=bb, flags=flags)
+        serial, both = [], []
+        for it in range(3):
+            # state: A resident, B swapped out
+            ok(kv, kp.swap_out(rid[B], ob, ib, lens[B]), "kv_swap_out")
+            ok(kv, kp.sync(), "kv_sync")
+            a = time.perf_counter()
+            ok(kv, kp.swap_out(rid[A], oa, ia, lens[A]), "kv_swap_out")
+            ok(kv, kp.sync(), "kv_sync")
+            ok(kv, kp.swap_in(rid[B], ob, ib), "kv_swap_in")
+            ok(kv, kp.sync(), "kv_sync")
+            serial.append(time.perf_counter() - a)
+            ok(kv, kp.swap_in(rid[A], oa, ia), "kv_swap_in")
+            ok(kv, kp.swap_out(rid[B], ob, ib, lens[B]), "kv_swap_out")
+            ok(kv, kp.sync(), "kv_sync")
+            a = time.perf_counter()
+            ok(kv, kp.swap_out(rid[A], oa, ia, lens[A]), "kv_swap_out")     # evict stream
+            ok(kv, kp.swap_in(rid[B], ob, ib), "kv_swap_in")                # load stream, no sync in between
+            ok(kv, kp.sync(), "kv_sync")
+            both.append(time.perf_counter() - a)
+            ok(kv, kp.swap_in(rid[A], oa, ia), "kv_swap_in")
+            ok(kv, kp.sync(), "kv_sync")
+        ts, tb = float(np.median(serial)), float(np.median(both))
+        res[name] = {"serial_ms": round(ts * 1e3, 1), "overlapped_ms": round(tb * 1e3, 1),
+                     "serial_aggregate_gbps": round((bytes_a + bytes_b) / ts / 1e9, 2),
+                     "overlapped_aggregate_gbps": round((bytes_a + bytes_b) / tb / 1e9, 2),
+                     "speedup": round(ts / tb, 3)}
+        kp.close()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--config", type=int, required=True, choices=[1, 3, 4, 5])
+    ap.add_argument("--config", type=int, required=True, choices=[1, 3, 4, 5, 6])
     ap.add_argument("--max-waves", type=int, default=4)
     args = ap.parse_args()
     import torch
@@ -382,7 +434,7 @@ def main():
     from paper_2510_02758_amd import workloads as W
     assert torch.cuda.is_available(), "needs a GPU"
     dev = torch.device("cuda:0")
-    fn = {1: config1, 3: config3, 4: config4, 5: config5}[args.config]
+    fn = {1: config1, 3: config3, 4: config4, 5: config5, 6: config6}[args.config]
     print(json.dumps(fn(kv, W, torch, dev, args)))
 
 

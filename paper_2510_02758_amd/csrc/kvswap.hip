@@ -37,6 +37,7 @@ struct Call {
   hipEvent_t start = nullptr, end = nullptr;
   std::vector<std::pair<hipEvent_t, hipEvent_t>> kev;
   kv_stats st{};
+  bool accounted = false;  // already folded into the telemetry
 };
 
 struct RingSeg {
@@ -96,6 +97,10 @@ struct kv_pool {
   kv_stats plan_stats{};  // figures of a call that enqueued nothing
   bool last_instant = false;
   int last_hip = 0;
+
+  // telemetry, updated when finished calls are retired
+  int64_t tot_calls[2] = {0, 0}, tot_bytes[2] = {0, 0};
+  double ewma_gbps[2] = {0, 0}, ewma_small_us[2] = {0, 0};
 
   int64_t max_wgs_device = 0, max_wgs_link = 0, variant = 0, dma_slice = 0;
   int cu_count = 256;
@@ -173,6 +178,30 @@ bool seq_done(kv_pool* p, uint64_t seq) {
   return false;
 }
 
+constexpr int64_t kSmallCallBytes = 4ll << 20;
+constexpr double kEwmaWeight = 0.25;
+
+// A finished call leaves the queue: fold its stream time into the running estimates.
+void account(kv_pool* p, Call& c) {
+  if (c.accounted || !c.start || !c.end || c.st.op == 4) return;
+  c.accounted = true;
+  float ms = 0.f;
+  if (hipEventElapsedTime(&ms, c.start, c.end) != hipSuccess || ms <= 0.f) {
+    (void)hipGetLastError();
+    return;
+  }
+  const int s = c.stream;
+  p->tot_calls[s]++;
+  p->tot_bytes[s] += c.st.bytes;
+  if (c.st.bytes >= kSmallCallBytes) {
+    const double gbps = (double)c.st.bytes / ((double)ms * 1e6);
+    p->ewma_gbps[s] = p->ewma_gbps[s] > 0 ? (1 - kEwmaWeight) * p->ewma_gbps[s] + kEwmaWeight * gbps : gbps;
+  } else if (c.st.bytes > 0) {
+    const double us = (double)ms * 1e3;
+    p->ewma_small_us[s] = p->ewma_small_us[s] > 0 ? (1 - kEwmaWeight) * p->ewma_small_us[s] + kEwmaWeight * us : us;
+  }
+}
+
 // Drop finished calls from the front, always keeping the newest for the statistics.
 void retire(kv_pool* p) {
   while (p->calls.size() > 1) {
@@ -181,6 +210,7 @@ void retire(kv_pool* p) {
       (void)hipGetLastError();
       break;
     }
+    account(p, c);
     recycle(p, c);
     p->calls.pop_front();
   }
@@ -777,6 +807,50 @@ int kv_last_stats(kv_pool* p, kv_stats* out) {
 }
 
 int64_t kv_slot_bytes(const kv_pool* p) { return p ? p->S : 0; }
+
+static void io_snapshot(kv_pool* p, kv_io_stats* o) {
+  std::memset(o, 0, sizeof(*o));
+  o->struct_size = sizeof(kv_io_stats);
+  if (!p->plan_only) {
+    retire(p);
+    for (auto& c : p->calls) {
+      if (!c.end || c.st.op == 4) continue;
+      if (hipEventQuery(c.end) == hipSuccess) {
+        account(p, c);  // the newest call stays in the queue for kv_last_stats even when finished
+        continue;
+      }
+      (void)hipGetLastError();
+      o->inflight_calls[c.stream]++;
+      o->inflight_bytes[c.stream] += c.st.bytes;
+    }
+  }
+  for (int s = 0; s < 2; s++) {
+    o->total_calls[s] = p->tot_calls[s];
+    o->total_bytes[s] = p->tot_bytes[s];
+    o->ewma_gbps[s] = p->ewma_gbps[s];
+    o->ewma_small_us[s] = p->ewma_small_us[s];
+  }
+}
+
+int kv_io_stats_get(kv_pool* p, kv_io_stats* out) {
+  if (!p || !out) return KV_EINVAL;
+  std::lock_guard<std::mutex> g(p->mu);
+  io_snapshot(p, out);
+  return KV_OK;
+}
+
+int64_t kv_budget_blocks(kv_pool* p, int32_t dir, double interval_us) {
+  if (!p || (dir != 0 && dir != 1) || !(interval_us >= 0)) return KV_EINVAL;
+  std::lock_guard<std::mutex> g(p->mu);
+  kv_io_stats io;
+  io_snapshot(p, &io);
+  const double rate = io.ewma_gbps[dir] > 0 ? io.ewma_gbps[dir] : 32.0;           // GB/s = bytes per ns
+  const double fixed = io.ewma_small_us[dir] > 0 ? io.ewma_small_us[dir] : 50.0;  // us
+  const double queued_us = (double)io.inflight_bytes[dir] / (rate * 1e3);
+  const double left_us = interval_us - fixed - queued_us;
+  if (left_us <= 0) return 0;
+  return (int64_t)(left_us * rate * 1e3 / (double)p->S);
+}
 
 int64_t kv_last_plan(kv_pool* p, int32_t* phys, int64_t* slot, int64_t cap) {
   if (!p) return KV_EINVAL;

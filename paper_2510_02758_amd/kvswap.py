@@ -26,7 +26,8 @@ KV_F16, KV_BF16, KV_FP8_E4M3 = 0, 1, 2
 
 EXPORTS = ["kv_pool_create", "kv_pool_destroy", "kv_swap_out", "kv_swap_out_delta", "kv_swap_in", "kv_sync",
            "kv_move_blocks", "kv_req_reserve", "kv_req_release", "kv_req_query", "kv_last_stats",
-           "kv_slot_bytes", "kv_last_plan", "kv_pool_tune", "kv_last_hip_error", "kv_strerror"]
+           "kv_slot_bytes", "kv_last_plan", "kv_pool_tune", "kv_last_hip_error", "kv_strerror",
+           "kv_io_stats_get", "kv_budget_blocks"]
 
 
 class kv_pool_config(C.Structure):
@@ -54,6 +55,15 @@ class kv_stats(C.Structure):
         return {k: getattr(self, k) for k, _ in self._fields_ if k != "struct_size"}
 
 
+class kv_io_stats(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("inflight_calls", C.c_int32 * 2), ("inflight_bytes", C.c_int64 * 2),
+                ("total_calls", C.c_int64 * 2), ("total_bytes", C.c_int64 * 2), ("ewma_gbps", C.c_double * 2),
+                ("ewma_small_us", C.c_double * 2)]
+
+    def as_dict(self):
+        return {k: list(getattr(self, k)) for k, _ in self._fields_ if k != "struct_size"}
+
+
 if not os.path.exists(LIB_PATH):
     raise ImportError("libkvswap.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
                       "(hipcc --offload-arch=gfx950) first; there is no fallback path")
@@ -77,6 +87,8 @@ _sig = {
     "kv_pool_tune": (C.c_int, [_vp, _i32, _i64]),
     "kv_last_hip_error": (C.c_int, [_vp]),
     "kv_strerror": (C.c_char_p, [C.c_int]),
+    "kv_io_stats_get": (C.c_int, [_vp, C.POINTER(kv_io_stats)]),
+    "kv_budget_blocks": (_i64, [_vp, _i32, C.c_double]),
     "kv_bench_copy": (C.c_double, [_vp, _vp, _i64, _i32, _i32, _vp]),
     "kv_bench_link": (C.c_double, [_vp, _vp, _i64, _i32, _i32, _vp]),
 }
@@ -192,6 +204,17 @@ def kv_last_plan(h):
     return phys, slot
 
 
+def kv_io_stats_get(h):
+    """-> (rc, dict of 2-element lists: index 0 evict stream, 1 load stream)"""
+    st = kv_io_stats()
+    rc = _lib.kv_io_stats_get(h, C.byref(st))
+    return rc, st.as_dict()
+
+
+def kv_budget_blocks(h, direction, interval_us):
+    return _lib.kv_budget_blocks(h, int(direction), float(interval_us))
+
+
 def kv_pool_tune(h, what, value):
     return _lib.kv_pool_tune(h, int(what), int(value))
 
@@ -295,6 +318,15 @@ class KVPool:
 
     def last_plan(self):
         return kv_last_plan(self.h)
+
+    def io_stats(self):
+        rc, st = kv_io_stats_get(self.h)
+        if rc:
+            raise KVSwapError(rc, "kv_io_stats_get")
+        return st
+
+    def budget_blocks(self, direction, interval_us):
+        return kv_budget_blocks(self.h, direction, interval_us)
 
     def tune(self, what, value):
         return kv_pool_tune(self.h, what, value)

@@ -233,6 +233,54 @@ def test_auto_path_choice(gpu):
     kp2.close()
 
 
+def test_telemetry_and_time_budget(gpu):
+    """Section 5.2: a write sized from the measured rate finishes inside the interval it was sized
+    for.  The budget must equal the documented formula applied to the reported telemetry."""
+    import time
+    import torch
+    g = W.config(2).geom
+    pool = torch.zeros(600 * g.block_bytes, dtype=torch.uint8, device="cuda")
+    g = W.Geometry(g.L, g.H, g.D, g.B, g.dtype, 600)
+    staging = torch.zeros(520 * g.S, dtype=torch.uint8).pin_memory()
+    kp = kv.KVPool(g, pool, staging)
+    ids = np.arange(600, dtype=np.int32)
+    # measure: a few large and a few small calls in each direction
+    for it in range(4):
+        assert kp.swap_out([1], [0, 128], ids[:128], [128 * g.B]) == kv.KV_OK
+        assert kp.swap_in([1], [0, 128], ids[128:256]) == kv.KV_OK
+        assert kp.swap_out([2], [0, 1], ids[300:301], [g.B]) == kv.KV_OK
+        assert kp.swap_in([2], [0, 1], ids[301:302]) == kv.KV_OK
+    assert kp.sync() == kv.KV_OK
+    io = kp.io_stats()
+    assert io["inflight_calls"] == [0, 0] and io["inflight_bytes"] == [0, 0]
+    assert io["total_calls"] == [8, 8] and io["total_bytes"] == [4 * 129 * g.S] * 2
+    for d in (0, 1):
+        assert 20.0 < io["ewma_gbps"][d] < 70.0, io        # a PCIe Gen5 x16 link
+        assert 5.0 < io["ewma_small_us"][d] < 2000.0, io
+    interval = 3000.0                                       # a 3 ms decode step
+    want = int((interval - io["ewma_small_us"][0]) * io["ewma_gbps"][0] * 1e3 / g.S)
+    budget = kp.budget_blocks(0, interval)
+    assert budget == want and 40 < budget < 120
+    # a delta with that budget over a long request moves exactly `budget` blocks, within the interval
+    assert kp.reserve(7, 500) == kv.KV_OK
+    t0 = time.perf_counter()
+    rc, moved = kp.swap_out_delta([7], [0, 500], ids[:500], [500 * g.B], budget=budget)
+    assert rc == kv.KV_OK and moved.tolist() == [budget]
+    assert kp.sync() == kv.KV_OK
+    wall_us = (time.perf_counter() - t0) * 1e6
+    assert kp.stats()["ms_total"] * 1e3 < 1.25 * interval, kp.stats()
+    assert wall_us < 2.0 * interval
+    # queued work shrinks the budget: enqueue 256 blocks, ask again before they finish
+    assert kp.release(7) == kv.KV_OK
+    assert kp.swap_out([8], [0, 256], ids[:256], [256 * g.B]) == kv.KV_OK
+    io2 = kp.io_stats()
+    b2 = kp.budget_blocks(0, interval)
+    if io2["inflight_bytes"][0]:
+        assert b2 < budget
+    assert kp.sync() == kv.KV_OK
+    kp.close()
+
+
 def test_create_checks_memory_kinds(gpu):
     import torch
     g = W.Geometry(2, 4, 64, 16, "f16", 64)

@@ -195,3 +195,17 @@ def test_plan_is_in_call_order():
     phys, slot = kp.last_plan()
     assert phys.tolist() == [20, 21, 22] and slot.tolist() == [2, 3, 4]
     kp.close()
+
+
+def test_budget_formula_without_measurements():
+    """Under KV_PLAN_ONLY nothing is ever measured: the budget uses the documented defaults
+    (32 GB/s, 50 us fixed cost)."""
+    g = W.Geometry(32, 8, 128, 16, "bf16", 64)
+    kp = kv.KVPool(g, flags=kv.KV_PLAN_ONLY, staging_bytes=16 * g.S)
+    io = kp.io_stats()
+    assert io["inflight_calls"] == [0, 0] and io["ewma_gbps"] == [0.0, 0.0]
+    for d in (0, 1):
+        assert kp.budget_blocks(d, 0.0) == 0 and kp.budget_blocks(d, 50.0) == 0
+        assert kp.budget_blocks(d, 1050.0) == int(1000.0 * 32.0 * 1e3 / g.S)      # 1 ms of link time
+    assert kp.budget_blocks(2, 100.0) == kv.KV_EINVAL
+    kp.close()
