@@ -100,8 +100,11 @@ enum {
   KV_PATH_DMA = 1u,       /* gather into bounce_dev, then hipMemcpyAsync (needs bounce_dev) */
   KV_PATH_ZEROCOPY = 2u,  /* kernels store to / load from the mapped host arena directly */
   KV_STAGING_DEVICE = 4u, /* staging_host is device memory: the on-device gather/scatter */
-  KV_PLAN_ONLY = 8u       /* no HIP call is ever made: bookkeeping and descriptor lists only
+  KV_PLAN_ONLY = 8u,      /* no HIP call is ever made: bookkeeping and descriptor lists only
                              (host-logic tests on machines without a GPU) */
+  KV_REQ_EVENTS = 16u     /* cut every call into segments that end on request boundaries (32 MiB or
+                             more each, see KV_TUNE_SEGMENT_BYTES) and record an event per segment, so
+                             that each request's completion can be polled, waited for and timed */
 };
 
 /* kv_swap_out_delta flags */
@@ -220,6 +223,19 @@ int64_t kv_slot_bytes(const kv_pool* p);
  * produced.  Meant for host-logic tests under KV_PLAN_ONLY. */
 int64_t kv_last_plan(kv_pool* p, int32_t* phys, int64_t* slot, int64_t cap);
 
+/* Per-request completion (needs KV_REQ_EVENTS; Section 6: a control thread follows the transfers
+ * through events; Section 5.3: blocks of a request whose eviction has finished can be reused while
+ * the rest of the burst is still moving).
+ * kv_req_poll: 1 when no transfer of this request is in flight (or none was ever enqueued), 0 while
+ * its last enqueued segment is unfinished.  kv_req_wait blocks until then.  Without KV_REQ_EVENTS
+ * both answer for the whole call the request was part of. */
+int kv_req_poll(kv_pool* p, uint64_t req_id);
+int kv_req_wait(kv_pool* p, uint64_t req_id);
+/* Completion times of the requests of the most recent swap call, in milliseconds of stream time
+ * from the start of that call, in call order.  Waits for the call.  Copies at most cap entries,
+ * returns how many requests the call moved data for. */
+int64_t kv_last_timeline(kv_pool* p, uint64_t* req_ids, float* done_ms, int64_t cap);
+
 /* I/O telemetry for a scheduler (Section 4.3: the memory manager exposes queue lengths and
  * transfer rates so that t_IO = evict queueing + evict + load queueing + load can be estimated;
  * Section 5.2: writes are sized to fit the next compute interval).  Index 0 = evict stream
@@ -247,7 +263,8 @@ enum {
   KV_TUNE_MAX_WGS_DEVICE = 1, /* workgroup cap when both ends are in HBM */
   KV_TUNE_MAX_WGS_LINK = 2,   /* workgroup cap when one end is host memory (CU budget) */
   KV_TUNE_KERNEL_VARIANT = 3, /* 0 default; other values select experimental kernels */
-  KV_TUNE_DMA_SLICE_BLOCKS = 4 /* blocks per gather+copy slice on the DMA path */
+  KV_TUNE_DMA_SLICE_BLOCKS = 4, /* blocks per gather+copy slice on the DMA path */
+  KV_TUNE_SEGMENT_BYTES = 5     /* smallest segment under KV_REQ_EVENTS (default 32 MiB) */
 };
 int kv_pool_tune(kv_pool* p, int32_t what, int64_t value);
 

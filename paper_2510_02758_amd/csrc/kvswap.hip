@@ -18,6 +18,7 @@
 #include <deque>
 #include <mutex>
 #include <new>
+#include <unordered_map>
 #include <vector>
 
 #include "planner.hpp"
@@ -36,6 +37,8 @@ struct Call {
   int stream = kEvict;
   hipEvent_t start = nullptr, end = nullptr;
   std::vector<std::pair<hipEvent_t, hipEvent_t>> kev;
+  std::vector<hipEvent_t> seg_ev;                  // one per segment under KV_REQ_EVENTS
+  std::vector<std::pair<uint64_t, int>> req_seg;   // (request id, segment that completes it; -1: the whole call)
   kv_stats st{};
   bool accounted = false;  // already folded into the telemetry
 };
@@ -93,6 +96,9 @@ struct kv_pool {
   std::deque<Call> calls;  // oldest first; the newest is kept for kv_last_stats
   uint64_t seq = 0;
   std::vector<PendingRelease> pending;
+  std::unordered_map<uint64_t, std::pair<uint64_t, int>> req_where;  // request -> (call seq, segment) of its last transfer
+  bool req_events = false;
+  int64_t segment_bytes = 32ll << 20;
   std::vector<Desc> last_plan;
   kv_stats plan_stats{};  // figures of a call that enqueued nothing
   bool last_instant = false;
@@ -158,6 +164,13 @@ void recycle(kv_pool* p, Call& c) {
     p->ev_free.push_back(k.second);
   }
   c.kev.clear();
+  for (auto e : c.seg_ev) p->ev_free.push_back(e);
+  c.seg_ev.clear();
+  for (auto& rs : c.req_seg) {
+    auto it = p->req_where.find(rs.first);
+    if (it != p->req_where.end() && it->second.first == c.seq) p->req_where.erase(it);
+  }
+  c.req_seg.clear();
   c.start = c.end = nullptr;
 }
 
@@ -375,46 +388,87 @@ bool use_dma(const kv_pool* p, size_t blocks) {
 }
 
 // Move the planned blocks between pool and arena.  out = true: pool -> arena.
-int enqueue_transfer(kv_pool* p, Call& call, const std::vector<Desc>& desc, bool out) {
+// Under KV_REQ_EVENTS the descriptor list is cut into segments that end where a request ends
+// (each at least segment_bytes long); every segment is launched on its own and followed by an
+// event, so a request is known to be complete while the rest of the burst still moves.
+int enqueue_transfer(kv_pool* p, Call& call, const Plan& plan, bool out) {
+  const std::vector<Desc>& desc = plan.desc;
   char* arena = (char*)p->cfg.staging_host;
   const size_t n = desc.size();
-  if (!use_dma(p, n)) {
-    call.st.path = KV_PATH_ZEROCOPY;
-    return enqueue_kernel(p, call, out ? 0 : 1, desc.data(), n, p->arena_dev, !p->dev_staging);
-  }
-  call.st.path = KV_PATH_DMA;
+  const bool dma = use_dma(p, n);
+  call.st.path = dma ? KV_PATH_DMA : KV_PATH_ZEROCOPY;
   hipStream_t st = p->stream[call.stream];
-  const int64_t half_slots = (p->cfg.bounce_bytes / 2) / p->S;
-  char* bounce = (char*)p->cfg.bounce_dev + (out ? 0 : (p->cfg.bounce_bytes / 2 / 16) * 16);
+
+  std::vector<size_t> seg_end;
+  if (p->req_events) {
+    const size_t min_blocks = (size_t)std::max<int64_t>(1, (p->segment_bytes + p->S - 1) / p->S);
+    size_t begin = 0;
+    for (size_t r = 0; r < plan.req_end.size(); r++) {
+      const size_t e = plan.req_end[r].second;
+      if (e - begin >= min_blocks || r + 1 == plan.req_end.size()) {
+        seg_end.push_back(e);
+        begin = e;
+      }
+    }
+  }
+  if (seg_end.empty() || seg_end.back() != n) seg_end.push_back(n);
+
+  const int64_t half_slots = dma ? (p->cfg.bounce_bytes / 2) / p->S : 0;
+  char* bounce = dma ? (char*)p->cfg.bounce_dev + (out ? 0 : (p->cfg.bounce_bytes / 2 / 16) * 16) : nullptr;
   int64_t slice = half_slots;
-  if (p->dma_slice > 0) slice = std::min<int64_t>(slice, p->dma_slice);
+  if (dma && p->dma_slice > 0) slice = std::min<int64_t>(slice, p->dma_slice);
   std::vector<Desc> kd;
-  for (size_t a0 = 0; a0 < n; a0 += (size_t)slice) {
-    const size_t a1 = std::min(n, a0 + (size_t)slice);
-    kd.resize(a1 - a0);
-    for (size_t i = a0; i < a1; i++) kd[i - a0] = {desc[i].a, (int32_t)(i - a0)};
-    if (out) {
-      int rc = enqueue_kernel(p, call, 0, kd.data(), kd.size(), bounce, false);
+  size_t s0 = 0, next_req = 0;
+  for (size_t sg = 0; sg < seg_end.size(); sg++) {
+    const size_t s1 = seg_end[sg];
+    if (!dma) {
+      int rc = enqueue_kernel(p, call, out ? 0 : 1, desc.data() + s0, s1 - s0, p->arena_dev, !p->dev_staging);
       if (rc) return rc;
+    } else {
+      for (size_t a0 = s0; a0 < s1; a0 += (size_t)slice) {
+        const size_t a1 = std::min(s1, a0 + (size_t)slice);
+        kd.resize(a1 - a0);
+        for (size_t i = a0; i < a1; i++) kd[i - a0] = {desc[i].a, (int32_t)(i - a0)};
+        if (out) {
+          int rc = enqueue_kernel(p, call, 0, kd.data(), kd.size(), bounce, false);
+          if (rc) return rc;
+        }
+        // one copy per run of consecutive staging slots
+        for (size_t i = a0; i < a1;) {
+          size_t j = i + 1;
+          while (j < a1 && (uint32_t)desc[j].b == (uint32_t)desc[j - 1].b + 1) j++;
+          char* h = arena + (int64_t)(uint32_t)desc[i].b * p->S;
+          char* d = bounce + (int64_t)(i - a0) * p->S;
+          const size_t bytes = (j - i) * (size_t)p->S;
+          if (out)
+            HIPCHK(p, hipMemcpyAsync(h, d, bytes, hipMemcpyDeviceToHost, st));
+          else
+            HIPCHK(p, hipMemcpyAsync(d, h, bytes, hipMemcpyHostToDevice, st));
+          call.st.copies++;
+          i = j;
+        }
+        if (!out) {
+          int rc = enqueue_kernel(p, call, 1, kd.data(), kd.size(), bounce, false);
+          if (rc) return rc;
+        }
+      }
     }
-    // one copy per run of consecutive staging slots
-    for (size_t i = a0; i < a1;) {
-      size_t j = i + 1;
-      while (j < a1 && (uint32_t)desc[j].b == (uint32_t)desc[j - 1].b + 1) j++;
-      char* h = arena + (int64_t)(uint32_t)desc[i].b * p->S;
-      char* d = bounce + (int64_t)(i - a0) * p->S;
-      const size_t bytes = (j - i) * (size_t)p->S;
-      if (out)
-        HIPCHK(p, hipMemcpyAsync(h, d, bytes, hipMemcpyDeviceToHost, st));
-      else
-        HIPCHK(p, hipMemcpyAsync(d, h, bytes, hipMemcpyHostToDevice, st));
-      call.st.copies++;
-      i = j;
-    }
-    if (!out) {
-      int rc = enqueue_kernel(p, call, 1, kd.data(), kd.size(), bounce, false);
+    int seg_index = -1;
+    if (p->req_events) {
+      hipEvent_t ev;
+      int rc = get_event(p, &ev);
       if (rc) return rc;
+      HIPCHK(p, hipEventRecord(ev, st));
+      call.seg_ev.push_back(ev);
+      seg_index = (int)call.seg_ev.size() - 1;
     }
+    while (next_req < plan.req_end.size() && plan.req_end[next_req].second <= s1) {
+      const uint64_t id = plan.req_end[next_req].first;
+      call.req_seg.push_back({id, seg_index});
+      p->req_where[id] = {call.seq, seg_index};
+      next_req++;
+    }
+    s0 = s1;
   }
   return KV_OK;
 }
@@ -511,6 +565,7 @@ int kv_pool_create(const kv_pool_config* cfg, kv_pool** out) {
   p->cfg = *cfg;
   p->plan_only = plan_only;
   p->dev_staging = (cfg->flags & KV_STAGING_DEVICE) != 0;
+  p->req_events = (cfg->flags & KV_REQ_EVENTS) != 0;
   p->chunk = chunk;
   p->block_bytes = 2 * (int64_t)cfg->num_layers * chunk;
   p->scale_chunk = scale_chunk;
@@ -640,7 +695,7 @@ static int swap_out_common(kv_pool* p, int op, Plan& plan, double t0, void* wait
   int rc = open_call(p, kEvict, op, dep, wait_event, &c);
   if (rc) return rc;
   fill_plan_stats(p, &c->st, op, plan.desc.size(), t1 - t0);
-  rc = enqueue_transfer(p, *c, plan.desc, true);
+  rc = enqueue_transfer(p, *c, plan, true);
   if (rc) return rc;
   rc = close_call(p, *c);
   if (rc) return rc;
@@ -701,7 +756,7 @@ int kv_swap_in(kv_pool* p, int32_t n, const uint64_t* req_ids, const int32_t* of
   rc = open_call(p, kLoad, 3, dep, wait_event, &c);
   if (rc) return rc;
   fill_plan_stats(p, &c->st, 3, plan.desc.size(), t1 - t0);
-  rc = enqueue_transfer(p, *c, plan.desc, false);
+  rc = enqueue_transfer(p, *c, plan, false);
   if (rc) return rc;
   rc = close_call(p, *c);
   if (rc) return rc;
@@ -808,6 +863,58 @@ int kv_last_stats(kv_pool* p, kv_stats* out) {
 
 int64_t kv_slot_bytes(const kv_pool* p) { return p ? p->S : 0; }
 
+// (call, event) that completes the request's last transfer; call == nullptr: nothing in flight
+static hipEvent_t req_event(kv_pool* p, uint64_t req_id) {
+  auto it = p->req_where.find(req_id);
+  if (it == p->req_where.end()) return nullptr;
+  Call* c = find_call(p, it->second.first);
+  if (!c) return nullptr;
+  const int sg = it->second.second;
+  return sg >= 0 && sg < (int)c->seg_ev.size() ? c->seg_ev[(size_t)sg] : c->end;
+}
+
+int kv_req_poll(kv_pool* p, uint64_t req_id) {
+  if (!p) return KV_EINVAL;
+  std::lock_guard<std::mutex> g(p->mu);
+  if (p->plan_only) return 1;
+  hipEvent_t ev = req_event(p, req_id);
+  if (!ev) return 1;
+  hipError_t e = hipEventQuery(ev);
+  if (e == hipSuccess) return 1;
+  (void)hipGetLastError();
+  if (e == hipErrorNotReady) return 0;
+  p->last_hip = (int)e;
+  return KV_EHIP;
+}
+
+int kv_req_wait(kv_pool* p, uint64_t req_id) {
+  if (!p) return KV_EINVAL;
+  std::lock_guard<std::mutex> g(p->mu);
+  if (p->plan_only) return KV_OK;
+  hipEvent_t ev = req_event(p, req_id);
+  if (ev) HIPCHK(p, hipEventSynchronize(ev));
+  return KV_OK;
+}
+
+int64_t kv_last_timeline(kv_pool* p, uint64_t* req_ids, float* done_ms, int64_t cap) {
+  if (!p) return KV_EINVAL;
+  std::lock_guard<std::mutex> g(p->mu);
+  if (p->plan_only || p->last_instant || p->calls.empty()) return 0;
+  Call& c = p->calls.back();
+  if (!c.end) return 0;
+  HIPCHK(p, hipEventSynchronize(c.end));
+  const int64_t n = (int64_t)c.req_seg.size();
+  for (int64_t i = 0; i < n && i < cap; i++) {
+    const int sg = c.req_seg[(size_t)i].second;
+    hipEvent_t ev = sg >= 0 && sg < (int)c.seg_ev.size() ? c.seg_ev[(size_t)sg] : c.end;
+    float ms = 0.f;
+    HIPCHK(p, hipEventElapsedTime(&ms, c.start, ev));
+    if (req_ids) req_ids[i] = c.req_seg[(size_t)i].first;
+    if (done_ms) done_ms[i] = ms;
+  }
+  return n;
+}
+
 static void io_snapshot(kv_pool* p, kv_io_stats* o) {
   std::memset(o, 0, sizeof(*o));
   o->struct_size = sizeof(kv_io_stats);
@@ -879,6 +986,9 @@ int kv_pool_tune(kv_pool* p, int32_t what, int64_t value) {
       return KV_OK;
     case KV_TUNE_DMA_SLICE_BLOCKS:
       p->dma_slice = value;
+      return KV_OK;
+    case KV_TUNE_SEGMENT_BYTES:
+      p->segment_bytes = value ? value : 32ll << 20;
       return KV_OK;
     default:
       return KV_EINVAL;

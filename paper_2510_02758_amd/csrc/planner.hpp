@@ -97,6 +97,7 @@ struct Plan {
   std::vector<std::pair<int64_t, int64_t>> fresh;   // slot runs newly taken from the arena
   std::vector<std::pair<int64_t, int64_t>> freed;   // slot runs given back (swap-in without keep)
   std::vector<uint64_t> touched;                    // request ids whose slots the call reads/writes
+  std::vector<std::pair<uint64_t, size_t>> req_end; // (request id, end of its descriptors in `desc`), call order
   uint64_t wait_out_seq = 0;                        // newest earlier call the plan's slots depend on
   uint64_t wait_in_seq = 0;
 };
@@ -157,6 +158,7 @@ class Planner {
       rc = ensure_cap(r, row, out);
       if (rc) break;
       for (int64_t j = 0; j < row; j++) out->desc.push_back({blk[off[i] + j], (int32_t)(r->base + j)});
+      if (row) out->req_end.push_back({ids[i], out->desc.size()});
       r->staged = (int32_t)row;
       r->wm = (int32_t)(len / B_);
       r->swapped = true;
@@ -200,6 +202,7 @@ class Planner {
       if (m > wm) {
         out->wait_in_seq = std::max(out->wait_in_seq, r->in_seq);
         out->touched.push_back(ids[i]);
+        out->req_end.push_back({ids[i], out->desc.size()});
       }
     }
     if (rc) {
@@ -224,6 +227,7 @@ class Planner {
     for (int32_t i = 0; i < n; i++) {
       Req* r = find_mut(ids[i]);
       for (int64_t j = 0; j < r->staged; j++) out->desc.push_back({blk[off[i] + j], (int32_t)(r->base + j)});
+      if (r->staged) out->req_end.push_back({ids[i], out->desc.size()});
       out->wait_out_seq = std::max(out->wait_out_seq, r->out_seq);
       if (flags & KV_KEEP_STAGING) {
         r->swapped = false;

@@ -18,16 +18,17 @@ LIB_PATH = os.path.join(_HERE, "libkvswap.so")
 
 KV_OK, KV_EINVAL, KV_ERANGE, KV_EDUP, KV_ENOENT = 0, -1, -2, -3, -4
 KV_EEXIST, KV_ENOSPC, KV_EHIP, KV_ESTATE = -5, -6, -7, -8
-KV_PATH_AUTO, KV_PATH_DMA, KV_PATH_ZEROCOPY, KV_STAGING_DEVICE, KV_PLAN_ONLY = 0, 1, 2, 4, 8
+KV_PATH_AUTO, KV_PATH_DMA, KV_PATH_ZEROCOPY, KV_STAGING_DEVICE, KV_PLAN_ONLY, KV_REQ_EVENTS = 0, 1, 2, 4, 8, 16
 KV_DELTA_INCLUDE_TAIL = 1
 KV_KEEP_STAGING = 1
 KV_TUNE_MAX_WGS_DEVICE, KV_TUNE_MAX_WGS_LINK, KV_TUNE_KERNEL_VARIANT, KV_TUNE_DMA_SLICE_BLOCKS = 1, 2, 3, 4
+KV_TUNE_SEGMENT_BYTES = 5
 KV_F16, KV_BF16, KV_FP8_E4M3 = 0, 1, 2
 
 EXPORTS = ["kv_pool_create", "kv_pool_destroy", "kv_swap_out", "kv_swap_out_delta", "kv_swap_in", "kv_sync",
            "kv_move_blocks", "kv_req_reserve", "kv_req_release", "kv_req_query", "kv_last_stats",
            "kv_slot_bytes", "kv_last_plan", "kv_pool_tune", "kv_last_hip_error", "kv_strerror",
-           "kv_io_stats_get", "kv_budget_blocks"]
+           "kv_io_stats_get", "kv_budget_blocks", "kv_req_poll", "kv_req_wait", "kv_last_timeline"]
 
 
 class kv_pool_config(C.Structure):
@@ -87,6 +88,9 @@ _sig = {
     "kv_pool_tune": (C.c_int, [_vp, _i32, _i64]),
     "kv_last_hip_error": (C.c_int, [_vp]),
     "kv_strerror": (C.c_char_p, [C.c_int]),
+    "kv_req_poll": (C.c_int, [_vp, _u64]),
+    "kv_req_wait": (C.c_int, [_vp, _u64]),
+    "kv_last_timeline": (_i64, [_vp, _vp, _vp, _i64]),
     "kv_io_stats_get": (C.c_int, [_vp, C.POINTER(kv_io_stats)]),
     "kv_budget_blocks": (_i64, [_vp, _i32, C.c_double]),
     "kv_bench_copy": (C.c_double, [_vp, _vp, _i64, _i32, _i32, _vp]),
@@ -204,6 +208,25 @@ def kv_last_plan(h):
     return phys, slot
 
 
+def kv_req_poll(h, req_id):
+    return _lib.kv_req_poll(h, int(req_id))
+
+
+def kv_req_wait(h, req_id):
+    return _lib.kv_req_wait(h, int(req_id))
+
+
+def kv_last_timeline(h):
+    """-> (req_ids uint64[n], done_ms float32[n]) of the most recent swap call"""
+    n = _lib.kv_last_timeline(h, None, None, 0)
+    if n < 0:
+        raise KVSwapError(n, "kv_last_timeline")
+    ids, ms = np.zeros(n, np.uint64), np.zeros(n, np.float32)
+    if n:
+        _lib.kv_last_timeline(h, _p(ids), _p(ms), n)
+    return ids, ms
+
+
 def kv_io_stats_get(h):
     """-> (rc, dict of 2-element lists: index 0 evict stream, 1 load stream)"""
     st = kv_io_stats()
@@ -318,6 +341,15 @@ class KVPool:
 
     def last_plan(self):
         return kv_last_plan(self.h)
+
+    def req_poll(self, req_id):
+        return kv_req_poll(self.h, req_id)
+
+    def req_wait(self, req_id):
+        return kv_req_wait(self.h, req_id)
+
+    def timeline(self):
+        return kv_last_timeline(self.h)
 
     def io_stats(self):
         rc, st = kv_io_stats_get(self.h)

@@ -233,6 +233,50 @@ def test_auto_path_choice(gpu):
     kp2.close()
 
 
+@pytest.mark.parametrize("base", ["zerocopy", "dma", "device"])
+def test_per_request_events(gpu, base):
+    """KV_REQ_EVENTS: the burst is cut at request boundaries; bytes stay the oracle's, every request
+    can be polled / waited for, and the timeline is monotone in call order."""
+    import torch
+    flags = PATHS[base] | kv.KV_REQ_EVENTS
+    g = W.Geometry(4, 8, 128, 16, "bf16", 900)              # block = 256 KiB
+    seed = 0xE7E
+    lens = W.request_lengths(seed, 12, ("uniform", 50, 900))
+    off, ids, free = W.block_tables(seed, g.N, W.blocks_for(lens, g.B))
+    rid = np.arange(1, 13, dtype=np.uint64)
+    total = int(off[-1])
+    a = HostPool(g, seed, slots=total + 2)
+    ora = a.oracle()
+    b = HostPool(g, seed, slots=total + 2)
+    gpuad = GpuAdapter(b, flags, bounce_slots=16, tune=((kv.KV_TUNE_SEGMENT_BYTES, 2 << 20),))
+    kp = gpuad.kp
+    assert ora.swap_out(rid, off, ids, lens) == ko.OK
+    gpuad._push()
+    assert kp.swap_out(rid, off, ids, lens) == kv.KV_OK
+    for r in rid[::-1]:
+        assert kp.req_wait(r) == kv.KV_OK
+        assert kp.req_poll(r) == 1
+    tids, tms = kp.timeline()
+    st = kp.stats()
+    assert tids.tolist() == rid.tolist()
+    assert (np.diff(tms) >= 0).all() and tms[0] > 0 and tms[-1] <= st["ms_total"] * 1.001
+    # a 2 MiB floor = 8 blocks: requests of 4..57 blocks -> several segments, each one launch (zero-copy)
+    nseg = len(np.unique(tms))
+    assert nseg >= 6
+    if base != "dma":
+        assert st["launches"] == nseg
+    gpuad._pull()
+    assert np.array_equal(a.staging, b.staging) and np.array_equal(a.pool, b.pool)
+    new = free[:total]
+    assert ora.swap_in(rid, off, new) == ko.OK
+    assert gpuad.swap_in(rid, off, new) == kv.KV_OK
+    assert np.array_equal(a.pool, b.pool)
+    tids, tms = kp.timeline()
+    assert tids.tolist() == rid.tolist() and (np.diff(tms) >= 0).all()
+    assert kp.req_poll(12345) == 1                           # never seen: nothing in flight
+    gpuad.close()
+
+
 def test_telemetry_and_time_budget(gpu):
     """Section 5.2: a write sized from the measured rate finishes inside the interval it was sized
     for.  The budget must equal the documented formula applied to the reported telemetry."""
