@@ -309,6 +309,7 @@ void launch_move(int u, int grid, bool link, hipStream_t st, const MoveArgs& a) 
 int pick_unroll(const kv_pool* p, bool link) {
   if (p->variant == 1 || p->variant == 2 || p->variant == 4 || p->variant == 8) return (int)p->variant;
   if (!link) return 1;
+  if (p->chunk < 4096) return 4;  // groups of small chunks: four 4 KiB groups per workgroup pass
   if (p->chunk >= 16384) return 4;
   if (p->chunk >= 8192) return 2;
   return 1;
@@ -343,6 +344,14 @@ int enqueue_kernel(kv_pool* p, Call& call, int mode, const Desc* desc, size_t n,
   a.chunk = (int32_t)p->chunk;
   a.ppc = (int32_t)((p->chunk + piece - 1) / piece);
   a.jobs_per_block = 2 * p->cfg.num_layers * a.ppc;
+  a.L2 = 2 * p->cfg.num_layers;
+  a.lpc = a.cpj = 0;
+  if (p->chunk < 4096) {  // several chunks per job
+    a.lpc = (int32_t)(p->chunk / 16);
+    a.cpj = 256 / a.lpc;
+    const int per_job = a.cpj * u;
+    a.jobs_per_block = (a.L2 + per_job - 1) / per_job;
+  }
   a.H = p->cfg.num_kv_heads;
   a.scale_words = p->cfg.scale_dev ? 2 * p->cfg.num_layers * p->cfg.num_kv_heads : 0;
   a.n_data_jobs = (int64_t)n * a.jobs_per_block;

@@ -138,6 +138,21 @@ def test_small_chunks(gpu, path):
     run_both(W.Geometry(5, 1, 128, 16, "bf16", 256), 0x702, "layer", path, 10, 16, 300, 6)
 
 
+@pytest.mark.parametrize("path", list(PATHS))
+@pytest.mark.parametrize("unroll", [0, 1, 2, 8])
+def test_small_chunk_groups(gpu, path, unroll):
+    """Chunks below 4 KiB are moved several per workgroup: 48 B (3 lanes per chunk, 85 chunks per
+    group, lanes left over), 1 KiB, 2 KiB, and 3088 B (one chunk per group, 63 idle lanes); 2L is
+    not a multiple of the group size, so the last group of every block is ragged."""
+    tune = ((kv.KV_TUNE_KERNEL_VARIANT, unroll),) if unroll else ()
+    run_both(W.Geometry(45, 1, 24, 1, "bf16", 300), 0x5C1 + unroll, "layer", path, 9, 1, 30, 6, tune=tune)
+    run_both(W.Geometry(7, 2, 64, 4, "bf16", 300), 0x5C2 + unroll, "padded", path, 9, 4, 100, 6, tune=tune)
+    run_both(W.Geometry(5, 1, 128, 8, "bf16", 300), 0x5C3 + unroll, "block", path, 9, 8, 200, 6, tune=tune)
+    run_both(W.Geometry(3, 1, 193, 8, "bf16", 300), 0x5C4 + unroll, "layer", path, 9, 8, 200, 6, tune=tune)
+    run_both(W.Geometry(3, 4, 16, 4, "fp8_e4m3", 200, scales=True), 0x5C5 + unroll, "padded", path, 7, 4, 90, 5,
+             tune=tune)
+
+
 def test_back_to_back_without_sync(gpu):
     """Stream ordering: swap-out then swap-in of the same requests with no kv_sync in between;
     then a second swap-out that reuses the slots the first swap-in is still reading."""
