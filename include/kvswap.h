@@ -264,7 +264,8 @@ enum {
   KV_TUNE_MAX_WGS_LINK = 2,   /* workgroup cap when one end is host memory (CU budget) */
   KV_TUNE_KERNEL_VARIANT = 3, /* 0 default; other values select experimental kernels */
   KV_TUNE_DMA_SLICE_BLOCKS = 4, /* blocks per gather+copy slice on the DMA path */
-  KV_TUNE_SEGMENT_BYTES = 5     /* smallest segment under KV_REQ_EVENTS (default 32 MiB) */
+  KV_TUNE_SEGMENT_BYTES = 5,    /* smallest segment under KV_REQ_EVENTS (default 32 MiB) */
+  KV_TUNE_SCALE_LDS = 6         /* scale side band: 0 default (LDS for the scatter), 1 word by word, 2 LDS both ways */
 };
 int kv_pool_tune(kv_pool* p, int32_t what, int64_t value);
 

@@ -132,6 +132,19 @@ def test_fp8_with_scales(gpu, path):
 
 
 @pytest.mark.parametrize("path", list(PATHS))
+@pytest.mark.parametrize("knob", [1, 2])
+def test_scale_side_band_variants(gpu, path, knob):
+    """The scale side band word by word (1) and staged through LDS (2) give the same bytes."""
+    tune = ((kv.KV_TUNE_SCALE_LDS, knob),)
+    run_both(W.Geometry(4, 32, 128, 32, "fp8_e4m3", 128, scales=True), 0x5CA + knob, "layer", path, 6, 32, 256, 4,
+             tune=tune)
+    run_both(W.Geometry(3, 6, 16, 4, "fp8_e4m3", 160, scales=True), 0x5CB + knob, "padded", path, 7, 1, 40, 5,
+             tune=tune)
+    run_both(W.Geometry(6, 2, 32, 1, "fp8_e4m3", 400, scales=True), 0x5CC + knob, "block", path, 9, 1, 40, 6,
+             tune=tune)
+
+
+@pytest.mark.parametrize("path", list(PATHS))
 def test_small_chunks(gpu, path):
     """Token-level pool (B=1) and a tensor-parallel shard with one KV head: chunks of 256 B / 4 KiB."""
     run_both(W.Geometry(4, 1, 128, 1, "bf16", 512), 0x701, "layer", path, 12, 1, 40, 7)
