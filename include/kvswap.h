@@ -50,12 +50,15 @@
  *     exception crosses the boundary.
  *   - All-or-nothing: a call checks every request and every block id before it
  *     changes any state or enqueues any work.
- *   - Calls are asynchronous.  Swap-out / delta work is enqueued on the evict
- *     stream, swap-in work on the load stream, in issue order.  The library
- *     inserts the cross-stream waits needed when a swap-in reads staging slots
- *     an unfinished swap-out writes, and when a swap-out reuses slots an
- *     unfinished swap-in still reads.  It does NOT track device blocks: the
- *     caller must not pass destination blocks that in-flight work still reads.
+ *   - Calls are asynchronous.  Swap-out / delta / move work is enqueued on the evict stream,
+ *     swap-in work on the load stream, in issue order.  The library inserts every cross-stream
+ *     wait the two streams need between themselves: for staging slots (a swap-in reads slots an
+ *     unfinished swap-out writes; a swap-out reuses slots an unfinished swap-in still reads) and
+ *     for device blocks (a swap-in is handed blocks an unfinished swap-out or move still reads;
+ *     a swap-out or move reads blocks an unfinished swap-in still writes).  Section 5.3 lets
+ *     eviction and loading overlap "while maintaining memory safety": this is that guarantee.
+ *     Work of OTHER streams (the model's compute) is the caller's to order, through wait_event
+ *     and kv_sync / kv_req_wait.
  *   - wait_event (nullable) is a hipEvent_t; the call's stream waits for it
  *     before touching the pool (ordering after the caller's compute stream).
  *   - Argument arrays are HOST pointers, read during the call, free on return.

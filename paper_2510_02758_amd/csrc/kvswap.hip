@@ -12,6 +12,7 @@
 #include <hip/hip_runtime.h>
 
 #include <chrono>
+#include <climits>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -46,6 +47,13 @@ struct Call {
 struct RingSeg {
   size_t begin, end;
   uint64_t seq;
+};
+
+// Last in-flight reader / writer of a device block: low 32 bits of the call's sequence number
+// (0: none) and the segment of that call that touches the block (-1: the call as a whole).
+struct BlkMark {
+  uint32_t seq;
+  int32_t seg;
 };
 
 struct PendingRelease {
@@ -96,6 +104,7 @@ struct kv_pool {
   std::deque<Call> calls;  // oldest first; the newest is kept for kv_last_stats
   uint64_t seq = 0;
   std::vector<PendingRelease> pending;
+  std::vector<BlkMark> blk_reader, blk_writer;  // per device block, see block_hazard()
   std::unordered_map<uint64_t, std::pair<uint64_t, int>> req_where;  // request -> (call seq, segment) of its last transfer
   bool req_events = false;
   int64_t segment_bytes = 32ll << 20;
@@ -403,6 +412,8 @@ bool use_dma(const kv_pool* p, size_t blocks) {
   return half_slots >= 1 && (int64_t)blocks * p->S >= kAutoDmaMinBytes;
 }
 
+void mark_blocks(kv_pool* p, const Call& c, int mode, const Desc* desc, size_t n, int seg);
+
 // Move the planned blocks between pool and arena.  out = true: pool -> arena.
 // Under KV_REQ_EVENTS the descriptor list is cut into segments that end where a request ends
 // (each at least segment_bytes long); every segment is launched on its own and followed by an
@@ -478,6 +489,7 @@ int enqueue_transfer(kv_pool* p, Call& call, const Plan& plan, bool out) {
       call.seg_ev.push_back(ev);
       seg_index = (int)call.seg_ev.size() - 1;
     }
+    mark_blocks(p, call, out ? 0 : 1, desc.data() + s0, s1 - s0, seg_index);
     while (next_req < plan.req_end.size() && plan.req_end[next_req].second <= s1) {
       const uint64_t id = plan.req_end[next_req].first;
       call.req_seg.push_back({id, seg_index});
@@ -489,10 +501,77 @@ int enqueue_transfer(kv_pool* p, Call& call, const Plan& plan, bool out) {
   return KV_OK;
 }
 
+// Device-block hazards between the two streams.  A new call on `stream` that READS block b must
+// come after an unfinished call of the other stream that WRITES b; one that WRITES b must come
+// after unfinished readers and writers of b on the other stream.  Calls of one stream finish in
+// order, so the newest (call, segment) among the conflicting marks is the one event to wait for.
+// mode: 0 gather (reads desc.a), 1 scatter (writes desc.a), 2 move (reads a, writes b).
+hipEvent_t block_hazard(kv_pool* p, int stream, int mode, const std::vector<Desc>& desc) {
+  if (p->blk_reader.empty()) return nullptr;
+  // unfinished calls of the other stream, oldest first
+  std::vector<Call*> other;
+  for (auto& c : p->calls)
+    if (c.stream != stream && c.end && c.seq != 0) {
+      if (hipEventQuery(c.end) != hipSuccess) {
+        (void)hipGetLastError();
+        other.push_back(&c);
+      }
+    }
+  if (other.empty()) return nullptr;
+  int best_call = -1, best_seg = -2;
+  auto consider = [&](const BlkMark& m) {
+    if (!m.seq) return;
+    for (int i = (int)other.size() - 1; i >= 0; i--)
+      if ((uint32_t)other[(size_t)i]->seq == m.seq) {
+        // -1 means "the whole call": later than any of its segments
+        const int seg = m.seg < 0 ? INT32_MAX : m.seg;
+        if (i > best_call || (i == best_call && seg > best_seg)) {
+          best_call = i;
+          best_seg = seg;
+        }
+        return;
+      }
+  };
+  for (const Desc& d : desc) {
+    if (mode == 0) {
+      consider(p->blk_writer[(size_t)d.a]);
+    } else if (mode == 1) {
+      consider(p->blk_reader[(size_t)d.a]);
+      consider(p->blk_writer[(size_t)d.a]);
+    } else {
+      consider(p->blk_writer[(size_t)d.a]);
+      consider(p->blk_reader[(size_t)d.b]);
+      consider(p->blk_writer[(size_t)d.b]);
+    }
+  }
+  if (best_call < 0) return nullptr;
+  Call* c = other[(size_t)best_call];
+  if (best_seg != INT32_MAX && best_seg >= 0 && best_seg < (int)c->seg_ev.size()) return c->seg_ev[(size_t)best_seg];
+  return c->end;
+}
+
+void mark_blocks(kv_pool* p, const Call& c, int mode, const Desc* desc, size_t n, int seg) {
+  if (p->blk_reader.empty()) return;
+  const BlkMark m{(uint32_t)c.seq, seg};
+  for (size_t i = 0; i < n; i++) {
+    if (mode == 0) {
+      p->blk_reader[(size_t)desc[i].a] = m;
+    } else if (mode == 1) {
+      p->blk_writer[(size_t)desc[i].a] = m;
+    } else {
+      p->blk_reader[(size_t)desc[i].a] = m;
+      p->blk_writer[(size_t)desc[i].b] = m;
+    }
+  }
+}
+
 // Open a call record: cross-stream waits, caller's event, start event.
-int open_call(kv_pool* p, int stream, int op, uint64_t wait_seq, void* wait_event, Call** out) {
+int open_call(kv_pool* p, int stream, int op, uint64_t wait_seq, void* wait_event, int mode,
+              const std::vector<Desc>& desc, Call** out) {
   retire(p);
   p->last_instant = false;
+  hipEvent_t blk_dep = block_hazard(p, stream, mode, desc);  // before any event is taken from the pool
+  if (blk_dep) HIPCHK(p, hipStreamWaitEvent(p->stream[stream], blk_dep, 0));
   p->calls.emplace_back();
   Call& c = p->calls.back();
   c.seq = ++p->seq;
@@ -665,6 +744,10 @@ int kv_pool_create(const kv_pool_config* cfg, kv_pool** out) {
     }
   }
   if (!rc) rc = grow_ring(p, (size_t)1 << 16);
+  if (!rc) {
+    p->blk_reader.assign((size_t)cfg->num_blocks, BlkMark{0, -1});
+    p->blk_writer.assign((size_t)cfg->num_blocks, BlkMark{0, -1});
+  }
   if (rc) {
     kv_pool_destroy(p);
     return rc;
@@ -708,7 +791,7 @@ static int swap_out_common(kv_pool* p, int op, Plan& plan, double t0, void* wait
     return KV_OK;
   }
   Call* c = nullptr;
-  int rc = open_call(p, kEvict, op, dep, wait_event, &c);
+  int rc = open_call(p, kEvict, op, dep, wait_event, 0, plan.desc, &c);
   if (rc) return rc;
   fill_plan_stats(p, &c->st, op, plan.desc.size(), t1 - t0);
   rc = enqueue_transfer(p, *c, plan, true);
@@ -769,7 +852,7 @@ int kv_swap_in(kv_pool* p, int32_t n, const uint64_t* req_ids, const int32_t* of
     return KV_OK;
   }
   Call* c = nullptr;
-  rc = open_call(p, kLoad, 3, dep, wait_event, &c);
+  rc = open_call(p, kLoad, 3, dep, wait_event, 1, plan.desc, &c);
   if (rc) return rc;
   fill_plan_stats(p, &c->st, 3, plan.desc.size(), t1 - t0);
   rc = enqueue_transfer(p, *c, plan, false);
@@ -799,12 +882,13 @@ int kv_move_blocks(kv_pool* p, int64_t n, const int32_t* src_ids, const int32_t*
     return KV_OK;
   }
   Call* c = nullptr;
-  rc = open_call(p, kEvict, 4, 0, wait_event, &c);
+  rc = open_call(p, kEvict, 4, 0, wait_event, 2, plan.desc, &c);
   if (rc) return rc;
   fill_plan_stats(p, &c->st, 4, plan.desc.size(), t1 - t0);
   c->st.path = KV_PATH_ZEROCOPY;
   rc = enqueue_kernel(p, *c, 2, plan.desc.data(), plan.desc.size(), nullptr, false);
   if (rc) return rc;
+  mark_blocks(p, *c, 2, plan.desc.data(), plan.desc.size(), -1);
   rc = close_call(p, *c);
   if (rc) return rc;
   c->st.enqueue_us = now_us() - t1;

@@ -199,6 +199,50 @@ def test_back_to_back_without_sync(gpu):
     kp.close()
 
 
+@pytest.mark.parametrize("events", [0, kv.KV_REQ_EVENTS])
+def test_device_block_hazards_between_streams(gpu, events):
+    """The library orders the evict and load streams around DEVICE blocks too: a swap-in may be
+    handed blocks that an unfinished swap-out still reads, a swap-out or a move may read blocks an
+    unfinished swap-in still writes, all without kv_sync in between.  Expected result: the oracle's,
+    which runs the same calls one after the other."""
+    import torch
+    g = W.Geometry(32, 8, 128, 16, "bf16", 1400)             # 2 MiB blocks, 2.7 GiB pool
+    seed = 0xB10CC
+    a = HostPool(g, seed, slots=1300)
+    ora = a.oracle()
+    pool = torch.from_numpy(a.pool.copy()).cuda()
+    staging = torch.full((len(a.staging),), CANARY, dtype=torch.uint8).pin_memory()
+    kp = kv.KVPool(g, pool, staging, flags=kv.KV_PATH_ZEROCOPY | events)
+    perm = np.random.default_rng(4).permutation(g.N).astype(np.int32)
+    X, Y, Z = perm[:300], perm[300:600], perm[600:900]
+    offA = np.array([0, 100, 300], np.int32)                  # request A = two requests, 100 + 200 blocks
+    lensA = np.array([100 * g.B, 200 * g.B - 3], np.int32)
+    lensB = np.array([300 * g.B], np.int32)
+
+    # Each follow-up walks the blocks in the opposite order, so that without ordering the second
+    # kernel reaches the far end of the list long before the first one does.
+    Xr, Zr = X[::-1].copy(), Z[::-1].copy()
+
+    def script(o, OK):
+        # B's KV lives in blocks Y and is swapped out first
+        assert o.swap_out([7], [0, 300], Y, lensB) == OK
+        # 1. evict A from X, and at once load B into the very same blocks
+        assert o.swap_out([1, 2], offA, X, lensA) == OK
+        assert o.swap_in([7], [0, 300], Xr, kv.KV_KEEP_STAGING) == OK
+        # 2. at once evict a new request that owns the blocks B was just loaded into (fresh slots)
+        assert o.swap_out([8], [0, 300], X, lensB) == OK
+        # 3. load A somewhere else and at once move it on inside the pool
+        assert o.swap_in([1, 2], offA, Z) == OK
+        assert o.move_blocks(Zr, Y) == OK
+
+    script(kp, kv.KV_OK)          # the library: six calls back to back, nothing waits on the host
+    assert kp.sync() == kv.KV_OK
+    script(ora, ko.OK)            # the oracle: the same calls, one after the other
+    assert np.array_equal(staging.numpy(), a.staging), "staging differs: a gather read blocks too late or too early"
+    assert np.array_equal(pool.cpu().numpy(), a.pool), "pool differs: a scatter or move ran too early"
+    kp.close()
+
+
 def test_wait_event_orders_after_producer(gpu):
     """The caller's compute stream fills the blocks; kv_swap_out must wait for its event."""
     import torch
