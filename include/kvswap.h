@@ -261,6 +261,18 @@ int kv_io_stats_get(kv_pool* p, kv_io_stats* out);
  * "nothing fits": do not pass it on, since a budget of 0 means unlimited there. */
 int64_t kv_budget_blocks(kv_pool* p, int32_t dir, double interval_us);
 
+/* Section 5.2 in one call: "synchronous chunked writing".  The requests are served in order of
+ * decreasing priority[i] (the scheduler's buffer sizes: a request with a larger buffer is the more
+ * likely victim; ties and priority == NULL: call order) under the block budget that
+ * kv_budget_blocks(p, 0, interval_us) gives at this moment, so that the write ends inside the next
+ * compute interval.  Otherwise as kv_swap_out_delta; blocks_moved is in the caller's order;
+ * budget_used (nullable) receives the budget applied.  If nothing fits, nothing moves (the
+ * arguments are still checked and extents reserved). */
+int kv_swap_out_delta_timed(kv_pool* p, int32_t n, const uint64_t* req_ids, const int32_t* offsets,
+                            const int32_t* block_ids, const int32_t* num_tokens, const float* priority,
+                            double interval_us, uint32_t flags, int32_t* blocks_moved, int64_t* budget_used,
+                            void* wait_event);
+
 /* Launch-shape knobs: value 0 restores the default. */
 enum {
   KV_TUNE_MAX_WGS_DEVICE = 1, /* workgroup cap when both ends are in HBM */

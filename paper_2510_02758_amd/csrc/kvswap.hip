@@ -1046,9 +1046,52 @@ int kv_io_stats_get(kv_pool* p, kv_io_stats* out) {
   return KV_OK;
 }
 
+static int64_t budget_blocks_locked(kv_pool* p, int32_t dir, double interval_us);
+
 int64_t kv_budget_blocks(kv_pool* p, int32_t dir, double interval_us) {
   if (!p || (dir != 0 && dir != 1) || !(interval_us >= 0)) return KV_EINVAL;
   std::lock_guard<std::mutex> g(p->mu);
+  return budget_blocks_locked(p, dir, interval_us);
+}
+
+int kv_swap_out_delta_timed(kv_pool* p, int32_t n, const uint64_t* req_ids, const int32_t* offsets,
+                            const int32_t* block_ids, const int32_t* num_tokens, const float* priority,
+                            double interval_us, uint32_t flags, int32_t* blocks_moved, int64_t* budget_used,
+                            void* wait_event) {
+  if (!p || !(interval_us >= 0)) return KV_EINVAL;
+  if (n < 0 || (n > 0 && (!req_ids || !offsets || !num_tokens))) return KV_EINVAL;
+  std::lock_guard<std::mutex> g(p->mu);
+  const double t0 = now_us();
+  const int64_t budget = budget_blocks_locked(p, 0, interval_us);
+  if (budget_used) *budget_used = budget;
+  // priority order, stable
+  std::vector<int32_t> order((size_t)n);
+  for (int32_t i = 0; i < n; i++) order[(size_t)i] = i;
+  if (priority)
+    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return priority[a] > priority[b]; });
+  for (int32_t i = 0; i < n; i++)
+    if (offsets[i + 1] < offsets[i] || offsets[0] < 0) return KV_EINVAL;
+  std::vector<uint64_t> ids((size_t)n);
+  std::vector<int32_t> off((size_t)n + 1, 0), tok((size_t)n), blk, moved((size_t)n, 0);
+  for (int32_t k = 0; k < n; k++) {
+    const int32_t i = order[(size_t)k];
+    ids[(size_t)k] = req_ids[i];
+    tok[(size_t)k] = num_tokens[i];
+    const int32_t len = offsets[i + 1] - offsets[i];
+    if (len > 0 && !block_ids) return KV_EINVAL;
+    blk.insert(blk.end(), block_ids + offsets[i], block_ids + offsets[i] + len);
+    off[(size_t)k + 1] = off[(size_t)k] + len;
+  }
+  Plan plan;
+  int rc = p->planner.plan_delta(n, ids.data(), off.data(), blk.data(), tok.data(), budget, flags, moved.data(), &plan,
+                                 /*limited_even_if_zero=*/true);
+  if (rc) return rc;
+  if (blocks_moved)
+    for (int32_t k = 0; k < n; k++) blocks_moved[order[(size_t)k]] = moved[(size_t)k];
+  return swap_out_common(p, 2, plan, t0, wait_event);
+}
+
+static int64_t budget_blocks_locked(kv_pool* p, int32_t dir, double interval_us) {
   kv_io_stats io;
   io_snapshot(p, &io);
   const double rate = io.ewma_gbps[dir] > 0 ? io.ewma_gbps[dir] : 32.0;           // GB/s = bytes per ns

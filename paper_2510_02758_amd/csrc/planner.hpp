@@ -170,8 +170,9 @@ class Planner {
   }
 
   // Incremental write-through (Section 5.1), sized and ordered (Section 5.2).
+  // limited_even_if_zero: a budget of 0 then means "move nothing" instead of "unlimited".
   int plan_delta(int32_t n, const uint64_t* ids, const int32_t* off, const int32_t* blk, const int32_t* ntok,
-                 int64_t budget, uint32_t flags, int32_t* moved, Plan* out) {
+                 int64_t budget, uint32_t flags, int32_t* moved, Plan* out, bool limited_even_if_zero = false) {
     int rc = check_call(n, ids, off, blk);
     if (rc) return rc;
     if (budget < 0) return KV_EINVAL;
@@ -179,7 +180,7 @@ class Planner {
     if (!ntok) return KV_EINVAL;
     begin();
     moved_.assign((size_t)n, 0);
-    const bool unlimited = budget == 0;
+    const bool unlimited = budget == 0 && !limited_even_if_zero;
     int64_t left = budget;
     for (int32_t i = 0; i < n && !rc; i++) {
       int64_t len = ntok[i], row = (int64_t)off[i + 1] - off[i];

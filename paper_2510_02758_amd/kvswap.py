@@ -29,7 +29,8 @@ KV_F16, KV_BF16, KV_FP8_E4M3 = 0, 1, 2
 EXPORTS = ["kv_pool_create", "kv_pool_destroy", "kv_swap_out", "kv_swap_out_delta", "kv_swap_in", "kv_sync",
            "kv_move_blocks", "kv_req_reserve", "kv_req_release", "kv_req_query", "kv_last_stats",
            "kv_slot_bytes", "kv_last_plan", "kv_pool_tune", "kv_last_hip_error", "kv_strerror",
-           "kv_io_stats_get", "kv_budget_blocks", "kv_req_poll", "kv_req_wait", "kv_last_timeline"]
+           "kv_io_stats_get", "kv_budget_blocks", "kv_req_poll", "kv_req_wait", "kv_last_timeline",
+           "kv_swap_out_delta_timed"]
 
 
 class kv_pool_config(C.Structure):
@@ -77,6 +78,7 @@ _sig = {
     "kv_pool_destroy": (C.c_int, [_vp]),
     "kv_swap_out": (C.c_int, [_vp, _i32, _vp, _vp, _vp, _vp, _vp]),
     "kv_swap_out_delta": (C.c_int, [_vp, _i32, _vp, _vp, _vp, _vp, _i64, _u32, _vp, _vp]),
+    "kv_swap_out_delta_timed": (C.c_int, [_vp, _i32, _vp, _vp, _vp, _vp, _vp, C.c_double, _u32, _vp, _vp, _vp]),
     "kv_swap_in": (C.c_int, [_vp, _i32, _vp, _vp, _vp, _u32, _vp]),
     "kv_sync": (C.c_int, [_vp]),
     "kv_move_blocks": (C.c_int, [_vp, _i64, _vp, _vp, _vp]),
@@ -153,6 +155,20 @@ def kv_swap_out_delta(h, req_ids, offsets, block_ids, num_tokens, block_budget=0
     rc = _lib.kv_swap_out_delta(h, len(r), _p(r), _p(o), _p(b), _p(t), int(block_budget), int(flags),
                                 _p(moved), wait_event)
     return rc, moved
+
+
+def kv_swap_out_delta_timed(h, req_ids, offsets, block_ids, num_tokens, priority, interval_us, flags=0,
+                            wait_event=None):
+    """-> (rc, blocks_moved int32[n] in the caller's order, budget applied)"""
+    r, o, b, t = _u64a(req_ids), _i32a(offsets), _i32a(block_ids), _i32a(num_tokens)
+    pr = None if priority is None else np.ascontiguousarray(np.asarray(priority, dtype=np.float32))
+    moved = np.zeros(len(r), dtype=np.int32)
+    if not _csr_ok(len(r), o, b, t) or (pr is not None and len(pr) != len(r)):
+        return KV_EINVAL, moved, 0
+    used = _i64(0)
+    rc = _lib.kv_swap_out_delta_timed(h, len(r), _p(r), _p(o), _p(b), _p(t), _p(pr), float(interval_us), int(flags),
+                                      _p(moved), C.byref(used), wait_event)
+    return rc, moved, used.value
 
 
 def kv_swap_in(h, req_ids, offsets, new_block_ids, flags=0, wait_event=None):
@@ -315,6 +331,11 @@ class KVPool:
 
     def swap_out_delta(self, req_ids, offsets, block_ids, num_tokens, budget=0, flags=0, wait_event=None):
         return kv_swap_out_delta(self.h, req_ids, offsets, block_ids, num_tokens, budget, flags, wait_event)
+
+    def swap_out_delta_timed(self, req_ids, offsets, block_ids, num_tokens, priority, interval_us, flags=0,
+                             wait_event=None):
+        return kv_swap_out_delta_timed(self.h, req_ids, offsets, block_ids, num_tokens, priority, interval_us, flags,
+                                       wait_event)
 
     def swap_in(self, req_ids, offsets, new_block_ids, flags=0, wait_event=None):
         return kv_swap_in(self.h, req_ids, offsets, new_block_ids, flags, wait_event)

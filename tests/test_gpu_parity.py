@@ -386,8 +386,15 @@ def test_telemetry_and_time_budget(gpu):
     wall_us = (time.perf_counter() - t0) * 1e6
     assert kp.stats()["ms_total"] * 1e3 < 1.25 * interval, kp.stats()
     assert wall_us < 2.0 * interval
-    # queued work shrinks the budget: enqueue 256 blocks, ask again before they finish
+    # the same in one call, two requests, the second one more urgent
     assert kp.release(7) == kv.KV_OK
+    assert kp.reserve(20, 200) == kv.KV_OK and kp.reserve(21, 200) == kv.KV_OK
+    rc, moved, used = kp.swap_out_delta_timed([20, 21], [0, 200, 400], ids[:400], [200 * g.B] * 2, [0.5, 2.0], interval)
+    assert rc == kv.KV_OK and 40 < used < 120 and moved.tolist() == [0, used]
+    assert kp.sync() == kv.KV_OK
+    assert kp.stats()["ms_total"] * 1e3 < 1.25 * interval
+    assert kp.release(20) == kv.KV_OK and kp.release(21) == kv.KV_OK
+    # queued work shrinks the budget: enqueue 256 blocks, ask again before they finish
     assert kp.swap_out([8], [0, 256], ids[:256], [256 * g.B]) == kv.KV_OK
     io2 = kp.io_stats()
     b2 = kp.budget_blocks(0, interval)

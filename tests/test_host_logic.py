@@ -209,3 +209,45 @@ def test_budget_formula_without_measurements():
         assert kp.budget_blocks(d, 1050.0) == int(1000.0 * 32.0 * 1e3 / g.S)      # 1 ms of link time
     assert kp.budget_blocks(2, 100.0) == kv.KV_EINVAL
     kp.close()
+
+
+def test_timed_delta_orders_by_priority_and_applies_the_budget():
+    """Section 5.2: larger buffers first, sized to the interval.  Plan-only: rate 32 GB/s, fixed
+    50 us, so the budget is known in closed form; the oracle, given the same order and budget,
+    must stage the same bytes."""
+    g = W.Geometry(1, 1, 8, 2, "f16", 64)                   # S = 64 bytes
+    a = HostPool(g, 5, slots=20)
+    b = HostPool(g, 5, slots=20)
+    ora, lib = a.oracle(), PlanOnlyAdapter(b)
+    rid = [10, 11, 12]
+    off = [0, 4, 8, 13]
+    blk = list(range(20, 33))
+    tok = [8, 8, 9]                                          # 4, 4 and 4 full blocks (+ a tail for the third)
+    prio = [1.0, 3.0, 2.0]
+    interval = 50.011                                        # (50.011 - 50) us * 32 GB/s / 64 B = 5.5 -> 5 blocks
+    rc, moved, used = lib.kp.swap_out_delta_timed(rid, off, blk, tok, prio, interval)
+    assert rc == kv.KV_OK and used == 5
+    assert moved.tolist() == [0, 4, 1]                       # request 11 first, then 12, nothing left for 10
+    phys, slot = lib.kp.last_plan()
+    assert phys.tolist() == [24, 25, 26, 27, 28]
+    lib._apply_out()
+    order = [1, 2, 0]
+    o2, b2 = W.csr_take(np.array(off, np.int32), np.array(blk, np.int32), order)
+    rc, m2 = ora.swap_out_delta([rid[i] for i in order], o2, b2, [tok[i] for i in order], budget=5)
+    assert rc == ko.OK and m2.tolist() == [4, 1, 0]
+    assert np.array_equal(a.staging, b.staging)
+    for r in rid:
+        assert ora.query(r) == lib.query(r)
+    # an interval shorter than the fixed cost: nothing moves, nothing changes
+    rc, moved, used = lib.kp.swap_out_delta_timed(rid, off, blk, tok, prio, 10.0)
+    assert rc == kv.KV_OK and used == 0 and not moved.any()
+    for r in rid:
+        assert ora.query(r) == lib.query(r)
+    # no priorities: call order; a long interval moves everything that is full
+    rc, moved, used = lib.kp.swap_out_delta_timed(rid, off, blk, tok, None, 1e6)
+    assert rc == kv.KV_OK and moved.tolist() == [4, 0, 3] and used > 1000
+    # errors pass through unchanged
+    rc, _, _ = lib.kp.swap_out_delta_timed(rid, off, [999] * 13, tok, prio, 100.0)
+    assert rc == kv.KV_ERANGE
+    rc, _, _ = lib.kp.swap_out_delta_timed(rid, off, blk, tok, prio, -1.0)
+    assert rc == kv.KV_EINVAL
