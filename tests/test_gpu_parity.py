@@ -166,6 +166,45 @@ def test_small_chunk_groups(gpu, path, unroll):
              tune=tune)
 
 
+@pytest.mark.parametrize("path", list(PATHS))
+def test_limits_whole_pool_and_full_arena(gpu, path):
+    """Edges: one request owning EVERY block of the pool (ids 0 and N-1 included), an arena with
+    exactly as many slots as blocks, a one-token request, a zero-token request, an empty call; the
+    whole pool comes back permuted through a swap-in issued with no sync after the swap-out."""
+    g = W.Geometry(3, 2, 64, 8, "bf16", 257)                  # chunk 2 KiB (small-chunk groups), odd block count
+    seed = 0x11A17
+    a = HostPool(g, seed, slots=g.N)
+    b = HostPool(g, seed, slots=g.N)
+    ora = a.oracle()
+    gpuad = GpuAdapter(b, PATHS[path], bounce_slots=7)
+    kp = gpuad.kp
+    rng = np.random.default_rng(9)
+    table = rng.permutation(g.N).astype(np.int32)
+    dest = rng.permutation(g.N).astype(np.int32)
+    lens = [(g.N - 1) * g.B - 5, 1, 0]                        # 256 blocks (ragged tail), 1 block, 0 blocks
+    off = [0, g.N - 1, g.N, g.N]
+    rid = [1, 2, 3]
+    for o, OK in ((ora, ko.OK), (None, kv.KV_OK)):
+        if o is None:
+            gpuad._push()
+            assert kp.swap_out([], [0], [], []) == OK         # empty call
+            assert kp.swap_out(rid, off, table, lens) == OK
+            assert kp.swap_in(rid, off, dest) == OK           # no sync: ordered inside the library
+            gpuad._pull()
+        else:
+            assert o.swap_out([], [0], [], []) == OK
+            assert o.swap_out(rid, off, table, lens) == OK
+            assert o.swap_in(rid, off, dest) == OK
+    assert np.array_equal(a.staging, b.staging)
+    assert np.array_equal(a.pool, b.pool)
+    # the arena was exactly full: one more block does not fit, and says so before doing anything
+    assert gpuad.swap_out([1], [0, g.N], table, [g.N * g.B]) == kv.KV_OK
+    assert ora.swap_out([1], [0, g.N], table, [g.N * g.B]) == ko.OK
+    assert gpuad.swap_out([9], [0, 1], [0], [1]) == kv.KV_ENOSPC and ora.swap_out([9], [0, 1], [0], [1]) == ko.ENOSPC
+    assert np.array_equal(a.staging, b.staging)
+    gpuad.close()
+
+
 def test_back_to_back_without_sync(gpu):
     """Stream ordering: swap-out then swap-in of the same requests with no kv_sync in between;
     then a second swap-out that reuses the slots the first swap-in is still reading."""
