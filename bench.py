@@ -34,9 +34,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
 # HBM bytes per on-device launch of the default workload, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs of this script (summary and scale factors: profiles/kv_move_kernel_llama8b_burst64.md):
-# (18 602 598 + 18 601 986) KiB for the scatter, against 2 x 18 601 984 KiB algorithmic.
-MEASURED_TRAFFIC = {("configs[1]", 9083, "scatter"): (18602598 + 18601986) * 1024,
-                    ("configs[1]", 9083, "gather"): (18602592 + 18601984) * 1024}
+# (18 602 475 + 18 601 121) KiB for the scatter, against 2 x 18 601 984 KiB algorithmic.
+MEASURED_TRAFFIC = {("configs[1]", 9083, "scatter"): (18602475 + 18601121) * 1024,
+                    ("configs[1]", 9083, "gather"): (18606473 + 18601121) * 1024}
 
 
 def pct(xs, q):
@@ -294,13 +294,13 @@ def main():
                  "measured_peak_h2d_gbps": round(link_h2d, 2),
                  "kernel_out_ms": round(m["out_k"], 2), "kernel_in_ms": round(m["in_k"], 2),
                  "how": "one 1 GiB contiguous pinned hipMemcpyAsync per direction, in this run"},
-        "roofline": {"bound": "hbm", "kernel": "kv_move_kernel<1,U,false> (scatter, both ends in HBM)",
+        "roofline": {"bound": "hbm", "kernel": "kv_move_kernel<1,1,0> (scatter, both ends in HBM)",
                      "achieved": round(scatter_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(scatter_gbs / HBM_PEAK_GBS, 4),
                      "traffic": MEASURED_TRAFFIC.get(("configs[1]", total, "scatter")) if not args.blocks else None,
                      "launch_ms": round(scatter_ms, 3), "bytes_per_launch": 2 * P,
                      "measured_copy_ceiling_gbps": None if copy_gbs is None else round(copy_gbs, 1)},
-        "roofline_gather": {"bound": "hbm", "kernel": "kv_move_kernel<0,U,false> (gather, both ends in HBM)",
+        "roofline_gather": {"bound": "hbm", "kernel": "kv_move_kernel<0,1,0> (gather, both ends in HBM)",
                             "achieved": round(gather_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                             "frac": round(gather_gbs / HBM_PEAK_GBS, 4),
                             "traffic": MEASURED_TRAFFIC.get(("configs[1]", total, "gather")) if not args.blocks else None,

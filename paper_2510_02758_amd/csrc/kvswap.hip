@@ -285,31 +285,34 @@ int ring_reserve(kv_pool* p, size_t n, uint64_t seq, size_t* at) {
   return KV_OK;
 }
 
-template <int MODE, bool LINK>
+template <int MODE, int KIND>
 void launch_move_u(int u, int grid, hipStream_t st, const MoveArgs& a) {
   const size_t lds = a.scale_lds ? (size_t)a.scale_words * 4 : 0;
   switch (u) {
     case 1:
-      hipLaunchKernelGGL((kv_move_kernel<MODE, 1, LINK>), dim3(grid), dim3(256), lds, st, a);
+      hipLaunchKernelGGL((kv_move_kernel<MODE, 1, KIND>), dim3(grid), dim3(256), lds, st, a);
       break;
     case 2:
-      hipLaunchKernelGGL((kv_move_kernel<MODE, 2, LINK>), dim3(grid), dim3(256), lds, st, a);
+      hipLaunchKernelGGL((kv_move_kernel<MODE, 2, KIND>), dim3(grid), dim3(256), lds, st, a);
       break;
     case 8:
-      hipLaunchKernelGGL((kv_move_kernel<MODE, 8, LINK>), dim3(grid), dim3(256), lds, st, a);
+      hipLaunchKernelGGL((kv_move_kernel<MODE, 8, KIND>), dim3(grid), dim3(256), lds, st, a);
       break;
     default:
-      hipLaunchKernelGGL((kv_move_kernel<MODE, 4, LINK>), dim3(grid), dim3(256), lds, st, a);
+      hipLaunchKernelGGL((kv_move_kernel<MODE, 4, KIND>), dim3(grid), dim3(256), lds, st, a);
       break;
   }
 }
 
+// kind: 0 HBM arena, 1 host arena (link-bound), 2 bounce buffer
 template <int MODE>
-void launch_move(int u, int grid, bool link, hipStream_t st, const MoveArgs& a) {
-  if (link)
-    launch_move_u<MODE, true>(u, grid, st, a);
+void launch_move(int u, int grid, int kind, hipStream_t st, const MoveArgs& a) {
+  if (kind == 1)
+    launch_move_u<MODE, 1>(u, grid, st, a);
+  else if (kind == 2)
+    launch_move_u<MODE, 2>(u, grid, st, a);
   else
-    launch_move_u<MODE, false>(u, grid, st, a);
+    launch_move_u<MODE, 0>(u, grid, st, a);
 }
 
 // Loads in flight per lane.  Both ends in HBM: one 16-byte load per lane and one workgroup per
@@ -327,8 +330,9 @@ int pick_unroll(const kv_pool* p, bool link) {
 
 // Upload n descriptors and launch one data kernel over them on stream `st`.
 // mode 0 gather, 1 scatter, 2 move.  `contig` is the contiguous side.
-int enqueue_kernel(kv_pool* p, Call& call, int mode, const Desc* desc, size_t n, char* contig, bool link) {
+int enqueue_kernel(kv_pool* p, Call& call, int mode, const Desc* desc, size_t n, char* contig, int kind) {
   if (n == 0) return KV_OK;
+  const bool link = kind == 1;
   hipStream_t st = p->stream[call.stream];
   size_t at = 0;
   int rc = ring_reserve(p, n, call.seq, &at);
@@ -383,11 +387,11 @@ int enqueue_kernel(kv_pool* p, Call& call, int mode, const Desc* desc, size_t n,
   if ((rc = get_event(p, &k0)) || (rc = get_event(p, &k1))) return rc;
   HIPCHK(p, hipEventRecord(k0, st));
   if (mode == 0)
-    launch_move<0>(u, grid, link, st, a);
+    launch_move<0>(u, grid, kind, st, a);
   else if (mode == 1)
-    launch_move<1>(u, grid, link, st, a);
+    launch_move<1>(u, grid, kind, st, a);
   else
-    launch_move_u<2, false>(u, grid, st, a);
+    launch_move_u<2, 0>(u, grid, st, a);
   HIPCHK(p, hipGetLastError());
   HIPCHK(p, hipEventRecord(k1, st));
   call.kev.push_back({k0, k1});
@@ -449,7 +453,7 @@ int enqueue_transfer(kv_pool* p, Call& call, const Plan& plan, bool out) {
   for (size_t sg = 0; sg < seg_end.size(); sg++) {
     const size_t s1 = seg_end[sg];
     if (!dma) {
-      int rc = enqueue_kernel(p, call, out ? 0 : 1, desc.data() + s0, s1 - s0, p->arena_dev, !p->dev_staging);
+      int rc = enqueue_kernel(p, call, out ? 0 : 1, desc.data() + s0, s1 - s0, p->arena_dev, p->dev_staging ? 0 : 1);
       if (rc) return rc;
     } else {
       for (size_t a0 = s0; a0 < s1; a0 += (size_t)slice) {
@@ -457,7 +461,7 @@ int enqueue_transfer(kv_pool* p, Call& call, const Plan& plan, bool out) {
         kd.resize(a1 - a0);
         for (size_t i = a0; i < a1; i++) kd[i - a0] = {desc[i].a, (int32_t)(i - a0)};
         if (out) {
-          int rc = enqueue_kernel(p, call, 0, kd.data(), kd.size(), bounce, false);
+          int rc = enqueue_kernel(p, call, 0, kd.data(), kd.size(), bounce, 2);
           if (rc) return rc;
         }
         // one copy per run of consecutive staging slots
@@ -475,7 +479,7 @@ int enqueue_transfer(kv_pool* p, Call& call, const Plan& plan, bool out) {
           i = j;
         }
         if (!out) {
-          int rc = enqueue_kernel(p, call, 1, kd.data(), kd.size(), bounce, false);
+          int rc = enqueue_kernel(p, call, 1, kd.data(), kd.size(), bounce, 2);
           if (rc) return rc;
         }
       }
@@ -886,7 +890,7 @@ int kv_move_blocks(kv_pool* p, int64_t n, const int32_t* src_ids, const int32_t*
   if (rc) return rc;
   fill_plan_stats(p, &c->st, 4, plan.desc.size(), t1 - t0);
   c->st.path = KV_PATH_ZEROCOPY;
-  rc = enqueue_kernel(p, *c, 2, plan.desc.data(), plan.desc.size(), nullptr, false);
+  rc = enqueue_kernel(p, *c, 2, plan.desc.data(), plan.desc.size(), nullptr, 0);
   if (rc) return rc;
   mark_blocks(p, *c, 2, plan.desc.data(), plan.desc.size(), -1);
   rc = close_call(p, *c);
