@@ -80,7 +80,7 @@ def main():
     ap.add_argument("--steps", type=int, default=8)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--path", choices=["auto", "zerocopy", "dma"], default="auto")
-    ap.add_argument("--cpu-sample", type=int, default=16, help="requests the CPU oracle is timed on (0: skip)")
+    ap.add_argument("--cpu-sample", type=int, default=40, help="requests the CPU oracle is timed on (0: skip)")
     ap.add_argument("--blocks", type=int, default=0, help="override the pool size (debugging on small boxes)")
     args = ap.parse_args()
     if args.gpus != 1:
