@@ -189,6 +189,18 @@ def main():
     elapsed = t1 - t0
     path_used = {kv.KV_PATH_DMA: "dma", kv.KV_PATH_ZEROCOPY: "zerocopy"}
 
+    # ---- the on-device kernels back to back (inside a step they run once, right after ~0.7 s of
+    # link-bound work, and their first launch is ~8 % slower than the following ones) ----
+    steady = []
+    for rep in range(4):
+        ok(kd.swap_out(rid, off, new, lens), "kv_swap_out(device arena)")
+        go = kd.stats()
+        ok(kd.swap_in(rid, off, ids), "kv_swap_in(device arena)")
+        gi = kd.stats()
+        ok(kd.sync(), "kv_sync")
+        if rep:
+            steady.append((go["ms_kernel"], gi["ms_kernel"]))
+
     # ---- check that nothing was skipped: the pool is back where it started ----
     # (block new[j] holds what block ids[j] was filled with; untouched blocks hold their own fill)
     rng = np.random.default_rng(1)
@@ -276,6 +288,9 @@ def main():
             "delta_gbps": round(Pd / m["delta"] / 1e9, 2),
             "ondevice_payload_gbps": round(2 * P / m["dev"] / 1e9, 1),
             "ondevice_gather_traffic_gbps": round(gather_gbs, 1), "ondevice_scatter_traffic_gbps": round(scatter_gbs, 1),
+            "ondevice_back_to_back_traffic_gbps": {
+                "gather": round(2 * P / float(np.mean([x[0] for x in steady])) / 1e6, 1),
+                "scatter": round(2 * P / float(np.mean([x[1] for x in steady])) / 1e6, 1)},
             "plan_us_burst": round(m["plan_us"], 1),
             "burst_preempt_ms_per_request": round(m["out"] * 1e3 / n, 3),
             "burst_resume_ms_per_request": round(m["in"] * 1e3 / n, 3),
