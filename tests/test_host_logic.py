@@ -21,14 +21,18 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_library_exports_every_declared_symbol():
-    hdr = open(os.path.join(ROOT, "include", "kvswap.h")).read()
-    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    declared = set(re.findall(r"\b(kv_[a-z_]+)\s*\(", hdr))
-    assert {"kv_pool_create", "kv_swap_out", "kv_swap_out_delta", "kv_swap_in", "kv_sync"} <= declared
+    from paper_2510_02758_amd import kvsched as ks
     lib = ctypes.CDLL(kv.LIB_PATH)
-    for name in sorted(declared):
-        assert hasattr(lib, name), "libkvswap.so does not export %s" % name
-    assert set(kv.EXPORTS) == declared
+    for header, exports in (("kvswap.h", kv.EXPORTS), ("kvsched.h", ks.EXPORTS)):
+        hdr = open(os.path.join(ROOT, "include", header)).read()
+        hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+        declared = set(re.findall(r"\b(kv_[a-z_0-9]+)\s*\(", hdr))
+        assert declared, header
+        for name in sorted(declared):
+            assert hasattr(lib, name), "libkvswap.so does not export %s" % name
+        assert set(exports) == declared, header
+    assert {"kv_pool_create", "kv_swap_out", "kv_swap_out_delta", "kv_swap_in", "kv_sync"} <= set(kv.EXPORTS)
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["kvsched.h", "kvswap.h"]
 
 
 def test_status_codes_match_header():
