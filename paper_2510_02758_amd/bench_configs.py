@@ -17,6 +17,10 @@ requests spread over all host cores, one oracle instance per thread.
      through HBM on another stream.
   6  load-evict overlap (paper Section 5.3) on the 8B shape: 32 requests evicted while 32
      others are loaded, serial (sync in between) against both streams at once.
+  7  the scheduler: microseconds per kv_sched_step for 64 / 256 / 1024 requests (the paper
+     reports ~0.4 ms per scheduling call for its Python scheduler, Section 7.5), and a simulated
+     burst (Section 7.3 shape: 80 requests, long inputs and outputs) served with real KV
+     blocks on the GPU under the buffer-aware policy and under run-to-completion FCFS.
 """
 import argparse
 import json
@@ -441,9 +445,56 @@ def config6(kv, W, torch, dev, args):
     return res
 
 
+def config7(kv, W, torch, dev, args):
+    from paper_2510_02758_amd import kvsched as ks
+    from paper_2510_02758_amd import sim as S
+    rng = np.random.default_rng(7)
+    calls = {}
+    for n in (64, 256, 1024):
+        reqs = [dict(state=int(rng.integers(0, 3)), arrival=float(rng.uniform(0, 10)), rate=float(rng.choice([15.0, 20.0])),
+                     buffer=float(rng.integers(0, 300)), blocks=int(rng.integers(32, 256)), dirty_blocks=int(rng.integers(0, 4)),
+                     tokens=int(rng.integers(512, 4096))) for _ in range(n)]
+        for r in reqs:
+            if r["state"] == ks.KVS_NEW:
+                r["buffer"] = 0.0
+        cfg = ks.make_config(mem_blocks=20000, ws_blocks=200000, max_running=64, interval=1.0, gen_rate=40.0, capacity=1e9,
+                             gamma=1.0, safety=1.5, w_adjust=0.0, t_critical=1.0, tau_schedule=5e-4, weight_tau=100.0,
+                             weight_alpha=0.01, evict_gbps=55.0, load_gbps=55.0, io_fixed=5e-5, evict_queue=0.0,
+                             load_queue=0.0, block_bytes=float(2 << 20), prefill_per_token=2e-5)
+        arr = (ks.kv_sched_req * n)()
+        for i, r in enumerate(reqs):
+            for k, _ in ks.kv_sched_req._fields_:
+                setattr(arr[i], k, r[k])
+        out = (ks.kv_sched_out * n)()
+        import ctypes as C
+        mode = C.c_int32()
+        reps = 200
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            ks._lib.kv_sched_step(C.byref(cfg), n, C.cast(arr, C.c_void_p), C.cast(out, C.c_void_p), C.byref(mode))
+        calls[str(n)] = round((time.perf_counter() - t0) / reps * 1e6, 1)
+    # a burst in the shape of the paper's setup (b): 80 requests, ~1024-token inputs, ~2048-token outputs
+    g = W.Geometry(32, 8, 128, 16, "bf16", 6000)                      # 8B-shaped blocks (2 MiB), 11.7 GiB pool
+    res = {"config": 7, "sched_step_us": calls,
+           "paper_context": "Section 7.5 reports ~0.4 ms per scheduling call for the Python implementation"}
+    pool = torch.empty(g.pool_bytes, dtype=torch.uint8, device=dev)
+    staging = torch.empty(16000 * g.S, dtype=torch.uint8, pin_memory=True)
+    for policy in ("tokenflow", "fcfs"):
+        cfg = S.SimConfig(geom=g, gpu_blocks=g.N, arena_blocks=16000, max_running=24, interval=1.0, policy=policy,
+                          step_base=0.020, step_per_req=0.0004, prefill_per_token=2e-5)
+        reqs = S.burst_requests(80, 80, prompt_mean=1024, out_mean=2048, rates=(15.0, 20.0))
+        sim = S.Simulator(cfg, reqs, pool=pool, staging=staging, seed=9)
+        t0 = time.perf_counter()
+        out = sim.run(max_time=4000.0)
+        out["wall_s"] = round(time.perf_counter() - t0, 1)
+        res[policy] = out
+        sim.close()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--config", type=int, required=True, choices=[1, 3, 4, 5, 6])
+    ap.add_argument("--config", type=int, required=True, choices=[1, 3, 4, 5, 6, 7])
     ap.add_argument("--max-waves", type=int, default=4)
     args = ap.parse_args()
     import torch
@@ -451,7 +502,7 @@ def main():
     from paper_2510_02758_amd import workloads as W
     assert torch.cuda.is_available(), "needs a GPU"
     dev = torch.device("cuda:0")
-    fn = {1: config1, 3: config3, 4: config4, 5: config5, 6: config6}[args.config]
+    fn = {1: config1, 3: config3, 4: config4, 5: config5, 6: config6, 7: config7}[args.config]
     print(json.dumps(fn(kv, W, torch, dev, args)))
 
 
