@@ -485,7 +485,15 @@ def config7(kv, W, torch, dev, args):
         reqs = S.burst_requests(80, 80, prompt_mean=1024, out_mean=2048, rates=(15.0, 20.0))
         sim = S.Simulator(cfg, reqs, pool=pool, staging=staging, seed=9)
         t0 = time.perf_counter()
-        out = sim.run(max_time=4000.0)
+        last = [t0]
+
+        def progress(sm):
+            if time.perf_counter() - last[0] > 20:
+                last[0] = time.perf_counter()
+                print("[%s] simulated %.0f s, %d requests done" % (policy, sm.t, sum(r.state == "done" for r in sm.reqs)),
+                      file=sys.stderr, flush=True)
+
+        out = sim.run(max_time=4000.0, progress=progress)
         out["wall_s"] = round(time.perf_counter() - t0, 1)
         res[policy] = out
         sim.close()

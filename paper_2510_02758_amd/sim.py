@@ -88,37 +88,39 @@ class Simulator:
     def _pattern_offset(self, rid, j):
         return ((rid << 20) + j) * self.g.block_bytes
 
-    def _fill(self, r, j, blk):
-        if not self.real:
-            return
-        ls, ks_, bs = self.g.strides
-        words = self.g.chunk // 8
+    def _pattern(self, rid, j0, n):
+        """Pattern of logical blocks j0..j0+n of request rid as a [L, 2, n, chunk] uint8 tensor."""
         import torch
-        base = self._pattern_offset(r.rid, j) // 8
-        col = torch.arange(words, dtype=torch.int64, device=self.pool.device)
-        for l in range(self.g.L):
-            for c in range(2):
-                off = l * ls + c * ks_ + blk * bs
-                w = base + (2 * l + c) * words + col
-                self.pool[off:off + self.g.chunk] = W.fill_words_torch(self.seed, w, self.g.dtype).reshape(-1)
+        g = self.g
+        words = g.chunk // 8
+        dev = self.pool.device
+        base = torch.tensor([self._pattern_offset(rid, j0 + k) // 8 for k in range(n)], dtype=torch.int64, device=dev)
+        plane = torch.arange(2 * g.L, dtype=torch.int64, device=dev) * words
+        col = torch.arange(words, dtype=torch.int64, device=dev)
+        w = base[None, :, None] + plane[:, None, None] + col[None, None, :]          # [2L, n, words]
+        return W.fill_words_torch(self.seed, w, g.dtype).reshape(g.L, 2, n, g.chunk)
+
+    def _poolv(self):
+        g = self.g
+        return self.pool[: g.pool_bytes].view(g.L, 2, g.N, g.chunk)                  # layer-major pool
+
+    def _fill_blocks(self, r, j0, blks):
+        if not self.real or not blks:
+            return
+        import torch
+        idx = torch.tensor(blks, dtype=torch.int64, device=self.pool.device)
+        self._poolv().index_copy_(2, idx, self._pattern(r.rid, j0, len(blks)))
+
+    def _fill(self, r, j, blk):
+        self._fill_blocks(r, j, [blk])
 
     def check_request(self, r):
         """True when every device block of r holds the pattern of its logical index."""
-        if not self.real:
+        if not self.real or not r.table:
             return True
         import torch
-        ls, ks_, bs = self.g.strides
-        words = self.g.chunk // 8
-        col = torch.arange(words, dtype=torch.int64, device=self.pool.device)
-        for j, blk in enumerate(r.table):
-            base = self._pattern_offset(r.rid, j) // 8
-            for l in range(self.g.L):
-                for c in range(2):
-                    off = l * ls + c * ks_ + blk * bs
-                    want = W.fill_words_torch(self.seed, base + (2 * l + c) * words + col, self.g.dtype).reshape(-1)
-                    if not torch.equal(self.pool[off:off + self.g.chunk], want):
-                        return False
-        return True
+        idx = torch.tensor(r.table, dtype=torch.int64, device=self.pool.device)
+        return bool(torch.equal(self._poolv().index_select(2, idx), self._pattern(r.rid, 0, len(r.table))))
 
     # ---- helpers ----
     def _ctx(self, r):
@@ -130,12 +132,14 @@ class Simulator:
     def _grow(self, r):
         """Give r the blocks its context needs; False if the pool is out of blocks."""
         need = self._blocks_needed(r)
+        j0, fresh = len(r.table), []
         while len(r.table) < need:
             if not self.free:
+                self._fill_blocks(r, j0, fresh)
                 return False
-            blk = self.free.pop()
-            self._fill(r, len(r.table), blk)
-            r.table.append(blk)
+            fresh.append(self.free.pop())
+            r.table.append(fresh[-1])
+        self._fill_blocks(r, j0, fresh)
         return True
 
     def _buffer(self, r):
@@ -145,6 +149,17 @@ class Simulator:
         rc, m = ks.kv_metric_stream(r.t_gen, r.arrival, r.rate)
         read = int(np.searchsorted(m["t_read"], self.t, side="right"))
         return float(len(r.t_gen) - read)
+
+    def _produced(self):
+        """Event after everything the "model" (torch, current stream) has written into the pool so far:
+        swap-outs must wait for it, exactly as they wait for the decode kernels in a real server."""
+        if not self.real:
+            return None
+        import torch
+        ev = torch.cuda.Event()
+        ev.record()
+        self._events = getattr(self, "_events", [])[-64:] + [ev]     # keep them alive until they have fired
+        return ev.cuda_event
 
     def _xfer_time(self, blocks):
         return self.cfg.io_fixed + blocks * self.g.S / (self.cfg.link_gbps * 1e9) if blocks else 0.0
@@ -167,18 +182,20 @@ class Simulator:
         off, ids = self._tables(rs)
         lens = [self._ctx(r) for r in rs]
         prio = [self._buffer(r) for r in rs]
-        rc, moved, used = self.kp.swap_out_delta_timed([r.rid for r in rs], off, ids, lens, prio, dt * 1e6)
+        rc, moved, used = self.kp.swap_out_delta_timed([r.rid for r in rs], off, ids, lens, prio, dt * 1e6,
+                                                       wait_event=self._produced())
         self._ok(rc, "kv_swap_out_delta_timed")
         self.moved_blocks["write_through"] += int(moved.sum())
 
     def _preempt(self, r):
         off, ids = self._tables([r])
         if self.cfg.write_through:
-            rc, moved = self.kp.swap_out_delta([r.rid], off, ids, [self._ctx(r)], flags=kv.KV_DELTA_INCLUDE_TAIL)
+            rc, moved = self.kp.swap_out_delta([r.rid], off, ids, [self._ctx(r)], flags=kv.KV_DELTA_INCLUDE_TAIL,
+                                               wait_event=self._produced())
             self._ok(rc, "kv_swap_out_delta")
             n = int(moved.sum())
         else:
-            self._ok(self.kp.swap_out([r.rid], off, ids, [self._ctx(r)]), "kv_swap_out")
+            self._ok(self.kp.swap_out([r.rid], off, ids, [self._ctx(r)], wait_event=self._produced()), "kv_swap_out")
             n = len(ids)
         self._ok(self.kp.sync(), "kv_sync")
         self.moved_blocks["evict"] += n
@@ -195,8 +212,7 @@ class Simulator:
             return None
         r.table = [self.free.pop() for _ in range(nb)]
         if how == ks.KVS_BY_RECOMPUTE:
-            for j, blk in enumerate(r.table):
-                self._fill(r, j, blk)               # the prefill produces the same KV again
+            self._fill_blocks(r, 0, r.table)        # the prefill produces the same KV again
             if not self.cfg.write_through:          # a cold host copy is dropped; a write-through image stays valid
                 self._ok(self.kp.release(r.rid), "kv_req_release")
             cost = self._ctx(r) * self.cfg.prefill_per_token
@@ -287,7 +303,8 @@ class Simulator:
                     n_run += 1
 
     # ---- main loop ----
-    def run(self, max_time=3600.0):
+    def run(self, max_time=3600.0, progress=None):
+        """progress: optional callable(sim) invoked about once per simulated scheduling interval."""
         cfg = self.cfg
         next_sched = 0.0
         pending = list(self.reqs)
@@ -306,9 +323,14 @@ class Simulator:
                 if cfg.policy == "tokenflow":
                     self._schedule_tokenflow(live)
                     next_sched = self.t + cfg.interval
+                    if progress:
+                        progress(self)
                 else:
                     self._schedule_fcfs(live)       # a conventional server looks at its queue every iteration
                     next_sched = self.t
+                    if progress and int(self.t / cfg.interval) != getattr(self, "_tick", -1):
+                        self._tick = int(self.t / cfg.interval)
+                        progress(self)
             running = [r for r in live if r.state == "running" and r.ready_at <= self.t]
             if not running:
                 # nothing can decode: jump to the next thing that can change that

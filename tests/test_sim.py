@@ -76,3 +76,22 @@ def test_sim_moves_real_kv_and_keeps_it_intact(gpu, write_through):
     assert out["finished"] == 16 and out["preemptions"] > 0
     assert out["kv_content_ok"], "a request's KV changed across preempt / resume cycles"
     sim.close()
+
+
+@pytest.mark.gpu
+def test_sim_at_8b_block_size(gpu):
+    """2 MiB blocks (Llama-3-8B shape), 32 requests, dozens of preemptions: large enough for a missing
+    stream dependency between the model's writes and the write-through to show up as wrong bytes."""
+    import torch
+    g = W.Geometry(32, 8, 128, 16, "bf16", 1200)
+    cfg = S.SimConfig(geom=g, gpu_blocks=g.N, arena_blocks=5000, max_running=16, interval=0.5, policy="tokenflow",
+                      prefill_per_token=2e-4)
+    reqs = S.burst_requests(11, 32, prompt_mean=512, out_mean=768, rates=(15.0, 20.0))
+    pool = torch.zeros(g.pool_bytes, dtype=torch.uint8, device=gpu)
+    staging = torch.zeros(cfg.arena_blocks * g.S, dtype=torch.uint8).pin_memory()
+    sim = S.Simulator(cfg, reqs, pool=pool, staging=staging, seed=5)
+    out = sim.run(max_time=4000.0)
+    assert out["finished"] == 32 and out["preemptions"] > 20 and out["blocks_moved"]["load"] > 500, out
+    assert out["kv_content_ok"]
+    assert sorted(sim.free) == list(range(g.N))
+    sim.close()
