@@ -12,8 +12,10 @@ Each function restates, in the order the paper gives them, the rules of
 Where the paper leaves a detail open the reading is the one documented for kv_sched_step.
 
 Parity status: pinned by tests/test_scheduler.py — closed forms for the metrics, hand-computed
-reader traces, and the timeline of the paper's motivating example (Section 4.1), which the
-scheduler must reproduce decision by decision.
+reader traces, exhaustive search over every feasible subset on tiny inputs for the selection, and
+the timeline of the paper's motivating example (Section 4.1), which the scheduler must reproduce
+decision by decision.  tests/test_sched_oracle_mutants.py plants one mistake at a time in a copy of
+this file and requires a pin to notice each.
 """
 import math
 

@@ -216,6 +216,81 @@ def test_adjacent_swap_prefers_the_starving_request():
     assert [o["decision"] for o in out] == [so.KEEP, so.KEEP]     # b keeps running, a stays out
 
 
+def _objective(cfg, reqs, s, overhead=None):
+    """Section 4.2 objective of running subset s for one interval, written out from the formulation: tokens
+    gained by the selected in what the context switch leaves of the interval, gamma * exp(-predicted buffer)
+    charged for every candidate."""
+    j = 0.0
+    for i, r in enumerate(reqs):
+        got = cfg["gen_rate"] * (cfg["interval"] - (overhead[i] if overhead else 0.0)) if i in s else 0.0
+        j += got - cfg["gamma"] * math.exp(-max(r["buffer"] + got - r["rate"] * cfg["interval"], 0.0))
+    return j
+
+
+def _brute_force_best(cfg, reqs):
+    """Exhaustive maximum of the objective over every feasible subset: (subset, value)."""
+    import itertools
+    best, best_j = None, -math.inf
+    for k in range(len(reqs) + 1):
+        for s in itertools.combinations(range(len(reqs)), k):
+            if k > cfg["max_running"] or sum(reqs[i]["blocks"] for i in s) > cfg["mem_blocks"]:
+                continue
+            j = _objective(cfg, reqs, set(s))
+            if j > best_j:
+                best, best_j = set(s), j
+    return best, best_j
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_selection_matches_exhaustive_search_when_greedy_is_optimal(seed):
+    """Equal values and sizes, no overheads, buffers that all outlast the interval: the penalty saved by
+    running a request, exp(-(b - rT)) * (1 - exp(-gT)), falls with its buffer, so the optimum is the k
+    emptiest buffers, which is exactly what the priority order picks first."""
+    rng = np.random.default_rng(400 + seed)
+    n, k = int(rng.integers(3, 9)), int(rng.integers(1, 4))
+    cfg = dict(BASE, mem_blocks=k, max_running=k + int(rng.integers(0, 2)), gamma=float(rng.uniform(0.5, 50)),
+               io_fixed=0.0, t_critical=1e9)
+    buffers = rng.permutation(np.arange(n)) * 0.37 + 25.0                       # distinct, all above rate * interval
+    reqs = [req(int(rng.choice([so.RUNNING, so.PREEMPTED])), 20.0, float(b)) for b in buffers]
+    reqs[0]["state"] = so.PREEMPTED                                             # someone is waiting: the round triggers
+    mode, out = both(cfg, reqs)
+    assert mode == so.BUFFER_AWARE
+    chosen = {i for i, (r, o) in enumerate(zip(reqs, out))
+              if o["decision"] == so.RUN or (r["state"] == so.RUNNING and o["decision"] == so.KEEP)}
+    assert chosen == _brute_force_best(cfg, reqs)[0] == set(np.argsort(buffers)[:k].tolist())
+
+
+def test_swap_pass_reaches_the_exhaustive_optimum_on_two_candidates():
+    """With two candidates and one slot the adjacent-swap pass sees every alternative, so the decision must
+    be the exhaustive optimum whichever of the two greedy took first."""
+    rng = np.random.default_rng(77)
+    flips = 0
+    for _ in range(300):
+        cfg = dict(BASE, mem_blocks=1, max_running=1, gamma=float(rng.uniform(0, 80)), io_fixed=0.0, t_critical=1e9)
+        # buffers of a few tokens around rate * interval keep the two alternatives' objectives well apart
+        reqs = [req(so.RUNNING, float(rng.choice([15.0, 30.0])), float(rng.uniform(10, 40))),
+                req(so.PREEMPTED, float(rng.choice([15.0, 30.0])), float(rng.uniform(10, 40)))]
+        mode, out = both(cfg, reqs)
+        chosen = {i for i, (r, o) in enumerate(zip(reqs, out))
+                  if o["decision"] == so.RUN or (r["state"] == so.RUNNING and o["decision"] == so.KEEP)}
+        assert _objective(cfg, reqs, chosen) >= _brute_force_best(cfg, reqs)[1] - 1e-9
+        flips += chosen != {int(np.argmin([r["buffer"] for r in reqs]))}
+    assert flips > 5            # the pass did overturn greedy's choice in some of them
+
+
+def test_swap_pass_weighs_the_context_switch_cost():
+    """Two full buffers (no starvation either way), one slot: the waiting request would spend half the
+    interval in the load queue, so keeping the running one yields twice the tokens and must win although
+    the waiting one has the (slightly) emptier buffer and is taken first by the priority order."""
+    cfg = dict(BASE, mem_blocks=1, max_running=1, io_fixed=0.0, load_queue=0.5, t_critical=1e9, prefill_per_token=1.0)
+    reqs = [req(so.PREEMPTED, 20.0, 100.0), req(so.RUNNING, 20.0, 101.0)]
+    mode, out = both(cfg, reqs)
+    assert out[0]["t_overhead"] == pytest.approx(0.5, rel=1e-9) and out[0]["how"] == so.BY_LOAD
+    assert [o["decision"] for o in out] == [so.KEEP, so.KEEP]
+    over = [0.5, 0.0]
+    assert _objective(cfg, reqs, {1}, over) > _objective(cfg, reqs, {0}, over)
+
+
 @pytest.mark.parametrize("seed", range(8))
 def test_scheduler_parity_random(seed):
     rng = np.random.default_rng(100 + seed)
@@ -258,3 +333,16 @@ def test_scheduler_rejects_bad_input():
     assert ks.kv_sched_step(bad, [req(so.RUNNING, 20, 1)])[0] == ks.KVS_EINVAL
     cfg.struct_size = 8
     assert ks.kv_sched_step(cfg, [req(so.RUNNING, 20, 1)])[0] == ks.KVS_EINVAL
+
+
+# Pins of the oracle (everything above except the random parity sweeps), for tests/test_sched_oracle_mutants.py.
+PINS = ([(test_token_weight_eq1, ())]
+        + [(test_reader_closed_form_fast_generation, a) for a in [(41.7, 20.3), (40.1, 29.7), (25.3, 24.9), (10.3, 7.1)]]
+        + [(test_reader_closed_form_slow_generation, a) for a in [(10.0, 20.0), (3.0, 4.0)]]
+        + [(test_reader_hand_trace, ()), (test_effective_throughput_thresholds, ()), (test_qos_eq2, ()),
+           (test_motivating_example_timeline, ("oracle",)), (test_idle_when_nothing_waits_and_nothing_is_critical, ()),
+           (test_fcfs_fallback_when_not_schedulable, ()), (test_load_or_recompute, ()),
+           (test_working_set_rule_limits_admission, ()), (test_adjacent_swap_prefers_the_starving_request, ()),
+           (test_swap_pass_reaches_the_exhaustive_optimum_on_two_candidates, ()),
+           (test_swap_pass_weighs_the_context_switch_cost, ())]
+        + [(test_selection_matches_exhaustive_search_when_greedy_is_optimal, (k,)) for k in range(6)])
