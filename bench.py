@@ -82,6 +82,7 @@ def main():
     ap.add_argument("--path", choices=["auto", "zerocopy", "dma"], default="auto")
     ap.add_argument("--cpu-sample", type=int, default=40, help="requests the CPU oracle is timed on (0: skip)")
     ap.add_argument("--blocks", type=int, default=0, help="override the pool size (debugging on small boxes)")
+    ap.add_argument("--variant", type=int, default=0, help="0: the configuration's own seed; 1, 2: further seeds")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is a one-GPU library (no sharding, no collectives); run with --gpus 1",
@@ -94,7 +95,7 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
-    wl = W.config(2, num_blocks=args.blocks or None)
+    wl = W.config(2, num_blocks=args.blocks or None, variant=args.variant)
     g = wl.geom
     lens = W.request_lengths(wl.seed, wl.n_requests, wl.length_dist)
     nb = W.blocks_for(lens, g.B)
@@ -129,6 +130,12 @@ def main():
     scratch = dev_arena[:4 * one] if dev_arena.numel() >= 8 * one else None
     link_d2h = one / kv.kv_bench_link(staging.data_ptr(), dev_arena.data_ptr(), one, 0, 4, evict.cuda_stream) / 1e6
     link_h2d = one / kv.kv_bench_link(staging.data_ptr(), dev_arena.data_ptr(), one, 1, 4, evict.cuda_stream) / 1e6
+    link_bidir = None
+    if staging.numel() >= 2 * one and dev_arena.numel() >= 2 * one:
+        # best of three: which copy engines the runtime picks for the two directions varies from try to try
+        ms = [kv.kv_bench_link_bidir(staging.data_ptr(), dev_arena.data_ptr(), staging.data_ptr() + one,
+                                     dev_arena.data_ptr() + one, one, 3) for _ in range(3)]
+        link_bidir = 2 * one / min(ms) / 1e6 if min(ms) > 0 else None
     copy_gbs = None
     if scratch is not None:
         ms = kv.kv_bench_copy(dev_arena[4 * one:].data_ptr(), scratch.data_ptr(), 4 * one, 1 << 18, 5,
@@ -278,6 +285,7 @@ def main():
         "config": {"workload": "configs[1]: Llama-3-8B-shaped KV bf16 L32 H8 D128 B16, %d-block pool, burst of %d "
                                "requests 512-4096 tokens (%d blocks, %.2f GiB per direction), random block tables"
                                % (g.N, n, total, P / 2**30),
+                   "seed": "0x%X" % wl.seed,
                    "path": path_used.get(sstat["path"], str(sstat["path"])),
                    "value_def": "host-link payload (swap-out + swap-in + write-through delta) per step / step wall "
                                 "time, step = swap-out, swap-in, delta, on-device gather+scatter, release"},
@@ -307,6 +315,7 @@ def main():
                                         "completion event (KV_REQ_EVENTS, one launch per request)"}},
         "link": {"bound": "host-link", "measured_peak_d2h_gbps": round(link_d2h, 2),
                  "measured_peak_h2d_gbps": round(link_h2d, 2),
+                 "measured_peak_bidirectional_gbps": None if link_bidir is None else round(link_bidir, 2),
                  "kernel_out_ms": round(m["out_k"], 2), "kernel_in_ms": round(m["in_k"], 2),
                  "how": "one 1 GiB contiguous pinned hipMemcpyAsync per direction, in this run"},
         "roofline": {"bound": "hbm", "kernel": "kv_move_kernel<1,1,0> (scatter, both ends in HBM)",

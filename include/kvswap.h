@@ -287,6 +287,21 @@ int kv_pool_tune(kv_pool* p, int32_t what, int64_t value);
 int kv_last_hip_error(const kv_pool* p);
 const char* kv_strerror(int code);
 
+/* ------------------------------------------------------------ measurement helpers
+ * Ceilings the swap is compared against (Section 7's bandwidth figures are quoted against the link);
+ * no pool handle needed.  All three are synchronous and return the mean milliseconds per iteration, or
+ * a negative number for bad arguments (-1), a failed HIP resource (-2) or a failed wait (-3).
+ *   kv_bench_copy        contiguous device-to-device copy kernel of `bytes` (multiple of 16 KiB), at most
+ *                        `grid` workgroups, on `stream`: the HBM copy ceiling.
+ *   kv_bench_link        one contiguous hipMemcpyAsync between PINNED host memory and device memory on
+ *                        `stream`; dir 0 device -> host, 1 host -> device: the host-link ceiling.
+ *   kv_bench_link_bidir  both directions at once on two internal streams (dev_a -> host_a while
+ *                        host_b -> dev_b); time until both copies of a pair have finished. */
+double kv_bench_copy(void* dst_dev, const void* src_dev, int64_t bytes, int32_t grid, int32_t iters, void* stream);
+double kv_bench_link(void* host_pinned, void* dev, int64_t bytes, int32_t dir, int32_t iters, void* stream);
+double kv_bench_link_bidir(void* host_a, const void* dev_a, const void* host_b, void* dev_b, int64_t bytes,
+                           int32_t iters);
+
 #ifdef __cplusplus
 }
 #endif

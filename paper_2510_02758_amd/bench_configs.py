@@ -100,7 +100,7 @@ def ok(kv, rc, what):
 
 
 def config1(kv, W, torch, dev, args):
-    wl = W.config(1)
+    wl = W.config(1, variant=args.variant)
     g = wl.geom
     lens = W.request_lengths(wl.seed, wl.n_requests, wl.length_dist)
     off, ids, free = W.block_tables(wl.seed, g.N, W.blocks_for(lens, g.B))
@@ -135,7 +135,7 @@ def config1(kv, W, torch, dev, args):
 
 
 def config3(kv, W, torch, dev, args):
-    wl = W.config(3)
+    wl = W.config(3, variant=args.variant)
     g = wl.geom
     n, steps = wl.n_requests, 64
     lens = W.request_lengths(wl.seed, n, wl.length_dist).astype(np.int64)
@@ -226,7 +226,7 @@ def config3(kv, W, torch, dev, args):
 
 
 def config4(kv, W, torch, dev, args):
-    wl = W.config(4)
+    wl = W.config(4, variant=args.variant)
     g = wl.geom
     lens = W.request_lengths(wl.seed, wl.n_requests, wl.length_dist)
     nb = W.blocks_for(lens, g.B)
@@ -306,7 +306,7 @@ def config4(kv, W, torch, dev, args):
 
 
 def config5(kv, W, torch, dev, args):
-    wl = W.config(5)
+    wl = W.config(5, variant=args.variant)
     g = wl.geom
     lens = W.request_lengths(wl.seed, wl.n_requests, wl.length_dist)
     nb = W.blocks_for(lens, g.B)
@@ -396,7 +396,7 @@ def config5(kv, W, torch, dev, args):
 
 
 def config6(kv, W, torch, dev, args):
-    wl = W.config(2)
+    wl = W.config(2, variant=args.variant)
     g = wl.geom
     lens = W.request_lengths(wl.seed, wl.n_requests, wl.length_dist)
     nb = W.blocks_for(lens, g.B)
@@ -410,9 +410,13 @@ def config6(kv, W, torch, dev, args):
     staging.view(torch.int64)[::512] = 0
     bounce = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
     link = ceilings(kv, torch, staging, dev)
+    one = 1 << 30
+    ms = min(kv.kv_bench_link_bidir(staging.data_ptr(), bounce.data_ptr(), staging.data_ptr() + one,
+                                    bounce.data_ptr() + one, one, 3) for _ in range(3))   # engine choice varies: best of three
     bytes_a, bytes_b = len(ia) * g.S, len(ib) * g.S
     res = {"config": 6, "workload": "8B shape: evict 32 requests (%.1f GiB) while loading 32 others (%.1f GiB)"
-           % (bytes_a / 2**30, bytes_b / 2**30), "measured_link_gbps": {"d2h": link[0], "h2d": link[1]}}
+           % (bytes_a / 2**30, bytes_b / 2**30),
+           "measured_link_gbps": {"d2h": link[0], "h2d": link[1], "both_at_once": round(2 * one / ms / 1e6, 2) if ms > 0 else None}}
     for name, flags, bb in (("zerocopy", kv.KV_PATH_ZEROCOPY, None), ("dma", kv.KV_PATH_DMA, bounce)):
         kp = kv.KVPool(g, pool, staging, bounce=bb, flags=flags)
         serial, both = [], []
@@ -504,6 +508,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--config", type=int, required=True, choices=[1, 3, 4, 5, 6, 7])
     ap.add_argument("--max-waves", type=int, default=4)
+    ap.add_argument("--variant", type=int, default=0, help="0: the configuration's own seed; 1, 2: further seeds")
     args = ap.parse_args()
     import torch
     from paper_2510_02758_amd import kvswap as kv

@@ -1210,4 +1210,36 @@ double kv_bench_link(void* host_pinned, void* dev, int64_t bytes, int32_t dir, i
   return (double)ms / iters;
 }
 
+// Both directions at once: `iters` copies device -> host (dev_a -> host_a) on one stream while as many
+// run host -> device (host_b -> dev_b) on another; the four buffers must not overlap.  Returns the mean
+// milliseconds until BOTH of a pair have finished (host clock around the whole batch), or < 0.
+double kv_bench_link_bidir(void* host_a, const void* dev_a, const void* host_b, void* dev_b, int64_t bytes,
+                           int32_t iters) {
+  if (!host_a || !dev_a || !host_b || !dev_b || bytes <= 0 || iters <= 0) return -1.0;
+  if (!range_ok(dev_a, bytes) || !range_ok(dev_b, bytes) || !range_ok(host_a, bytes) || !range_ok(host_b, bytes))
+    return -1.0;
+  hipStream_t up = nullptr, down = nullptr;
+  if (hipStreamCreateWithFlags(&down, hipStreamNonBlocking) != hipSuccess) return -2.0;
+  if (hipStreamCreateWithFlags(&up, hipStreamNonBlocking) != hipSuccess) {
+    (void)hipStreamDestroy(down);
+    return -2.0;
+  }
+  auto pair = [&]() {
+    (void)hipMemcpyAsync(host_a, dev_a, (size_t)bytes, hipMemcpyDeviceToHost, down);
+    (void)hipMemcpyAsync(dev_b, host_b, (size_t)bytes, hipMemcpyHostToDevice, up);
+  };
+  pair();  // warm-up
+  double ms = -3.0;
+  if (hipStreamSynchronize(down) == hipSuccess && hipStreamSynchronize(up) == hipSuccess) {
+    const auto t0 = std::chrono::steady_clock::now();
+    for (int i = 0; i < iters; i++) pair();
+    const bool ok = hipStreamSynchronize(down) == hipSuccess && hipStreamSynchronize(up) == hipSuccess;
+    const auto t1 = std::chrono::steady_clock::now();
+    if (ok) ms = std::chrono::duration<double, std::milli>(t1 - t0).count() / iters;
+  }
+  (void)hipStreamDestroy(down);
+  (void)hipStreamDestroy(up);
+  return ms;
+}
+
 }  // extern "C"

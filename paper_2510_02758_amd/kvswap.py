@@ -30,7 +30,7 @@ EXPORTS = ["kv_pool_create", "kv_pool_destroy", "kv_swap_out", "kv_swap_out_delt
            "kv_move_blocks", "kv_req_reserve", "kv_req_release", "kv_req_query", "kv_last_stats",
            "kv_slot_bytes", "kv_last_plan", "kv_pool_tune", "kv_last_hip_error", "kv_strerror",
            "kv_io_stats_get", "kv_budget_blocks", "kv_req_poll", "kv_req_wait", "kv_last_timeline",
-           "kv_swap_out_delta_timed"]
+           "kv_swap_out_delta_timed", "kv_bench_copy", "kv_bench_link", "kv_bench_link_bidir"]
 
 
 class kv_pool_config(C.Structure):
@@ -98,6 +98,7 @@ _sig = {
     "kv_budget_blocks": (_i64, [_vp, _i32, C.c_double]),
     "kv_bench_copy": (C.c_double, [_vp, _vp, _i64, _i32, _i32, _vp]),
     "kv_bench_link": (C.c_double, [_vp, _vp, _i64, _i32, _i32, _vp]),
+    "kv_bench_link_bidir": (C.c_double, [_vp, _vp, _vp, _vp, _i64, _i32]),
 }
 for _name, (_res, _args) in _sig.items():
     _f = getattr(_lib, _name)
@@ -269,6 +270,10 @@ def kv_bench_copy(dst_ptr, src_ptr, nbytes, grid, iters, stream=None):
 
 def kv_bench_link(host_ptr, dev_ptr, nbytes, direction, iters, stream=None):
     return _lib.kv_bench_link(host_ptr, dev_ptr, int(nbytes), int(direction), int(iters), stream)
+
+
+def kv_bench_link_bidir(host_a, dev_a, host_b, dev_b, nbytes, iters):
+    return _lib.kv_bench_link_bidir(host_a, dev_a, host_b, dev_b, int(nbytes), int(iters))
 
 
 class KVSwapError(RuntimeError):

@@ -13,6 +13,7 @@ pattern would be a NaN of the KV dtype are folded onto a finite pattern, since
 serving systems never store NaNs in a KV cache; the swap itself is a byte copy
 and never interprets the values.
 """
+import dataclasses
 from dataclasses import dataclass, field
 
 import numpy as np
@@ -99,7 +100,16 @@ class Workload:
 # models and burst sizes in the range of the paper's controlled setups
 # (Section 7.3, Table 2: bursts of 60-400 requests, inputs 512/1024 tokens,
 # outputs 1024-4096 tokens).
-def config(i, num_blocks=None):
+def config(i, num_blocks=None, variant=0):
+    """Configuration i.  variant 0 is the configuration's own seed; variants 1, 2, ... are further seeds
+    of the same recipe (other lengths, other tables, other fill), for run-to-run spread."""
+    wl = _config(i, num_blocks)
+    if variant:
+        wl = dataclasses.replace(wl, seed=wl.seed + (int(variant) << 8), name=wl.name + "/seed+%d" % variant)
+    return wl
+
+
+def _config(i, num_blocks):
     if i == 1:
         g = Geometry(2, 4, 64, 16, "f16", num_blocks or 1024)
         return Workload("tiny-fp16", g, 0x5EED0001, 8, ("uniform", 16, 256), 3)
