@@ -57,6 +57,9 @@
  *     for device blocks (a swap-in is handed blocks an unfinished swap-out or move still reads;
  *     a swap-out or move reads blocks an unfinished swap-in still writes).  Section 5.3 lets
  *     eviction and loading overlap "while maintaining memory safety": this is that guarantee.
+ *     Each segment of a transfer (the whole call without KV_REQ_EVENTS) waits only for the newest
+ *     conflicting segment of the other stream, so a swap-in may be handed the blocks of a request
+ *     whose eviction has just been enqueued and fills them piece by piece behind it.
  *     Work of OTHER streams (the model's compute) is the caller's to order, through wait_event
  *     and kv_sync / kv_req_wait.
  *   - wait_event (nullable) is a hipEvent_t; the call's stream waits for it
@@ -107,7 +110,9 @@ enum {
                              (host-logic tests on machines without a GPU) */
   KV_REQ_EVENTS = 16u     /* cut every call into segments that end on request boundaries (32 MiB or
                              more each, see KV_TUNE_SEGMENT_BYTES) and record an event per segment, so
-                             that each request's completion can be polled, waited for and timed */
+                             that each request's completion can be polled, waited for and timed, and so
+                             that device-block hazards between the two streams are resolved segment by
+                             segment instead of call by call */
 };
 
 /* kv_swap_out_delta flags */
@@ -280,7 +285,10 @@ enum {
   KV_TUNE_KERNEL_VARIANT = 3, /* 0 default; other values select experimental kernels */
   KV_TUNE_DMA_SLICE_BLOCKS = 4, /* blocks per gather+copy slice on the DMA path */
   KV_TUNE_SEGMENT_BYTES = 5,    /* smallest segment under KV_REQ_EVENTS (default 32 MiB) */
-  KV_TUNE_SCALE_LDS = 6         /* scale side band: 0 default (LDS for the scatter), 1 word by word, 2 LDS both ways */
+  KV_TUNE_SCALE_LDS = 6,        /* scale side band: 0 default (LDS for the scatter), 1 word by word, 2 LDS both ways */
+  KV_TUNE_SEGMENT_MAX_BYTES = 7 /* under KV_REQ_EVENTS: also cut a segment inside a long request once it reaches this
+                                   many bytes (0, the default: only at request ends).  Smaller segments let a swap-in
+                                   follow closer behind an eviction whose blocks it reuses, at one launch each */
 };
 int kv_pool_tune(kv_pool* p, int32_t what, int64_t value);
 

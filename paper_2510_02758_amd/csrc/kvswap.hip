@@ -108,6 +108,7 @@ struct kv_pool {
   std::unordered_map<uint64_t, std::pair<uint64_t, int>> req_where;  // request -> (call seq, segment) of its last transfer
   bool req_events = false;
   int64_t segment_bytes = 32ll << 20;
+  int64_t segment_max_bytes = 0;  // > 0: a segment is also cut inside a request once it reaches this size
   std::vector<Desc> last_plan;
   kv_stats plan_stats{};  // figures of a call that enqueued nothing
   bool last_instant = false;
@@ -417,11 +418,16 @@ bool use_dma(const kv_pool* p, size_t blocks) {
 }
 
 void mark_blocks(kv_pool* p, const Call& c, int mode, const Desc* desc, size_t n, int seg);
+hipEvent_t block_hazard(kv_pool* p, int stream, int mode, const Desc* desc, size_t n);
 
 // Move the planned blocks between pool and arena.  out = true: pool -> arena.
 // Under KV_REQ_EVENTS the descriptor list is cut into segments that end where a request ends
-// (each at least segment_bytes long); every segment is launched on its own and followed by an
-// event, so a request is known to be complete while the rest of the burst still moves.
+// (each at least segment_bytes long) and, with segment_max_bytes set, also inside a long request;
+// every segment is launched on its own and followed by an event, so a request is known to be
+// complete while the rest of the burst still moves.  Device-block hazards against the other
+// stream are resolved per segment: a segment waits only for the newest segment of the other
+// stream that touches ITS blocks, which lets a swap-in refill the blocks of a request whose
+// eviction is still in flight, piece by piece behind it (Section 5.3).
 int enqueue_transfer(kv_pool* p, Call& call, const Plan& plan, bool out) {
   const std::vector<Desc>& desc = plan.desc;
   char* arena = (char*)p->cfg.staging_host;
@@ -433,9 +439,16 @@ int enqueue_transfer(kv_pool* p, Call& call, const Plan& plan, bool out) {
   std::vector<size_t> seg_end;
   if (p->req_events) {
     const size_t min_blocks = (size_t)std::max<int64_t>(1, (p->segment_bytes + p->S - 1) / p->S);
+    const size_t max_blocks =
+        p->segment_max_bytes > 0 ? (size_t)std::max<int64_t>(1, p->segment_max_bytes / p->S) : 0;
     size_t begin = 0;
     for (size_t r = 0; r < plan.req_end.size(); r++) {
       const size_t e = plan.req_end[r].second;
+      if (max_blocks)
+        while (e - begin > max_blocks) {
+          begin += max_blocks;
+          seg_end.push_back(begin);
+        }
       if (e - begin >= min_blocks || r + 1 == plan.req_end.size()) {
         seg_end.push_back(e);
         begin = e;
@@ -450,8 +463,14 @@ int enqueue_transfer(kv_pool* p, Call& call, const Plan& plan, bool out) {
   if (dma && p->dma_slice > 0) slice = std::min<int64_t>(slice, p->dma_slice);
   std::vector<Desc> kd;
   size_t s0 = 0, next_req = 0;
+  hipEvent_t waited = nullptr;
   for (size_t sg = 0; sg < seg_end.size(); sg++) {
     const size_t s1 = seg_end[sg];
+    hipEvent_t hazard = block_hazard(p, call.stream, out ? 0 : 1, desc.data() + s0, s1 - s0);
+    if (hazard && hazard != waited) {
+      HIPCHK(p, hipStreamWaitEvent(st, hazard, 0));
+      waited = hazard;
+    }
     if (!dma) {
       int rc = enqueue_kernel(p, call, out ? 0 : 1, desc.data() + s0, s1 - s0, p->arena_dev, p->dev_staging ? 0 : 1);
       if (rc) return rc;
@@ -510,8 +529,8 @@ int enqueue_transfer(kv_pool* p, Call& call, const Plan& plan, bool out) {
 // after unfinished readers and writers of b on the other stream.  Calls of one stream finish in
 // order, so the newest (call, segment) among the conflicting marks is the one event to wait for.
 // mode: 0 gather (reads desc.a), 1 scatter (writes desc.a), 2 move (reads a, writes b).
-hipEvent_t block_hazard(kv_pool* p, int stream, int mode, const std::vector<Desc>& desc) {
-  if (p->blk_reader.empty()) return nullptr;
+hipEvent_t block_hazard(kv_pool* p, int stream, int mode, const Desc* desc, size_t n) {
+  if (p->blk_reader.empty() || n == 0) return nullptr;
   // unfinished calls of the other stream, oldest first
   std::vector<Call*> other;
   for (auto& c : p->calls)
@@ -536,7 +555,8 @@ hipEvent_t block_hazard(kv_pool* p, int stream, int mode, const std::vector<Desc
         return;
       }
   };
-  for (const Desc& d : desc) {
+  for (size_t k = 0; k < n; k++) {
+    const Desc& d = desc[k];
     if (mode == 0) {
       consider(p->blk_writer[(size_t)d.a]);
     } else if (mode == 1) {
@@ -569,12 +589,15 @@ void mark_blocks(kv_pool* p, const Call& c, int mode, const Desc* desc, size_t n
   }
 }
 
-// Open a call record: cross-stream waits, caller's event, start event.
+// Open a call record: cross-stream waits, caller's event, start event.  mode 2 (move) resolves its
+// device-block hazards here, for the whole call; transfers (mode 0 / 1) do it per segment in
+// enqueue_transfer.  Events of unfinished calls are only recycled by retire(), which runs here and
+// nowhere else, so an event block_hazard() returns stays valid until the call is enqueued.
 int open_call(kv_pool* p, int stream, int op, uint64_t wait_seq, void* wait_event, int mode,
               const std::vector<Desc>& desc, Call** out) {
   retire(p);
   p->last_instant = false;
-  hipEvent_t blk_dep = block_hazard(p, stream, mode, desc);  // before any event is taken from the pool
+  hipEvent_t blk_dep = mode == 2 ? block_hazard(p, stream, mode, desc.data(), desc.size()) : nullptr;
   if (blk_dep) HIPCHK(p, hipStreamWaitEvent(p->stream[stream], blk_dep, 0));
   p->calls.emplace_back();
   Call& c = p->calls.back();
@@ -1140,6 +1163,9 @@ int kv_pool_tune(kv_pool* p, int32_t what, int64_t value) {
       return KV_OK;
     case KV_TUNE_SEGMENT_BYTES:
       p->segment_bytes = value ? value : 32ll << 20;
+      return KV_OK;
+    case KV_TUNE_SEGMENT_MAX_BYTES:
+      p->segment_max_bytes = value;
       return KV_OK;
     default:
       return KV_EINVAL;

@@ -24,6 +24,7 @@ KV_KEEP_STAGING = 1
 KV_TUNE_MAX_WGS_DEVICE, KV_TUNE_MAX_WGS_LINK, KV_TUNE_KERNEL_VARIANT, KV_TUNE_DMA_SLICE_BLOCKS = 1, 2, 3, 4
 KV_TUNE_SEGMENT_BYTES = 5
 KV_TUNE_SCALE_LDS = 6
+KV_TUNE_SEGMENT_MAX_BYTES = 7
 KV_F16, KV_BF16, KV_FP8_E4M3 = 0, 1, 2
 
 EXPORTS = ["kv_pool_create", "kv_pool_destroy", "kv_swap_out", "kv_swap_out_delta", "kv_swap_in", "kv_sync",

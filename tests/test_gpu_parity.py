@@ -238,12 +238,20 @@ def test_back_to_back_without_sync(gpu):
     kp.close()
 
 
-@pytest.mark.parametrize("events", [0, kv.KV_REQ_EVENTS])
-def test_device_block_hazards_between_streams(gpu, events):
+@pytest.mark.parametrize("path", ["zerocopy", "dma"])
+@pytest.mark.parametrize("events,seg_max,order", [(0, 0, "reverse"), (kv.KV_REQ_EVENTS, 0, "reverse"),
+                                                  (kv.KV_REQ_EVENTS, 16 << 20, "reverse"), (kv.KV_REQ_EVENTS, 16 << 20, "same"),
+                                                  (kv.KV_REQ_EVENTS, 2 << 20, "same"), (kv.KV_REQ_EVENTS, 16 << 20, "head_first")])
+def test_device_block_hazards_between_streams(gpu, events, seg_max, order, path):
     """The library orders the evict and load streams around DEVICE blocks too: a swap-in may be
     handed blocks that an unfinished swap-out still reads, a swap-out or a move may read blocks an
     unfinished swap-in still writes, all without kv_sync in between.  Expected result: the oracle's,
-    which runs the same calls one after the other."""
+    which runs the same calls one after the other.  With segments cut inside a request (seg_max) the
+    follow-up runs piece by piece behind the call it depends on: in the same block order it trails it
+    by one segment, the narrowest window there is; in the opposite order its first piece needs the
+    other call's last; "head_first" takes the first 8 blocks in the same order and the rest in the opposite
+    one, so the first piece may start at once while the second has to wait for nearly the whole other call:
+    a wait taken only once per call would let it run far too early."""
     import torch
     g = W.Geometry(32, 8, 128, 16, "bf16", 1400)             # 2 MiB blocks, 2.7 GiB pool
     seed = 0xB10CC
@@ -251,7 +259,14 @@ def test_device_block_hazards_between_streams(gpu, events):
     ora = a.oracle()
     pool = torch.from_numpy(a.pool.copy()).cuda()
     staging = torch.full((len(a.staging),), CANARY, dtype=torch.uint8).pin_memory()
-    kp = kv.KVPool(g, pool, staging, flags=kv.KV_PATH_ZEROCOPY | events)
+    if path == "dma":             # slices of 24 blocks through each half of the bounce buffer
+        bounce = torch.zeros(2 * 24 * g.S, dtype=torch.uint8, device="cuda")
+        kp = kv.KVPool(g, pool, staging, bounce=bounce, flags=kv.KV_PATH_DMA | events)
+    else:
+        kp = kv.KVPool(g, pool, staging, flags=kv.KV_PATH_ZEROCOPY | events)
+    if seg_max:
+        assert kp.tune(kv.KV_TUNE_SEGMENT_BYTES, seg_max) == kv.KV_OK
+        assert kp.tune(kv.KV_TUNE_SEGMENT_MAX_BYTES, seg_max) == kv.KV_OK
     perm = np.random.default_rng(4).permutation(g.N).astype(np.int32)
     X, Y, Z = perm[:300], perm[300:600], perm[600:900]
     offA = np.array([0, 100, 300], np.int32)                  # request A = two requests, 100 + 200 blocks
@@ -260,7 +275,13 @@ def test_device_block_hazards_between_streams(gpu, events):
 
     # Each follow-up walks the blocks in the opposite order, so that without ordering the second
     # kernel reaches the far end of the list long before the first one does.
-    Xr, Zr = X[::-1].copy(), Z[::-1].copy()
+    def walk(v):
+        if order == "reverse":
+            return v[::-1].copy()
+        if order == "head_first":
+            return np.concatenate([v[:8], v[8:][::-1]])
+        return v
+    Xr, Zr = walk(X), walk(Z)
 
     def script(o, OK):
         # B's KV lives in blocks Y and is swapped out first
@@ -279,6 +300,39 @@ def test_device_block_hazards_between_streams(gpu, events):
     script(ora, ko.OK)            # the oracle: the same calls, one after the other
     assert np.array_equal(staging.numpy(), a.staging), "staging differs: a gather read blocks too late or too early"
     assert np.array_equal(pool.cpu().numpy(), a.pool), "pool differs: a scatter or move ran too early"
+    kp.close()
+
+
+def test_segments_cut_inside_a_request(gpu):
+    """KV_TUNE_SEGMENT_MAX_BYTES: a long request goes out in pieces of that size (one launch each on the
+    zero-copy path); its completion is that of its last piece; the bytes are the oracle's."""
+    import torch
+    g = W.Geometry(8, 8, 128, 16, "bf16", 400)             # block = 512 KiB
+    a = HostPool(g, 0x5E6, slots=260)
+    ora = a.oracle()
+    pool = torch.from_numpy(a.pool.copy()).cuda()
+    staging = torch.full((len(a.staging),), CANARY, dtype=torch.uint8).pin_memory()
+    kp = kv.KVPool(g, pool, staging, flags=kv.KV_PATH_ZEROCOPY | kv.KV_REQ_EVENTS)
+    assert kp.tune(kv.KV_TUNE_SEGMENT_BYTES, 1 << 20) == kv.KV_OK          # 2 blocks
+    assert kp.tune(kv.KV_TUNE_SEGMENT_MAX_BYTES, 4 << 20) == kv.KV_OK      # 8 blocks
+    perm = np.random.default_rng(8).permutation(g.N).astype(np.int32)
+    off = np.array([0, 1, 101, 104, 204], np.int32)        # 1, 100, 3 and 100 blocks
+    lens = np.array([1, 100, 3, 100], np.int32) * g.B
+    rid = [11, 12, 13, 14]
+    assert kp.swap_out(rid, off, perm[:204], lens) == kv.KV_OK
+    assert kp.req_wait(12) == kv.KV_OK and kp.req_poll(11) == 1            # 11 ended in an earlier piece than 12
+    # pieces of 8 blocks: [0,8) .. [88,96), then [96,101) ends request 12, [101,104) is request 13,
+    # [104,112) .. [192,200), [200,204) ends request 14: 12 + 1 + 1 + 12 + 1
+    assert kp.stats()["launches"] == 27
+    assert kp.sync() == kv.KV_OK
+    ids, done_ms = kp.timeline()
+    assert [int(x) for x in ids] == rid and np.all(np.diff(done_ms) >= 0)
+    assert ora.swap_out(rid, off, perm[:204], lens) == ko.OK
+    assert np.array_equal(staging.numpy(), a.staging)
+    assert kp.swap_in(rid, off, perm[204:408 - 8].tolist() + perm[:8].tolist()) == kv.KV_OK
+    assert kp.sync() == kv.KV_OK
+    assert ora.swap_in(rid, off, np.concatenate([perm[204:400], perm[:8]])) == ko.OK
+    assert np.array_equal(pool.cpu().numpy(), a.pool)
     kp.close()
 
 
