@@ -222,6 +222,33 @@ int kv_req_release(kv_pool* p, uint64_t req_id);
 /* Any out pointer may be NULL.  staging_offset is in bytes from staging_host. */
 int kv_req_query(kv_pool* p, uint64_t req_id, int64_t* staging_offset, int32_t* cap_blocks,
                  int32_t* blocks_staged, int32_t* watermark, int32_t* swapped);
+/* Write queue (Section 5.2: the KV a decode iteration produces is buffered, and after each iteration a
+ * chunk sized to the next compute interval is written out, requests with larger buffers first).
+ * The queue lives in the handle, so the serving loop posts only what changed and drains once per
+ * iteration.
+ *
+ * kv_wq_post    records, for each request, its current block table (CSR as in kv_swap_out_delta), token
+ *               count and priority (NULL: 0), replacing what an earlier post recorded for it.  The
+ *               arrays are copied.  Errors (nothing recorded): KV_EINVAL (a row shorter than the token
+ *               count needs, a request named twice, NaN priority), KV_ERANGE (block id), KV_EEXIST
+ *               (request is swapped out), KV_ESTATE (fewer tokens than already written through).
+ * kv_wq_drain   one kv_swap_out_delta over the queued requests in order of decreasing priority (ties:
+ *               order of posting).  Budget: block_budget > 0: that many blocks; else interval_us > 0:
+ *               kv_budget_blocks(p, 0, interval_us), where 0 means nothing moves; both 0: unlimited.
+ *               flags as kv_swap_out_delta.  blocks_written, blocks_pending (full blocks still not
+ *               written through, over the whole queue) and budget_used are nullable.  A planning error
+ *               (KV_ENOSPC, ...) leaves queue and state unchanged.
+ * kv_wq_remove  forgets a request (KV_ENOENT if it is not queued).  kv_swap_out, kv_swap_in and
+ *               kv_req_release do this for the requests they name: a request's entry must not outlive its
+ *               block table, and a caller that gives up blocks in another way removes or re-posts it.
+ * kv_wq_pending full blocks not yet written through, and the number of requests that have some. */
+int kv_wq_post(kv_pool* p, int32_t n, const uint64_t* req_ids, const int32_t* offsets, const int32_t* block_ids,
+               const int32_t* num_tokens, const double* priority);
+int kv_wq_drain(kv_pool* p, double interval_us, int64_t block_budget, uint32_t flags, int64_t* blocks_written,
+                int64_t* blocks_pending, int64_t* budget_used, void* wait_event);
+int kv_wq_remove(kv_pool* p, uint64_t req_id);
+int kv_wq_pending(kv_pool* p, int64_t* blocks, int32_t* requests);
+
 /* Waits for the most recent swap call to finish, then reports it. */
 int kv_last_stats(kv_pool* p, kv_stats* out);
 /* Bytes of one staging slot (S) for this geometry. */

@@ -109,6 +109,16 @@ struct kv_pool {
   bool req_events = false;
   int64_t segment_bytes = 32ll << 20;
   int64_t segment_max_bytes = 0;  // > 0: a segment is also cut inside a request once it reaches this size
+
+  // write queue (kv_wq_*): the running requests' latest tables, drained in priority order
+  struct WqEntry {
+    std::vector<int32_t> blocks;
+    int32_t tokens = 0;
+    double priority = 0;
+    uint64_t order = 0;  // position in the most recent post: ties keep post order
+  };
+  std::unordered_map<uint64_t, WqEntry> wq;
+  uint64_t wq_order = 0;
   std::vector<Desc> last_plan;
   kv_stats plan_stats{};  // figures of a call that enqueued nothing
   bool last_instant = false;
@@ -839,6 +849,7 @@ int kv_swap_out(kv_pool* p, int32_t n, const uint64_t* req_ids, const int32_t* o
   Plan plan;
   int rc = p->planner.plan_swap_out(n, req_ids, offsets, block_ids, num_tokens, &plan);
   if (rc) return rc;
+  for (int32_t i = 0; i < n; i++) p->wq.erase(req_ids[i]);  // a swapped-out request has nothing left to write through
   return swap_out_common(p, 1, plan, t0, wait_event);
 }
 
@@ -863,6 +874,7 @@ int kv_swap_in(kv_pool* p, int32_t n, const uint64_t* req_ids, const int32_t* of
   Plan plan;
   int rc = p->planner.plan_swap_in(n, req_ids, offsets, new_block_ids, flags, &plan);
   if (rc) return rc;
+  for (int32_t i = 0; i < n; i++) p->wq.erase(req_ids[i]);  // their tables have just changed
   p->last_plan = plan.desc;
   const double t1 = now_us();
   if (p->plan_only) {
@@ -942,6 +954,7 @@ int kv_req_release(kv_pool* p, uint64_t req_id) {
   std::lock_guard<std::mutex> g(p->mu);
   kvswap::Req was;
   int rc = p->planner.release(req_id, &was);
+  if (!rc) p->wq.erase(req_id);
   if (rc || p->plan_only) return rc;
   // the slots may still be in use by unfinished work of either stream: later writers wait for it
   const uint64_t s = std::max(was.in_seq, was.out_seq);
@@ -1115,6 +1128,100 @@ int kv_swap_out_delta_timed(kv_pool* p, int32_t n, const uint64_t* req_ids, cons
   if (rc) return rc;
   if (blocks_moved)
     for (int32_t k = 0; k < n; k++) blocks_moved[order[(size_t)k]] = moved[(size_t)k];
+  return swap_out_common(p, 2, plan, t0, wait_event);
+}
+
+int kv_wq_post(kv_pool* p, int32_t n, const uint64_t* req_ids, const int32_t* offsets, const int32_t* block_ids,
+               const int32_t* num_tokens, const double* priority) {
+  if (!p || n < 0 || (n > 0 && (!req_ids || !offsets || !num_tokens))) return KV_EINVAL;
+  std::lock_guard<std::mutex> g(p->mu);
+  const int64_t B = p->cfg.block_size, N = p->cfg.num_blocks;
+  if (n > 0 && offsets[0] < 0) return KV_EINVAL;
+  for (int32_t i = 0; i < n; i++) {
+    const int64_t row = (int64_t)offsets[i + 1] - offsets[i], len = num_tokens[i];
+    if (row < 0 || len < 0 || row < (len + B - 1) / B) return KV_EINVAL;
+    if (row > 0 && !block_ids) return KV_EINVAL;
+    if (priority && !(priority[i] == priority[i])) return KV_EINVAL;  // NaN has no place in an order
+    for (int32_t j = 0; j < i; j++)
+      if (req_ids[j] == req_ids[i]) return KV_EINVAL;
+    for (int64_t j = offsets[i]; j < offsets[i + 1]; j++)
+      if (block_ids[j] < 0 || block_ids[j] >= N) return KV_ERANGE;
+    const kvswap::Req* r = p->planner.find(req_ids[i]);
+    if (r && r->swapped) return KV_EEXIST;
+    if (r && len < (int64_t)r->wm * B) return KV_ESTATE;
+  }
+  for (int32_t i = 0; i < n; i++) {
+    kv_pool::WqEntry& e = p->wq[req_ids[i]];
+    e.blocks.assign(block_ids + offsets[i], block_ids + offsets[i + 1]);
+    e.tokens = num_tokens[i];
+    e.priority = priority ? priority[i] : 0.0;
+    e.order = ++p->wq_order;
+  }
+  return KV_OK;
+}
+
+int kv_wq_remove(kv_pool* p, uint64_t req_id) {
+  if (!p) return KV_EINVAL;
+  std::lock_guard<std::mutex> g(p->mu);
+  return p->wq.erase(req_id) ? KV_OK : KV_ENOENT;
+}
+
+// Full blocks the queued requests have not written through yet.
+static void wq_count(kv_pool* p, int64_t* blocks, int32_t* requests) {
+  int64_t nb = 0;
+  int32_t nr = 0;
+  for (auto& kvp : p->wq) {
+    const kvswap::Req* r = p->planner.find(kvp.first);
+    const int64_t d = kvp.second.tokens / p->cfg.block_size - (r ? r->wm : 0);
+    if (d > 0) {
+      nb += d;
+      nr++;
+    }
+  }
+  if (blocks) *blocks = nb;
+  if (requests) *requests = nr;
+}
+
+int kv_wq_pending(kv_pool* p, int64_t* blocks, int32_t* requests) {
+  if (!p) return KV_EINVAL;
+  std::lock_guard<std::mutex> g(p->mu);
+  wq_count(p, blocks, requests);
+  return KV_OK;
+}
+
+int kv_wq_drain(kv_pool* p, double interval_us, int64_t block_budget, uint32_t flags, int64_t* blocks_written,
+                int64_t* blocks_pending, int64_t* budget_used, void* wait_event) {
+  if (!p || !(interval_us >= 0) || block_budget < 0) return KV_EINVAL;
+  std::lock_guard<std::mutex> g(p->mu);
+  const double t0 = now_us();
+  const bool timed = block_budget == 0 && interval_us > 0;
+  const int64_t budget = timed ? budget_blocks_locked(p, 0, interval_us) : block_budget;
+  if (budget_used) *budget_used = budget;
+  std::vector<std::pair<uint64_t, const kv_pool::WqEntry*>> order;
+  order.reserve(p->wq.size());
+  for (auto& kvp : p->wq) order.push_back({kvp.first, &kvp.second});
+  std::sort(order.begin(), order.end(), [](const auto& a, const auto& b) {
+    if (a.second->priority != b.second->priority) return a.second->priority > b.second->priority;
+    return a.second->order < b.second->order;
+  });
+  const int32_t n = (int32_t)order.size();
+  std::vector<uint64_t> ids((size_t)n);
+  std::vector<int32_t> off((size_t)n + 1, 0), tok((size_t)n), blk, moved((size_t)n, 0);
+  for (int32_t k = 0; k < n; k++) {
+    const kv_pool::WqEntry& e = *order[(size_t)k].second;
+    ids[(size_t)k] = order[(size_t)k].first;
+    tok[(size_t)k] = e.tokens;
+    blk.insert(blk.end(), e.blocks.begin(), e.blocks.end());
+    off[(size_t)k + 1] = (int32_t)blk.size();
+  }
+  Plan plan;
+  int rc = p->planner.plan_delta(n, ids.data(), off.data(), blk.data(), tok.data(), budget, flags, moved.data(), &plan,
+                                 /*limited_even_if_zero=*/timed);
+  if (rc) return rc;
+  int64_t total = 0;
+  for (int32_t k = 0; k < n; k++) total += moved[(size_t)k];
+  if (blocks_written) *blocks_written = total;
+  wq_count(p, blocks_pending, nullptr);
   return swap_out_common(p, 2, plan, t0, wait_event);
 }
 

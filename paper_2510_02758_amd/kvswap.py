@@ -31,7 +31,8 @@ EXPORTS = ["kv_pool_create", "kv_pool_destroy", "kv_swap_out", "kv_swap_out_delt
            "kv_move_blocks", "kv_req_reserve", "kv_req_release", "kv_req_query", "kv_last_stats",
            "kv_slot_bytes", "kv_last_plan", "kv_pool_tune", "kv_last_hip_error", "kv_strerror",
            "kv_io_stats_get", "kv_budget_blocks", "kv_req_poll", "kv_req_wait", "kv_last_timeline",
-           "kv_swap_out_delta_timed", "kv_bench_copy", "kv_bench_link", "kv_bench_link_bidir"]
+           "kv_swap_out_delta_timed", "kv_bench_copy", "kv_bench_link", "kv_bench_link_bidir",
+           "kv_wq_post", "kv_wq_drain", "kv_wq_remove", "kv_wq_pending"]
 
 
 class kv_pool_config(C.Structure):
@@ -100,6 +101,10 @@ _sig = {
     "kv_bench_copy": (C.c_double, [_vp, _vp, _i64, _i32, _i32, _vp]),
     "kv_bench_link": (C.c_double, [_vp, _vp, _i64, _i32, _i32, _vp]),
     "kv_bench_link_bidir": (C.c_double, [_vp, _vp, _vp, _vp, _i64, _i32]),
+    "kv_wq_post": (C.c_int, [_vp, _i32, _vp, _vp, _vp, _vp, _vp]),
+    "kv_wq_drain": (C.c_int, [_vp, C.c_double, _i64, _u32, _vp, _vp, _vp, _vp]),
+    "kv_wq_remove": (C.c_int, [_vp, _u64]),
+    "kv_wq_pending": (C.c_int, [_vp, _vp, _vp]),
 }
 for _name, (_res, _args) in _sig.items():
     _f = getattr(_lib, _name)
@@ -171,6 +176,33 @@ def kv_swap_out_delta_timed(h, req_ids, offsets, block_ids, num_tokens, priority
     rc = _lib.kv_swap_out_delta_timed(h, len(r), _p(r), _p(o), _p(b), _p(t), _p(pr), float(interval_us), int(flags),
                                       _p(moved), C.byref(used), wait_event)
     return rc, moved, used.value
+
+
+def kv_wq_post(h, req_ids, offsets, block_ids, num_tokens, priority=None):
+    r, o, b, t = _u64a(req_ids), _i32a(offsets), _i32a(block_ids), _i32a(num_tokens)
+    pr = None if priority is None else np.ascontiguousarray(np.asarray(priority, dtype=np.float64))
+    if not _csr_ok(len(r), o, b, t) or (pr is not None and len(pr) != len(r)):
+        return KV_EINVAL
+    return _lib.kv_wq_post(h, len(r), _p(r), _p(o), _p(b), _p(t), _p(pr))
+
+
+def kv_wq_drain(h, interval_us=0.0, block_budget=0, flags=0, wait_event=None):
+    """-> (rc, blocks written, full blocks still pending, budget applied)"""
+    w, pend, used = _i64(0), _i64(0), _i64(0)
+    rc = _lib.kv_wq_drain(h, float(interval_us), int(block_budget), int(flags), C.byref(w), C.byref(pend),
+                          C.byref(used), wait_event)
+    return rc, w.value, pend.value, used.value
+
+
+def kv_wq_remove(h, req_id):
+    return _lib.kv_wq_remove(h, int(req_id))
+
+
+def kv_wq_pending(h):
+    """-> (rc, full blocks not yet written through, requests that have some)"""
+    nb, nr = _i64(0), _i32(0)
+    rc = _lib.kv_wq_pending(h, C.byref(nb), C.byref(nr))
+    return rc, nb.value, nr.value
 
 
 def kv_swap_in(h, req_ids, offsets, new_block_ids, flags=0, wait_event=None):
@@ -342,6 +374,18 @@ class KVPool:
                              wait_event=None):
         return kv_swap_out_delta_timed(self.h, req_ids, offsets, block_ids, num_tokens, priority, interval_us, flags,
                                        wait_event)
+
+    def wq_post(self, req_ids, offsets, block_ids, num_tokens, priority=None):
+        return kv_wq_post(self.h, req_ids, offsets, block_ids, num_tokens, priority)
+
+    def wq_drain(self, interval_us=0.0, block_budget=0, flags=0, wait_event=None):
+        return kv_wq_drain(self.h, interval_us, block_budget, flags, wait_event)
+
+    def wq_remove(self, req_id):
+        return kv_wq_remove(self.h, req_id)
+
+    def wq_pending(self):
+        return kv_wq_pending(self.h)
 
     def swap_in(self, req_ids, offsets, new_block_ids, flags=0, wait_event=None):
         return kv_swap_in(self.h, req_ids, offsets, new_block_ids, flags, wait_event)

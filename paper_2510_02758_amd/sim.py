@@ -179,13 +179,15 @@ class Simulator:
         rs = [r for r in running if r.table]
         if not rs or not self.cfg.write_through:
             return
+        # the handle's write queue: post what this iteration produced (priority = unread buffer, the likelier
+        # victim first), then drain a chunk sized to the next iteration
         off, ids = self._tables(rs)
         lens = [self._ctx(r) for r in rs]
         prio = [self._buffer(r) for r in rs]
-        rc, moved, used = self.kp.swap_out_delta_timed([r.rid for r in rs], off, ids, lens, prio, dt * 1e6,
-                                                       wait_event=self._produced())
-        self._ok(rc, "kv_swap_out_delta_timed")
-        self.moved_blocks["write_through"] += int(moved.sum())
+        self._ok(self.kp.wq_post([r.rid for r in rs], off, ids, lens, prio), "kv_wq_post")
+        rc, wrote, pending, used = self.kp.wq_drain(interval_us=dt * 1e6, wait_event=self._produced())
+        self._ok(rc, "kv_wq_drain")
+        self.moved_blocks["write_through"] += int(wrote)
 
     def _preempt(self, r):
         off, ids = self._tables([r])
@@ -198,6 +200,7 @@ class Simulator:
             self._ok(self.kp.swap_out([r.rid], off, ids, [self._ctx(r)], wait_event=self._produced()), "kv_swap_out")
             n = len(ids)
         self._ok(self.kp.sync(), "kv_sync")
+        self.kp.wq_remove(r.rid)                    # its table is about to be given up (KV_ENOENT if it was not queued)
         self.moved_blocks["evict"] += n
         self.free.extend(reversed(r.table))        # the allocator takes the blocks back
         r.table = []
@@ -248,6 +251,7 @@ class Simulator:
         self.ok_content = getattr(self, "ok_content", True) and self.check_request(r)
         self.free.extend(reversed(r.table))
         r.table = []
+        self.kp.wq_remove(r.rid)
         self.kp.release(r.rid)                      # KV_ENOENT when it never had a host copy
         self.log.append((self.t, "done", r.rid))
 

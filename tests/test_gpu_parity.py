@@ -497,6 +497,67 @@ def test_telemetry_and_time_budget(gpu):
     kp.close()
 
 
+def test_write_queue_on_the_gpu(gpu):
+    """kv_wq_post / kv_wq_drain with real transfers: decode steps post their growth, each drain writes a
+    budgeted chunk in priority order; the arena must equal the oracle's after the same deltas, and a drain
+    sized from an interval must finish inside it."""
+    import torch
+    g = W.Geometry(4, 8, 128, 16, "bf16", 700)              # 256 KiB blocks
+    a = HostPool(g, 0xC0FFEE, slots=640)
+    ora = a.oracle()
+    pool = torch.from_numpy(a.pool.copy()).cuda()
+    staging = torch.full((len(a.staging),), CANARY, dtype=torch.uint8).pin_memory()
+    kp = kv.KVPool(g, pool, staging)
+    rng = np.random.default_rng(12)
+    perm = rng.permutation(g.N).astype(np.int32)
+    rid = [1, 2, 3, 4]
+    tables = {r: perm[150 * i:150 * (i + 1)] for i, r in enumerate(rid)}
+    for r in rid:
+        assert kp.reserve(r, 150) == kv.KV_OK and ora.reserve(r, 150) == ko.OK
+    length = {r: 0 for r in rid}
+    for step in range(12):
+        prio = {}
+        for r in rid:
+            length[r] = min(length[r] + int(rng.integers(1, 12)) * g.B + int(rng.integers(0, g.B)), 150 * g.B)
+            prio[r] = float(rng.integers(0, 3))
+        nb = {r: -(-length[r] // g.B) for r in rid}
+        off = np.concatenate([[0], np.cumsum([nb[r] for r in rid])]).astype(np.int32)
+        blk = np.concatenate([tables[r][:nb[r]] for r in rid])
+        assert kp.wq_post(rid, off, blk, [length[r] for r in rid], [prio[r] for r in rid]) == kv.KV_OK
+        budget = int(rng.integers(1, 30))
+        rc, wrote, pend, used = kp.wq_drain(block_budget=budget)
+        assert rc == kv.KV_OK and used == budget
+        order = sorted(rid, key=lambda r: (-prio[r], rid.index(r)))
+        o2 = np.concatenate([[0], np.cumsum([nb[r] for r in order])]).astype(np.int32)
+        rc, moved = ora.swap_out_delta(order, o2, np.concatenate([tables[r][:nb[r]] for r in order]),
+                                       [length[r] for r in order], budget=budget)
+        assert rc == ko.OK and int(moved.sum()) == wrote
+    rc, wrote, pend, used = kp.wq_drain()                    # flush what is left
+    assert rc == kv.KV_OK and pend == 0
+    rc, moved = ora.swap_out_delta(rid, off, blk, [length[r] for r in rid])
+    assert rc == ko.OK and int(moved.sum()) == wrote
+    assert kp.sync() == kv.KV_OK
+    assert np.array_equal(staging.numpy(), a.staging)
+    for r in rid:
+        assert kp.query(r)[1] == ora.query(r)[1]
+    # a drain sized from an interval: warm the telemetry up, then 2 ms worth of a long request
+    for r in rid:
+        assert kp.release(r) == kv.KV_OK
+    assert kp.wq_pending() == (kv.KV_OK, 0, 0)
+    for it in range(3):
+        assert kp.swap_out([9], [0, 400], perm[:400], [400 * g.B]) == kv.KV_OK
+        assert kp.swap_in([9], [0, 400], perm[:400]) == kv.KV_OK
+    assert kp.sync() == kv.KV_OK
+    assert kp.release(9) == kv.KV_ENOENT                    # the swap-in gave its extent back
+    assert kp.reserve(10, 600) == kv.KV_OK
+    assert kp.wq_post([10], [0, 600], perm[:600], [600 * g.B]) == kv.KV_OK
+    rc, wrote, pend, used = kp.wq_drain(interval_us=2000.0)
+    assert rc == kv.KV_OK and wrote == used and 200 < used < 500 and pend == 600 - used   # ~55 GB/s * 2 ms / 256 KiB
+    assert kp.sync() == kv.KV_OK
+    assert kp.stats()["ms_total"] < 1.25 * 2.0
+    kp.close()
+
+
 def test_create_checks_memory_kinds(gpu):
     import torch
     g = W.Geometry(2, 4, 64, 16, "f16", 64)

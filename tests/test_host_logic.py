@@ -255,3 +255,133 @@ def test_timed_delta_orders_by_priority_and_applies_the_budget():
     assert rc == kv.KV_ERANGE
     rc, _, _ = lib.kp.swap_out_delta_timed(rid, off, blk, tok, prio, -1.0)
     assert rc == kv.KV_EINVAL
+
+
+# ------------------------------------------------------------------ write queue (Section 5.2)
+def test_write_queue_drains_by_priority_under_a_budget():
+    """kv_wq_post + kv_wq_drain is one kv_swap_out_delta over the queued requests in priority order:
+    the oracle, handed that order and that budget, must reach the same bytes and the same request state."""
+    g = W.Geometry(1, 1, 8, 2, "f16", 64)
+    a, b = HostPool(g, 6, slots=24), HostPool(g, 6, slots=24)
+    ora, lib = a.oracle(), PlanOnlyAdapter(b)
+    kp = lib.kp
+    rid, off, blk, tok = [10, 11, 12], [0, 4, 8, 13], list(range(20, 33)), [8, 8, 9]
+    for o in (ora, lib):                                    # extents are reserved up front, as for any write-through
+        assert o.reserve(12, 8) == 0 and o.reserve(10, 8) == 0
+    assert kp.wq_post(rid, off, blk, tok, [1.0, 3.0, 2.0]) == kv.KV_OK
+    assert kp.wq_pending() == (kv.KV_OK, 12, 3)
+    rc, wrote, pend, used = kp.wq_drain(block_budget=5)
+    assert (rc, wrote, pend, used) == (kv.KV_OK, 5, 7, 5)
+    phys, slot = kp.last_plan()
+    assert phys.tolist() == [24, 25, 26, 27, 28]            # request 11 whole, then one block of 12
+    lib._apply_out()
+    order = [1, 2, 0]
+    o2, b2 = W.csr_take(np.array(off, np.int32), np.array(blk, np.int32), order)
+    rc, m2 = ora.swap_out_delta([rid[i] for i in order], o2, b2, [tok[i] for i in order], budget=5)
+    assert rc == ko.OK and m2.tolist() == [4, 1, 0]
+    assert np.array_equal(a.staging, b.staging) and all(ora.query(r) == lib.query(r) for r in rid)
+    # request 10 grows by two blocks and becomes the most urgent; the others keep their entries
+    assert kp.wq_post([10], [0, 6], [20, 21, 22, 23, 40, 41], [12], [9.0]) == kv.KV_OK
+    rc, wrote, pend, used = kp.wq_drain()                   # no budget: everything that is full
+    assert (rc, wrote, pend) == (kv.KV_OK, 9, 0)
+    lib._apply_out()
+    rc, m3 = ora.swap_out_delta([10, 11, 12], [0, 6, 10, 15], [20, 21, 22, 23, 40, 41] + blk[4:], [12, 8, 9])
+    assert rc == ko.OK and m3.tolist() == [6, 0, 3]
+    assert np.array_equal(a.staging, b.staging) and all(ora.query(r) == lib.query(r) for r in rid)
+    # an interval: plan-only rate 32 GB/s, fixed 50 us, 64-byte slots -> (50.005 - 50) us * 32e3 B/us / 64 = 2 blocks
+    assert kp.wq_post([12], [0, 7], blk[8:] + [50, 51], [14], [0.5]) == kv.KV_OK          # 7 full blocks, 4 written
+    rc, wrote, pend, used = kp.wq_drain(interval_us=50.005)
+    assert (rc, wrote, pend, used) == (kv.KV_OK, 2, 1, 2)
+    rc, wrote, pend, used = kp.wq_drain(interval_us=10.0)   # shorter than the fixed cost: nothing fits, nothing moves
+    assert (rc, wrote, pend, used) == (kv.KV_OK, 0, 1, 0)
+    kp.close()
+
+
+def test_write_queue_entries_follow_the_requests():
+    g = W.Geometry(1, 1, 8, 2, "f16", 64)
+    kp = kv.KVPool(g, flags=kv.KV_PLAN_ONLY, staging_bytes=40 * g.S)
+    assert kp.wq_post([1, 2, 3], [0, 2, 4, 6], [0, 1, 2, 3, 4, 5], [4, 4, 4]) == kv.KV_OK
+    assert kp.wq_pending() == (kv.KV_OK, 6, 3)
+    # a full swap-out, a release and a swap-in each take their requests out of the queue
+    assert kp.swap_out([1], [0, 2], [0, 1], [4]) == kv.KV_OK
+    assert kp.wq_pending() == (kv.KV_OK, 4, 2) and kp.wq_remove(1) == kv.KV_ENOENT
+    rc, wrote, pend, _ = kp.wq_drain(block_budget=1)
+    assert (rc, wrote, pend) == (kv.KV_OK, 1, 3)
+    assert kp.release(2) == kv.KV_OK and kp.wq_pending() == (kv.KV_OK, 2, 1)
+    assert kp.swap_in([1], [0, 2], [10, 11]) == kv.KV_OK
+    assert kp.wq_remove(3) == kv.KV_OK and kp.wq_remove(3) == kv.KV_ENOENT
+    assert kp.wq_drain() == (kv.KV_OK, 0, 0, 0)
+    # rejected posts record nothing
+    assert kp.wq_post([5, 5], [0, 1, 2], [0, 1], [2, 2]) == kv.KV_EINVAL                   # named twice
+    assert kp.wq_post([5], [0, 1], [0], [4]) == kv.KV_EINVAL                               # 4 tokens need 2 blocks
+    assert kp.wq_post([5], [0, 1], [64], [2]) == kv.KV_ERANGE
+    assert kp.wq_post([5], [0, 1], [0], [2], [float("nan")]) == kv.KV_EINVAL
+    assert kp.swap_out([6], [0, 1], [7], [2]) == kv.KV_OK
+    assert kp.wq_post([6], [0, 1], [7], [2]) == kv.KV_EEXIST                               # swapped out
+    assert kp.wq_pending() == (kv.KV_OK, 0, 0)
+    # a drain that cannot be planned changes nothing: the arena has 40 slots
+    assert kp.wq_post([8], [0, 60], list(range(60)), [120]) == kv.KV_OK
+    rc, _, _, _ = kp.wq_drain()
+    assert rc == kv.KV_ENOSPC and kp.wq_pending() == (kv.KV_OK, 60, 1) and kp.query(8)[0] == kv.KV_ENOENT
+    assert kp.wq_drain(interval_us=-1.0)[0] == kv.KV_EINVAL and kp.wq_drain(block_budget=-1)[0] == kv.KV_EINVAL
+    kp.close()
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_write_queue_random_against_oracle(seed):
+    """Random growth, posts, budgets and preempt / resume cycles: after every drain the staged bytes and the
+    per-request state equal the oracle's, which receives the same requests in the same priority order."""
+    rng = np.random.default_rng(900 + seed)
+    g = W.Geometry(2, 1, 8, 2, "f16", 96)
+    a, b = HostPool(g, 40 + seed, slots=80), HostPool(g, 40 + seed, slots=80)
+    ora, lib = a.oracle(), PlanOnlyAdapter(b)
+    kp = lib.kp
+    free = list(rng.permutation(g.N))
+    table, length, prio, queued = {}, {}, {}, {}
+    for r in range(1, 7):
+        table[r], length[r] = [], 0
+        for o in (ora, lib):
+            assert o.reserve(r, 13) == 0                     # 6 x 13 of the 80 slots
+    for step in range(120):
+        grow = [r for r in table if rng.random() < 0.6]
+        for r in grow:                                       # decode: a few more tokens, new blocks as needed
+            length[r] = min(length[r] + int(rng.integers(1, 4)), 13 * g.B)
+            while len(table[r]) * g.B < length[r] and free:
+                table[r].append(int(free.pop()))
+            length[r] = min(length[r], len(table[r]) * g.B)
+            prio[r] = float(rng.integers(0, 4))
+        if grow:
+            off = np.concatenate([[0], np.cumsum([len(table[r]) for r in grow])]).astype(np.int32)
+            blk = [x for r in grow for x in table[r]]
+            assert kp.wq_post(grow, off, blk, [length[r] for r in grow], [prio[r] for r in grow]) == kv.KV_OK
+            for r in grow:
+                queued[r] = (list(table[r]), length[r], prio[r], step * 100 + grow.index(r))
+        if rng.random() < 0.7:
+            budget = int(rng.integers(0, 6))
+            rc, wrote, pend, used = kp.wq_drain(block_budget=budget)
+            assert rc == kv.KV_OK
+            lib._apply_out()
+            order = sorted(queued, key=lambda r: (-queued[r][2], queued[r][3]))
+            if order:
+                off = np.concatenate([[0], np.cumsum([len(queued[r][0]) for r in order])]).astype(np.int32)
+                rc, moved = ora.swap_out_delta(order, off, [x for r in order for x in queued[r][0]],
+                                               [queued[r][1] for r in order], budget=budget)
+                assert rc == ko.OK and int(moved.sum()) == wrote
+            assert np.array_equal(a.staging, b.staging)
+            for r in table:
+                assert ora.query(r) == lib.query(r)
+            want = sum(max(0, queued[r][1] // g.B - (ora.query(r)[1]["wm"] if ora.query(r)[0] == 0 else 0)) for r in queued)
+            assert pend == want
+        if rng.random() < 0.15 and queued:                   # preempt one (tail flush) and bring it back elsewhere
+            r = int(rng.choice(list(queued)))
+            off = [0, len(table[r])]
+            for o in (ora, lib):
+                rc, _ = o.swap_out_delta([r], off, table[r], [length[r]], flags=kv.KV_DELTA_INCLUDE_TAIL)
+                assert rc == 0
+            new = [int(free.pop(0)) for _ in table[r]]
+            free.extend(table[r])
+            for o in (ora, lib):
+                assert o.swap_in([r], off, new, kv.KV_KEEP_STAGING) == 0
+            table[r] = new
+            queued.pop(r)                                    # the library dropped its entry at the swap-in
+    kp.close()
