@@ -49,7 +49,9 @@
  *   - Every entry point returns 0 (KV_OK) or a negative KV_E* code.  No C++
  *     exception crosses the boundary.
  *   - All-or-nothing: a call checks every request and every block id before it
- *     changes any state or enqueues any work.
+ *     changes any state or enqueues any work.  KV_EHIP is the exception: a HIP runtime failure
+ *     in the middle of enqueuing leaves bookkeeping and streams out of step; the only call that is
+ *     still meaningful on such a handle is kv_pool_destroy.
  *   - Calls are asynchronous.  Swap-out / delta / move work is enqueued on the evict stream,
  *     swap-in work on the load stream, in issue order.  The library inserts every cross-stream
  *     wait the two streams need between themselves: for staging slots (a swap-in reads slots an

@@ -276,20 +276,28 @@ int grow_ring(kv_pool* p, size_t need) {
   return KV_OK;
 }
 
-// Reserve n consecutive descriptors in both rings; waits (on the host) for
-// earlier calls whose descriptors still occupy that part.
-int ring_reserve(kv_pool* p, size_t n, uint64_t seq, size_t* at) {
+// Reserve n consecutive descriptors in both rings; waits (on the host) for earlier work whose
+// descriptors still occupy that part: other calls through their end event, earlier launches of
+// this same call (a call cut into more slices than the ring holds) through its stream.
+int ring_reserve(kv_pool* p, size_t n, uint64_t seq, hipStream_t st, size_t* at) {
   if (n > p->ring_cap / 2) {
     int rc = grow_ring(p, n * 4);
     if (rc) return rc;
   }
   if (p->ring_head + n > p->ring_cap) p->ring_head = 0;
   const size_t b = p->ring_head, e = b + n;
-  for (auto& s : p->ring_inflight)
-    if (s.begin < e && b < s.end && s.seq != seq) {
+  bool own_synced = false;
+  for (auto& s : p->ring_inflight) {
+    if (!(s.begin < e && b < s.end)) continue;
+    if (s.seq != seq) {
       int rc = wait_seq_on_host(p, s.seq);
       if (rc) return rc;
+    } else {
+      if (!own_synced) HIPCHK(p, hipStreamSynchronize(st));
+      own_synced = true;
+      s.begin = s.end = 0;  // consumed: its kernel and its descriptor upload have run
     }
+  }
   p->ring_inflight.push_back({b, e, seq});
   p->ring_head = e;
   *at = b;
@@ -346,7 +354,7 @@ int enqueue_kernel(kv_pool* p, Call& call, int mode, const Desc* desc, size_t n,
   const bool link = kind == 1;
   hipStream_t st = p->stream[call.stream];
   size_t at = 0;
-  int rc = ring_reserve(p, n, call.seq, &at);
+  int rc = ring_reserve(p, n, call.seq, st, &at);
   if (rc) return rc;
   std::memcpy(p->ring_host + at, desc, n * sizeof(Desc));
   HIPCHK(p, hipMemcpyAsync(p->ring_dev + at, p->ring_host + at, n * sizeof(Desc), hipMemcpyHostToDevice, st));
@@ -389,10 +397,12 @@ int enqueue_kernel(kv_pool* p, Call& call, int mode, const Desc* desc, size_t n,
   a.n_jobs = a.n_data_jobs + (a.scale_words ? (int64_t)n : 0);
 
   // default caps: host link 64 workgroups, grid-stride (the link saturates there and three
-  // quarters of the CUs stay free for the model); HBM to HBM one workgroup per job
-  int64_t cap = link ? (p->max_wgs_link ? p->max_wgs_link : 64)
-                     : (p->max_wgs_device ? p->max_wgs_device : (int64_t)1 << 30);
-  const int grid = (int)std::min<int64_t>(a.n_jobs, cap);
+  // quarters of the CUs stay free for the model); HBM to HBM one workgroup per job, up to the
+  // largest grid whose thread count still fits 32 bits (64 GiB per launch at 4 KiB a job; the
+  // kernel strides over what is beyond)
+  constexpr int64_t kMaxGrid = ((int64_t)1 << 32) / 256 - 1;
+  int64_t cap = link ? (p->max_wgs_link ? p->max_wgs_link : 64) : (p->max_wgs_device ? p->max_wgs_device : kMaxGrid);
+  const int grid = (int)std::min<int64_t>(a.n_jobs, std::min(cap, kMaxGrid));
 
   hipEvent_t k0, k1;
   if ((rc = get_event(p, &k0)) || (rc = get_event(p, &k1))) return rc;
@@ -601,8 +611,9 @@ void mark_blocks(kv_pool* p, const Call& c, int mode, const Desc* desc, size_t n
 
 // Open a call record: cross-stream waits, caller's event, start event.  mode 2 (move) resolves its
 // device-block hazards here, for the whole call; transfers (mode 0 / 1) do it per segment in
-// enqueue_transfer.  Events of unfinished calls are only recycled by retire(), which runs here and
-// nowhere else, so an event block_hazard() returns stays valid until the call is enqueued.
+// enqueue_transfer.  Events of unfinished calls are only recycled by retire(), which never runs
+// between open_call and close_call, so an event block_hazard() returns stays valid until the wait on
+// it has been enqueued.
 int open_call(kv_pool* p, int stream, int op, uint64_t wait_seq, void* wait_event, int mode,
               const std::vector<Desc>& desc, Call** out) {
   retire(p);

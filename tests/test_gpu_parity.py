@@ -558,6 +558,32 @@ def test_write_queue_on_the_gpu(gpu):
     kp.close()
 
 
+def test_one_call_longer_than_the_descriptor_ring(gpu):
+    """Token-level blocks (B = 1, 256 bytes each), one request of 150 000 of them through a bounce buffer
+    that holds 2048 at a time: the call is cut into 74 slices whose descriptors together exceed the ring
+    (65 536 entries), so late slices reuse the ring space of early ones of the same call."""
+    import torch
+    g = W.Geometry(1, 1, 64, 1, "f16", 200000)
+    n = 150000
+    a = HostPool(g, 0x4126, slots=n + 8)
+    ora = a.oracle()
+    pool = torch.from_numpy(a.pool.copy()).cuda()
+    staging = torch.full((len(a.staging),), CANARY, dtype=torch.uint8).pin_memory()
+    bounce = torch.zeros(2 * 2048 * g.S, dtype=torch.uint8, device="cuda")
+    kp = kv.KVPool(g, pool, staging, bounce=bounce, flags=kv.KV_PATH_DMA)
+    perm = np.random.default_rng(5).permutation(g.N).astype(np.int32)
+    assert kp.swap_out([1], [0, n], perm[:n], [n]) == kv.KV_OK
+    st = kp.stats()
+    assert st["launches"] == 74 and st["copies"] == 74
+    assert kp.swap_in([1], [0, n], perm[g.N - n:][::-1].copy()) == kv.KV_OK
+    assert kp.sync() == kv.KV_OK
+    assert ora.swap_out([1], [0, n], perm[:n], [n]) == ko.OK
+    assert np.array_equal(staging.numpy(), a.staging)
+    assert ora.swap_in([1], [0, n], perm[g.N - n:][::-1].copy()) == ko.OK
+    assert np.array_equal(pool.cpu().numpy(), a.pool)
+    kp.close()
+
+
 def test_create_checks_memory_kinds(gpu):
     import torch
     g = W.Geometry(2, 4, 64, 16, "f16", 64)
