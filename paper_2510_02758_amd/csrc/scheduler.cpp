@@ -86,8 +86,8 @@ int kv_sched_step(const kv_sched_config* cfg, int32_t n, const kv_sched_req* req
       !(cfg->evict_gbps > 0.0) || !(cfg->load_gbps > 0.0) || !(cfg->block_bytes > 0.0))
     return KVS_EINVAL;
   for (int32_t i = 0; i < n; i++)
-    if (req[i].state < KVS_NEW || req[i].state > KVS_PREEMPTED || !(req[i].rate > 0.0) || req[i].buffer < 0.0 ||
-        req[i].blocks < 0 || req[i].dirty_blocks < 0 || req[i].tokens < 0)
+    if (req[i].state < KVS_NEW || req[i].state > KVS_PREEMPTED || !(req[i].rate > 0.0) || !(req[i].buffer >= 0.0) ||
+        !(req[i].arrival == req[i].arrival) || req[i].blocks < 0 || req[i].dirty_blocks < 0 || req[i].tokens < 0)
       return KVS_EINVAL;
 
   // per-request estimates

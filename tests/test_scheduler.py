@@ -329,6 +329,8 @@ def test_scheduler_rejects_bad_input():
     assert ks.kv_sched_step(cfg, [req(7, 20, 0)])[0] == ks.KVS_EINVAL
     assert ks.kv_sched_step(cfg, [req(so.RUNNING, 0.0, 0)])[0] == ks.KVS_EINVAL
     assert ks.kv_sched_step(cfg, [req(so.RUNNING, 20, -1.0)])[0] == ks.KVS_EINVAL
+    assert ks.kv_sched_step(cfg, [req(so.RUNNING, 20, float("nan"))])[0] == ks.KVS_EINVAL
+    assert ks.kv_sched_step(cfg, [req(so.RUNNING, 20, 1.0, arrival=float("nan"))])[0] == ks.KVS_EINVAL
     bad = ks.make_config(**dict(BASE, interval=0.0))
     assert ks.kv_sched_step(bad, [req(so.RUNNING, 20, 1)])[0] == ks.KVS_EINVAL
     cfg.struct_size = 8
