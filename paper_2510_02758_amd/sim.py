@@ -60,6 +60,8 @@ class SimConfig:
     tau_schedule: float = 0.0005
     qos_lambda: float = 1.0
     qos_mu: float = 1.0
+    sync_io: bool = False             # True: the host waits for every eviction and load (the simple serving loop);
+                                      # False: nothing waits on the host, the streams are ordered by events alone
 
     def step_time(self, batch):
         return self.step_base + self.step_per_req * batch
@@ -75,7 +77,11 @@ class Simulator:
         g = W.Geometry(self.g.L, self.g.H, self.g.D, self.g.B, self.g.dtype, cfg.gpu_blocks, scales=False)
         self.g = g
         if self.real:
-            self.kp = kv.KVPool(g, pool, staging)
+            import torch
+            # the library's two streams, known to torch so that the "model" can order itself after them
+            self.s_evict, self.s_load = torch.cuda.Stream(), torch.cuda.Stream()
+            self.kp = kv.KVPool(g, pool, staging, flags=kv.KV_REQ_EVENTS, evict_stream=self.s_evict,
+                                load_stream=self.s_load)
         else:
             self.kp = kv.KVPool(g, flags=kv.KV_PLAN_ONLY, staging_bytes=cfg.arena_blocks * g.S)
         self.free = list(range(cfg.gpu_blocks - 1, -1, -1))
@@ -104,10 +110,19 @@ class Simulator:
         g = self.g
         return self.pool[: g.pool_bytes].view(g.L, 2, g.N, g.chunk)                  # layer-major pool
 
+    def _after_transfers(self):
+        """The model's stream waits (on the GPU, not on the host) for the transfers enqueued so far: a block
+        may be rewritten only after its eviction has read it, and read only after its load has filled it."""
+        import torch
+        cur = torch.cuda.current_stream()
+        cur.wait_stream(self.s_evict)
+        cur.wait_stream(self.s_load)
+
     def _fill_blocks(self, r, j0, blks):
         if not self.real or not blks:
             return
         import torch
+        self._after_transfers()
         idx = torch.tensor(blks, dtype=torch.int64, device=self.pool.device)
         self._poolv().index_copy_(2, idx, self._pattern(r.rid, j0, len(blks)))
 
@@ -119,6 +134,7 @@ class Simulator:
         if not self.real or not r.table:
             return True
         import torch
+        self._after_transfers()
         idx = torch.tensor(r.table, dtype=torch.int64, device=self.pool.device)
         return bool(torch.equal(self._poolv().index_select(2, idx), self._pattern(r.rid, 0, len(r.table))))
 
@@ -199,7 +215,8 @@ class Simulator:
         else:
             self._ok(self.kp.swap_out([r.rid], off, ids, [self._ctx(r)], wait_event=self._produced()), "kv_swap_out")
             n = len(ids)
-        self._ok(self.kp.sync(), "kv_sync")
+        if self.cfg.sync_io:
+            self._ok(self.kp.sync(), "kv_sync")
         self.kp.wq_remove(r.rid)                    # its table is about to be given up (KV_ENOENT if it was not queued)
         self.moved_blocks["evict"] += n
         self.free.extend(reversed(r.table))        # the allocator takes the blocks back
@@ -222,8 +239,12 @@ class Simulator:
             r.recomputes += 1
         else:
             off, ids = self._tables([r])
-            self._ok(self.kp.swap_in([r.rid], off, ids, kv.KV_KEEP_STAGING if self.cfg.write_through else 0), "kv_swap_in")
-            self._ok(self.kp.sync(), "kv_sync")
+            # the blocks were the model's (or another request's) a moment ago: after its writes, and, inside the
+            # library, after any eviction that still reads them
+            self._ok(self.kp.swap_in([r.rid], off, ids, kv.KV_KEEP_STAGING if self.cfg.write_through else 0,
+                                     wait_event=self._produced()), "kv_swap_in")
+            if self.cfg.sync_io:
+                self._ok(self.kp.sync(), "kv_sync")
             self.moved_blocks["load"] += nb
             cost = self._xfer_time(nb)
         r.state = "running"

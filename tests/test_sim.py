@@ -64,10 +64,14 @@ def test_without_write_through_evictions_move_whole_requests():
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("sync_io", [True, False])
 @pytest.mark.parametrize("write_through", [True, False])
-def test_sim_moves_real_kv_and_keeps_it_intact(gpu, write_through):
+def test_sim_moves_real_kv_and_keeps_it_intact(gpu, write_through, sync_io):
+    """sync_io False: no host wait anywhere in the loop; evictions, loads and the model's writes are
+    ordered by events only (the library's between its two streams, the loop's towards the model)."""
     import torch
     cfg, reqs = make("tokenflow", n=16, gpu_blocks=200, write_through=write_through, prefill_per_token=2e-6)
+    cfg.sync_io = sync_io
     g = W.Geometry(GEOM.L, GEOM.H, GEOM.D, GEOM.B, GEOM.dtype, cfg.gpu_blocks)
     pool = torch.zeros(g.pool_bytes, dtype=torch.uint8, device=gpu)
     staging = torch.zeros(cfg.arena_blocks * g.S, dtype=torch.uint8).pin_memory()
@@ -79,13 +83,14 @@ def test_sim_moves_real_kv_and_keeps_it_intact(gpu, write_through):
 
 
 @pytest.mark.gpu
-def test_sim_at_8b_block_size(gpu):
+@pytest.mark.parametrize("sync_io", [True, False])
+def test_sim_at_8b_block_size(gpu, sync_io):
     """2 MiB blocks (Llama-3-8B shape), 32 requests, dozens of preemptions: large enough for a missing
     stream dependency between the model's writes and the write-through to show up as wrong bytes."""
     import torch
     g = W.Geometry(32, 8, 128, 16, "bf16", 1200)
     cfg = S.SimConfig(geom=g, gpu_blocks=g.N, arena_blocks=5000, max_running=16, interval=0.5, policy="tokenflow",
-                      prefill_per_token=2e-4)
+                      prefill_per_token=2e-4, sync_io=sync_io)
     reqs = S.burst_requests(11, 32, prompt_mean=512, out_mean=768, rates=(15.0, 20.0))
     pool = torch.zeros(g.pool_bytes, dtype=torch.uint8, device=gpu)
     staging = torch.zeros(cfg.arena_blocks * g.S, dtype=torch.uint8).pin_memory()
