@@ -347,17 +347,28 @@ int pick_unroll(const kv_pool* p, bool link) {
   return 1;
 }
 
-// Upload n descriptors and launch one data kernel over them on stream `st`.
-// mode 0 gather, 1 scatter, 2 move.  `contig` is the contiguous side.
-int enqueue_kernel(kv_pool* p, Call& call, int mode, const Desc* desc, size_t n, char* contig, int kind) {
+// Very short descriptor lists (a preemption after write-through moves one tail block per victim)
+// travel inside the kernel arguments: no upload in front of the kernel, no ring space.
+constexpr size_t kInlineDescMax = sizeof(MoveArgs::inl) / sizeof(Desc);
+
+// Hand n descriptors to the device and launch one data kernel over them on stream `st`.
+// mode 0 gather, 1 scatter, 2 move.  `contig` is the contiguous side.  `sole`: this is the only
+// launch of its call, so the call's own start and end events already bracket it and the pair of
+// kernel events (a marker packet each) is left out.
+int enqueue_kernel(kv_pool* p, Call& call, int mode, const Desc* desc, size_t n, char* contig, int kind,
+                   bool sole = false) {
   if (n == 0) return KV_OK;
   const bool link = kind == 1;
   hipStream_t st = p->stream[call.stream];
   size_t at = 0;
-  int rc = ring_reserve(p, n, call.seq, st, &at);
-  if (rc) return rc;
-  std::memcpy(p->ring_host + at, desc, n * sizeof(Desc));
-  HIPCHK(p, hipMemcpyAsync(p->ring_dev + at, p->ring_host + at, n * sizeof(Desc), hipMemcpyHostToDevice, st));
+  int rc = KV_OK;
+  const bool inline_desc = n <= kInlineDescMax;
+  if (!inline_desc) {
+    rc = ring_reserve(p, n, call.seq, st, &at);
+    if (rc) return rc;
+    std::memcpy(p->ring_host + at, desc, n * sizeof(Desc));
+    HIPCHK(p, hipMemcpyAsync(p->ring_dev + at, p->ring_host + at, n * sizeof(Desc), hipMemcpyHostToDevice, st));
+  }
 
   const int u = pick_unroll(p, link);
   const int64_t piece = 256 * 16 * (int64_t)u;
@@ -374,6 +385,9 @@ int enqueue_kernel(kv_pool* p, Call& call, int mode, const Desc* desc, size_t n,
   a.S = p->S;
   a.block_bytes = p->block_bytes;
   a.desc = p->ring_dev + at;
+  a.use_inl = inline_desc ? 1 : 0;
+  std::memset(a.inl, 0, sizeof(a.inl));
+  if (inline_desc) std::memcpy(a.inl, desc, n * sizeof(Desc));
   a.chunk = (int32_t)p->chunk;
   a.ppc = (int32_t)((p->chunk + piece - 1) / piece);
   a.jobs_per_block = 2 * p->cfg.num_layers * a.ppc;
@@ -404,9 +418,11 @@ int enqueue_kernel(kv_pool* p, Call& call, int mode, const Desc* desc, size_t n,
   int64_t cap = link ? (p->max_wgs_link ? p->max_wgs_link : 64) : (p->max_wgs_device ? p->max_wgs_device : kMaxGrid);
   const int grid = (int)std::min<int64_t>(a.n_jobs, std::min(cap, kMaxGrid));
 
-  hipEvent_t k0, k1;
-  if ((rc = get_event(p, &k0)) || (rc = get_event(p, &k1))) return rc;
-  HIPCHK(p, hipEventRecord(k0, st));
+  hipEvent_t k0 = nullptr, k1 = nullptr;
+  if (!sole) {
+    if ((rc = get_event(p, &k0)) || (rc = get_event(p, &k1))) return rc;
+    HIPCHK(p, hipEventRecord(k0, st));
+  }
   if (mode == 0)
     launch_move<0>(u, grid, kind, st, a);
   else if (mode == 1)
@@ -414,8 +430,10 @@ int enqueue_kernel(kv_pool* p, Call& call, int mode, const Desc* desc, size_t n,
   else
     launch_move_u<2, 0>(u, grid, st, a);
   HIPCHK(p, hipGetLastError());
-  HIPCHK(p, hipEventRecord(k1, st));
-  call.kev.push_back({k0, k1});
+  if (!sole) {
+    HIPCHK(p, hipEventRecord(k1, st));
+    call.kev.push_back({k0, k1});
+  }
   call.st.launches++;
   call.st.grid = grid;
   return KV_OK;
@@ -492,7 +510,8 @@ int enqueue_transfer(kv_pool* p, Call& call, const Plan& plan, bool out) {
       waited = hazard;
     }
     if (!dma) {
-      int rc = enqueue_kernel(p, call, out ? 0 : 1, desc.data() + s0, s1 - s0, p->arena_dev, p->dev_staging ? 0 : 1);
+      int rc = enqueue_kernel(p, call, out ? 0 : 1, desc.data() + s0, s1 - s0, p->arena_dev, p->dev_staging ? 0 : 1,
+                              /*sole=*/seg_end.size() == 1);
       if (rc) return rc;
     } else {
       for (size_t a0 = s0; a0 < s1; a0 += (size_t)slice) {
@@ -936,7 +955,7 @@ int kv_move_blocks(kv_pool* p, int64_t n, const int32_t* src_ids, const int32_t*
   if (rc) return rc;
   fill_plan_stats(p, &c->st, 4, plan.desc.size(), t1 - t0);
   c->st.path = KV_PATH_ZEROCOPY;
-  rc = enqueue_kernel(p, *c, 2, plan.desc.data(), plan.desc.size(), nullptr, 0);
+  rc = enqueue_kernel(p, *c, 2, plan.desc.data(), plan.desc.size(), nullptr, 0, /*sole=*/true);
   if (rc) return rc;
   mark_blocks(p, *c, 2, plan.desc.data(), plan.desc.size(), -1);
   rc = close_call(p, *c);
@@ -1006,7 +1025,8 @@ int kv_last_stats(kv_pool* p, kv_stats* out) {
       HIPCHK(p, hipEventElapsedTime(&ms, k.first, k.second));
       ks += ms;
     }
-    c.st.ms_kernel = ks;
+    // a call that is one launch and nothing else carries no kernel events: its own events bracket the kernel
+    c.st.ms_kernel = c.kev.empty() && c.st.launches == 1 && c.st.copies == 0 ? c.st.ms_total : ks;
   }
   *out = c.st;
   return KV_OK;
