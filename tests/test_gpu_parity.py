@@ -584,6 +584,56 @@ def test_one_call_longer_than_the_descriptor_ring(gpu):
     kp.close()
 
 
+def test_control_thread_polls_while_the_main_thread_enqueues(gpu):
+    """Section 6: a control thread follows the transfers through events while the serving thread keeps
+    enqueuing.  The handle serialises the two with its own lock; results stay the oracle's."""
+    import threading
+    import torch
+    g = W.Geometry(8, 8, 128, 16, "bf16", 600)             # 512 KiB blocks
+    a = HostPool(g, 0x7EAD, slots=320)
+    ora = a.oracle()
+    pool = torch.from_numpy(a.pool.copy()).cuda()
+    staging = torch.full((len(a.staging),), CANARY, dtype=torch.uint8).pin_memory()
+    kp = kv.KVPool(g, pool, staging, flags=kv.KV_REQ_EVENTS)
+    perm = np.random.default_rng(21).permutation(g.N).astype(np.int32)
+    stop, seen, errors = threading.Event(), {"polls": 0, "busy": 0}, []
+
+    def control():
+        try:
+            while not stop.is_set():
+                for r in range(1, 9):
+                    rc = kp.req_poll(r)
+                    assert rc in (0, 1), rc
+                    seen["busy"] += rc == 0
+                    seen["polls"] += 1
+                io = kp.io_stats()
+                assert min(io["inflight_calls"]) >= 0 and min(io["inflight_bytes"]) >= 0
+        except Exception as e:                              # noqa: BLE001 - reported by the main thread
+            errors.append(e)
+
+    t = threading.Thread(target=control)
+    t.start()
+    rid = list(range(1, 9))
+    off = np.arange(0, 9 * 36, 36, dtype=np.int32)[:9]
+    lens = [36 * g.B] * 8
+    try:
+        for it in range(6):
+            src = np.roll(perm, 31 * it)[:288]
+            dst = np.roll(perm, 31 * it)[288:576]
+            assert kp.swap_out(rid, off, src, lens) == kv.KV_OK
+            assert kp.swap_in(rid, off, dst) == kv.KV_OK
+            assert ora.swap_out(rid, off, src, lens) == ko.OK and ora.swap_in(rid, off, dst) == ko.OK
+            assert kp.req_wait(rid[it % 8]) == kv.KV_OK
+    finally:
+        stop.set()
+        t.join(60)
+    assert not t.is_alive() and not errors, errors
+    assert kp.sync() == kv.KV_OK
+    assert seen["polls"] > 100
+    assert np.array_equal(pool.cpu().numpy(), a.pool) and np.array_equal(staging.numpy(), a.staging)
+    kp.close()
+
+
 def test_create_checks_memory_kinds(gpu):
     import torch
     g = W.Geometry(2, 4, 64, 16, "f16", 64)
