@@ -144,9 +144,12 @@ def main():
         link_bidir = 2 * one / min(ms) / 1e6 if min(ms) > 0 else None
     copy_gbs = None
     if scratch is not None:
-        ms = kv.kv_bench_copy(dev_arena[4 * one:].data_ptr(), scratch.data_ptr(), 4 * one, 1 << 18, 5,
-                              evict.cuda_stream)
+        # 16 GiB of plain copy first: the memory clocks take some hundred milliseconds of load to come up
+        kv.kv_bench_copy(dev_arena[4 * one:].data_ptr(), scratch.data_ptr(), 4 * one, 0, 40, evict.cuda_stream)
+        ms = kv.kv_bench_copy(dev_arena[4 * one:].data_ptr(), scratch.data_ptr(), 4 * one, 0, 5, evict.cuda_stream)
         copy_gbs = 2 * 4 * one / ms / 1e6
+        # the 16 KiB-piece shape, kept under its own kernel name as the known-size reference of the counter runs
+        kv.kv_bench_copy(dev_arena[4 * one:].data_ptr(), scratch.data_ptr(), 4 * one, 1 << 18, 2, evict.cuda_stream)
 
     def ok(rc, what):
         if rc != kv.KV_OK:
@@ -324,13 +327,13 @@ def main():
                  "measured_peak_bidirectional_gbps": None if link_bidir is None else round(link_bidir, 2),
                  "kernel_out_ms": round(m["out_k"], 2), "kernel_in_ms": round(m["in_k"], 2),
                  "how": "one 1 GiB contiguous pinned hipMemcpyAsync per direction, in this run"},
-        "roofline": {"bound": "hbm", "kernel": "kv_move_kernel<1,1,0> (scatter, both ends in HBM)",
+        "roofline": {"bound": "hbm", "kernel": "kv_move_kernel<1,1,0,true> (scatter, both ends in HBM)",
                      "achieved": round(scatter_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(scatter_gbs / HBM_PEAK_GBS, 4),
                      "traffic": MEASURED_TRAFFIC.get(("configs[1]", total, "scatter")) if not args.blocks else None,
                      "launch_ms": round(scatter_ms, 3), "bytes_per_launch": 2 * P,
                      "measured_copy_ceiling_gbps": None if copy_gbs is None else round(copy_gbs, 1)},
-        "roofline_gather": {"bound": "hbm", "kernel": "kv_move_kernel<0,1,0> (gather, both ends in HBM)",
+        "roofline_gather": {"bound": "hbm", "kernel": "kv_move_kernel<0,1,0,true> (gather, both ends in HBM)",
                             "achieved": round(gather_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                             "frac": round(gather_gbs / HBM_PEAK_GBS, 4),
                             "traffic": MEASURED_TRAFFIC.get(("configs[1]", total, "gather")) if not args.blocks else None,

@@ -328,8 +328,10 @@ const char* kv_strerror(int code);
  * Ceilings the swap is compared against (Section 7's bandwidth figures are quoted against the link);
  * no pool handle needed.  All three are synchronous and return the mean milliseconds per iteration, or
  * a negative number for bad arguments (-1), a failed HIP resource (-2) or a failed wait (-3).
- *   kv_bench_copy        contiguous device-to-device copy kernel of `bytes` (multiple of 16 KiB), at most
- *                        `grid` workgroups, on `stream`: the HBM copy ceiling.
+ *   kv_bench_copy        contiguous device-to-device copy kernel of `bytes` (multiple of 16 KiB) on `stream`:
+ *                        the HBM copy ceiling.  grid 0: one workgroup per 4 KiB piece (the launch shape of
+ *                        the on-device gather/scatter, the fastest plain copy); grid > 0: at most that many
+ *                        workgroups, grid-stride, 16 KiB pieces.
  *   kv_bench_link        one contiguous hipMemcpyAsync between PINNED host memory and device memory on
  *                        `stream`; dir 0 device -> host, 1 host -> device: the host-link ceiling.
  *   kv_bench_link_bidir  both directions at once on two internal streams (dev_a -> host_a while

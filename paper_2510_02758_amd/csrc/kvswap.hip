@@ -304,34 +304,39 @@ int ring_reserve(kv_pool* p, size_t n, uint64_t seq, hipStream_t st, size_t* at)
   return KV_OK;
 }
 
-template <int MODE, int KIND>
+template <int MODE, int KIND, bool LEAN>
 void launch_move_u(int u, int grid, hipStream_t st, const MoveArgs& a) {
   const size_t lds = a.scale_lds ? (size_t)a.scale_words * 4 : 0;
   switch (u) {
     case 1:
-      hipLaunchKernelGGL((kv_move_kernel<MODE, 1, KIND>), dim3(grid), dim3(256), lds, st, a);
+      hipLaunchKernelGGL((kv_move_kernel<MODE, 1, KIND, LEAN>), dim3(grid), dim3(256), lds, st, a);
       break;
     case 2:
-      hipLaunchKernelGGL((kv_move_kernel<MODE, 2, KIND>), dim3(grid), dim3(256), lds, st, a);
+      hipLaunchKernelGGL((kv_move_kernel<MODE, 2, KIND, LEAN>), dim3(grid), dim3(256), lds, st, a);
       break;
     case 8:
-      hipLaunchKernelGGL((kv_move_kernel<MODE, 8, KIND>), dim3(grid), dim3(256), lds, st, a);
+      hipLaunchKernelGGL((kv_move_kernel<MODE, 8, KIND, LEAN>), dim3(grid), dim3(256), lds, st, a);
       break;
     default:
-      hipLaunchKernelGGL((kv_move_kernel<MODE, 4, KIND>), dim3(grid), dim3(256), lds, st, a);
+      hipLaunchKernelGGL((kv_move_kernel<MODE, 4, KIND, LEAN>), dim3(grid), dim3(256), lds, st, a);
       break;
   }
 }
 
-// kind: 0 HBM arena, 1 host arena (link-bound), 2 bounce buffer
+// kind: 0 HBM arena, 1 host arena (link-bound), 2 bounce buffer.  The lean build of the kernel serves
+// every launch that has neither small chunks nor scales.
 template <int MODE>
 void launch_move(int u, int grid, int kind, hipStream_t st, const MoveArgs& a) {
-  if (kind == 1)
-    launch_move_u<MODE, 1>(u, grid, st, a);
-  else if (kind == 2)
-    launch_move_u<MODE, 2>(u, grid, st, a);
-  else
-    launch_move_u<MODE, 0>(u, grid, st, a);
+  const bool lean = !a.cpj && !a.scale_words;
+  if (MODE == 2) {
+    lean ? launch_move_u<MODE, 0, true>(u, grid, st, a) : launch_move_u<MODE, 0, false>(u, grid, st, a);
+  } else if (kind == 1) {
+    lean ? launch_move_u<MODE, 1, true>(u, grid, st, a) : launch_move_u<MODE, 1, false>(u, grid, st, a);
+  } else if (kind == 2) {
+    lean ? launch_move_u<MODE, 2, true>(u, grid, st, a) : launch_move_u<MODE, 2, false>(u, grid, st, a);
+  } else {
+    lean ? launch_move_u<MODE, 0, true>(u, grid, st, a) : launch_move_u<MODE, 0, false>(u, grid, st, a);
+  }
 }
 
 // Loads in flight per lane.  Both ends in HBM: one 16-byte load per lane and one workgroup per
@@ -428,7 +433,7 @@ int enqueue_kernel(kv_pool* p, Call& call, int mode, const Desc* desc, size_t n,
   else if (mode == 1)
     launch_move<1>(u, grid, kind, st, a);
   else
-    launch_move_u<2, 0>(u, grid, st, a);
+    launch_move<2>(u, grid, 0, st, a);
   HIPCHK(p, hipGetLastError());
   if (!sole) {
     HIPCHK(p, hipEventRecord(k1, st));
@@ -1329,20 +1334,32 @@ const char* kv_strerror(int code) {
 
 // ---- measurement helpers: ceilings the swap is compared against ----
 
-// Contiguous device-to-device copy of `bytes` (multiple of 16 KiB) with the same lane shape as
-// the gather.  Runs `iters` times on `stream`; returns the mean milliseconds per copy, or < 0.
+// Contiguous device-to-device copy of `bytes` (multiple of 16 KiB) with the lane shape of the gather.
+// grid == 0: one workgroup per 4 KiB piece, one 16-byte load per lane, the launch shape of the on-device
+// gather/scatter and the fastest plain copy measured on MI355X; grid > 0: at most that many workgroups,
+// four loads per lane, grid-stride.  Runs `iters` times on `stream`; returns the mean milliseconds per
+// copy, or < 0.
 double kv_bench_copy(void* dst_dev, const void* src_dev, int64_t bytes, int32_t grid, int32_t iters, void* stream) {
-  if (!dst_dev || !src_dev || bytes <= 0 || bytes % 16384 || grid <= 0 || iters <= 0) return -1.0;
+  if (!dst_dev || !src_dev || bytes <= 0 || bytes % 16384 || grid < 0 || iters <= 0) return -1.0;
   if (!range_ok(dst_dev, bytes) || !range_ok(src_dev, bytes)) return -1.0;
   hipStream_t st = (hipStream_t)stream;
   hipEvent_t a, b;
   if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return -2.0;
-  const int64_t pieces = bytes / 16384;
-  const int g = (int)std::min<int64_t>(pieces, grid);
-  hipLaunchKernelGGL((kv_copy_kernel<4>), dim3(g), dim3(256), 0, st, (const char*)src_dev, (char*)dst_dev, pieces);
+  constexpr int64_t kMaxGrid = ((int64_t)1 << 32) / 256 - 1;
+  auto once = [&]() {
+    if (grid == 0) {
+      const int64_t pieces = bytes / 4096;
+      hipLaunchKernelGGL((kv_copy_kernel<1>), dim3((unsigned)std::min(pieces, kMaxGrid)), dim3(256), 0, st,
+                         (const char*)src_dev, (char*)dst_dev, pieces);
+    } else {
+      const int64_t pieces = bytes / 16384;
+      hipLaunchKernelGGL((kv_copy_kernel<4>), dim3((unsigned)std::min<int64_t>(pieces, grid)), dim3(256), 0, st,
+                         (const char*)src_dev, (char*)dst_dev, pieces);
+    }
+  };
+  once();
   (void)hipEventRecord(a, st);
-  for (int i = 0; i < iters; i++)
-    hipLaunchKernelGGL((kv_copy_kernel<4>), dim3(g), dim3(256), 0, st, (const char*)src_dev, (char*)dst_dev, pieces);
+  for (int i = 0; i < iters; i++) once();
   (void)hipEventRecord(b, st);
   float ms = -1.f;
   if (hipEventSynchronize(b) != hipSuccess || hipEventElapsedTime(&ms, a, b) != hipSuccess) ms = -3.f * iters;
