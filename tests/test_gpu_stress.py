@@ -1,0 +1,197 @@
+"""Random serving histories on the GPU with no host synchronisation inside them.
+
+A seeded driver plays a few hundred operations (growth with budgeted write-through, cold and warm
+preemption, resumption into the most recently freed blocks, compaction moves, releases) against the
+library, enqueuing everything back to back; blocks given up by one call are handed to the next one at
+once, so that almost every call depends on unfinished work of the other stream.  The oracle runs the
+same history call by call.  Pool and arena must be equal byte for byte at the end of every chunk of the
+history: any missing ordering between the two streams shows up as a stale or torn block.
+"""
+import time
+
+import numpy as np
+import pytest
+
+from oracle import kv_oracle as ko
+from paper_2510_02758_amd import kvswap as kv
+from paper_2510_02758_amd import workloads as W
+
+from hostpool import CANARY, HostPool
+
+pytestmark = pytest.mark.gpu
+
+
+class History:
+    """Generates only valid calls: it tracks, on the host, what a serving engine's allocator would."""
+
+    def __init__(self, g, rng, n_req, cap):
+        self.g, self.rng, self.cap = g, rng, cap
+        self.free = [int(x) for x in rng.permutation(g.N)]
+        self.table = {r: [] for r in range(1, n_req + 1)}
+        self.length = {r: 0 for r in self.table}
+        self.state = {r: "idle" for r in self.table}     # idle -> running <-> out
+        self.reserved = set()
+
+    def csr(self, reqs, tables=None):
+        tables = tables or self.table
+        off = np.concatenate([[0], np.cumsum([len(tables[r]) for r in reqs])]).astype(np.int32)
+        blk = np.array([b for r in reqs for b in tables[r]], np.int32)
+        return off, blk
+
+    def step(self, both):
+        g, rng = self.g, self.rng
+        running = [r for r in self.table if self.state[r] == "running"]
+        out = [r for r in self.table if self.state[r] == "out"]
+        idle = [r for r in self.table if self.state[r] == "idle"]
+        op = rng.choice(["start", "grow", "grow", "preempt_warm", "preempt_cold", "resume", "resume", "move", "finish"])
+        if op == "start" and idle and len(self.free) > 8:
+            r = int(rng.choice(idle))
+            both(lambda o: o.reserve(r, self.cap))
+            self.reserved.add(r)
+            self.state[r], self.length[r], self.table[r] = "running", 0, []
+            op = "grow"
+            running = [r]
+        if op == "grow" and running:
+            rs = [int(r) for r in rng.permutation(running)[: int(rng.integers(1, len(running) + 1))]]
+            for r in rs:
+                want = min(self.length[r] + int(rng.integers(1, 3 * g.B)), self.cap * g.B)
+                while len(self.table[r]) * g.B < want and self.free:
+                    self.table[r].append(self.free.pop())
+                self.length[r] = min(want, len(self.table[r]) * g.B)
+            rs = [r for r in rs if self.table[r]]
+            if rs:
+                off, blk = self.csr(rs)
+                budget = int(rng.integers(0, 6))
+                toks = [self.length[r] for r in rs]          # values, not references: the oracle replays later
+                both(lambda o: o.swap_out_delta(rs, off, blk, toks, budget, 0)[0])
+        elif op in ("preempt_warm", "preempt_cold") and running:
+            r = int(rng.choice(running))
+            if not self.table[r]:
+                return
+            off, blk = self.csr([r])
+            toks = [self.length[r]]
+            if op == "preempt_warm":
+                both(lambda o: o.swap_out_delta([r], off, blk, toks, 0, kv.KV_DELTA_INCLUDE_TAIL)[0])
+            else:                                           # the whole request again, whatever was written through
+                both(lambda o: o.swap_out([r], off, blk, toks))
+            self.free.extend(self.table[r])                 # given up at once: the next call may get them
+            self.table[r] = []
+            self.state[r] = "out"
+        elif op == "resume" and out:
+            r = int(rng.choice(out))
+            nb = -(-self.length[r] // g.B)
+            if len(self.free) < nb:
+                return
+            self.table[r] = [self.free.pop() for _ in range(nb)]   # LIFO: the blocks freed a moment ago
+            off, blk = self.csr([r])
+            both(lambda o: o.swap_in([r], off, blk, kv.KV_KEEP_STAGING))
+            self.state[r] = "running"
+        elif op == "move" and running:
+            r = int(rng.choice(running))
+            k = min(len(self.table[r]), len(self.free), int(rng.integers(1, 5)))
+            if k == 0:
+                return
+            src = self.table[r][:k]
+            dst = [self.free.pop() for _ in range(k)]
+            both(lambda o: o.move_blocks(np.array(src, np.int32), np.array(dst, np.int32)))
+            self.table[r][:k] = dst
+            self.free.extend(src)
+        elif op == "finish" and (running or out):
+            r = int(rng.choice(running + out))
+            self.free.extend(self.table[r])
+            self.table[r], self.length[r], self.state[r] = [], 0, "idle"
+            both(lambda o: o.release(r))
+            self.reserved.discard(r)
+
+
+class Both:
+    """Applies each call to the library at once and keeps it for the oracle, which replays the chunk after
+    the library has been handed all of it: nothing on the host slows the enqueuing down."""
+
+    def __init__(self, kp, ora):
+        self.kp, self.ora, self.calls, self.todo = _Lib(kp), ora, 0, []
+
+    def __call__(self, fn):
+        rc = fn(self.kp)
+        assert rc == 0, rc
+        self.todo.append(fn)
+        self.calls += 1
+
+    def replay(self):
+        for fn in self.todo:
+            rc = fn(self.ora)
+            assert rc == 0, rc
+        self.todo = []
+
+
+class _Lib:
+    """The library under the oracle's method names (no synchronisation anywhere)."""
+
+    def __init__(self, kp):
+        self.kp = kp
+
+    def reserve(self, r, n):
+        return self.kp.reserve(r, n)
+
+    def release(self, r):
+        return self.kp.release(r)
+
+    def swap_out(self, *a):
+        return self.kp.swap_out(*a)
+
+    def swap_out_delta(self, rid, off, blk, tok, budget, flags):
+        return self.kp.swap_out_delta(rid, off, blk, tok, budget, flags)
+
+    def swap_in(self, *a):
+        return self.kp.swap_in(*a)
+
+    def move_blocks(self, src, dst):
+        return self.kp.move_blocks(src, dst)
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+@pytest.mark.parametrize("mode", ["zerocopy", "dma", "events", "dma_events"])
+def test_random_history_without_host_sync(gpu, mode, seed):
+    import torch
+    g = W.Geometry(16, 8, 128, 16, "bf16", 700)             # 1 MiB blocks
+    a = HostPool(g, 0xD1CE + seed, slots=480)
+    ora = a.oracle()
+    pool = torch.from_numpy(a.pool.copy()).cuda()
+    staging = torch.full((len(a.staging),), CANARY, dtype=torch.uint8).pin_memory()
+    flags = {"zerocopy": kv.KV_PATH_ZEROCOPY, "dma": kv.KV_PATH_DMA, "events": kv.KV_PATH_ZEROCOPY | kv.KV_REQ_EVENTS,
+             "dma_events": kv.KV_PATH_DMA | kv.KV_REQ_EVENTS}[mode]
+    bounce = torch.zeros(2 * 7 * g.S, dtype=torch.uint8, device="cuda") if "dma" in mode else None
+    evict, load = torch.cuda.Stream(), torch.cuda.Stream()
+    kp = kv.KVPool(g, pool, staging, bounce=bounce, flags=flags, evict_stream=evict, load_stream=load)
+    # A bounded spin kernel (torch's own test utility) holds one of the two streams back while a whole chunk of
+    # the history is enqueued: everything on that stream is then pending when the other stream's calls arrive, so
+    # every dependency between the streams is a live one.  Calibrated to about 40 ms.
+    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0.record()
+    torch.cuda._sleep(1_000_000)
+    t1.record()
+    t1.synchronize()
+    spin = int(40.0 / max(t0.elapsed_time(t1), 1e-3) * 1_000_000)
+    if "events" in mode:
+        assert kp.tune(kv.KV_TUNE_SEGMENT_BYTES, 2 * g.S) == kv.KV_OK
+        assert kp.tune(kv.KV_TUNE_SEGMENT_MAX_BYTES, 3 * g.S) == kv.KV_OK
+    rng = np.random.default_rng(1000 * seed + len(mode))
+    h = History(g, rng, n_req=10, cap=40)
+    both = Both(kp, ora)
+    enqueue_ms = []
+    for chunk in range(6):
+        with torch.cuda.stream(evict if chunk % 2 == 0 else load):
+            torch.cuda._sleep(spin)
+        t_host = time.perf_counter()
+        for _ in range(60):
+            h.step(both)
+        enqueue_ms.append((time.perf_counter() - t_host) * 1e3)
+        both.replay()
+        assert kp.sync() == kv.KV_OK
+        assert np.array_equal(staging.numpy(), a.staging), "arena differs after chunk %d" % chunk
+        assert np.array_equal(pool.cpu().numpy(), a.pool), "pool differs after chunk %d" % chunk
+        for r in h.table:
+            assert kp.query(r) == ora.query(r)
+    assert both.calls > 150
+    assert max(enqueue_ms) < 40.0, "the host took longer than the spin: the streams were not held back"
+    kp.close()
