@@ -249,10 +249,22 @@ class Planner {
     for (int64_t i = 0; i < n; i++)
       if (src[i] < 0 || src[i] >= N_ || dst[i] < 0 || dst[i] >= N_) return KV_ERANGE;
     if (has_duplicates(dst, n)) return KV_EDUP;
-    mark_.assign((size_t)((N_ + 63) / 64), 0);
-    for (int64_t i = 0; i < n; i++) mark_[(size_t)(src[i] >> 6)] |= 1ull << (src[i] & 63);
-    for (int64_t i = 0; i < n; i++)
-      if (mark_[(size_t)(dst[i] >> 6)] >> (dst[i] & 63) & 1) return KV_EDUP;
+    if (sparse(n)) {  // a destination that is also a source: merge of the two sorted lists
+      sorted_.assign(dst, dst + n);  // has_duplicates left `sorted_` = sorted dst, but be explicit
+      std::sort(sorted_.begin(), sorted_.end());
+      sorted2_.assign(src, src + n);
+      std::sort(sorted2_.begin(), sorted2_.end());
+      size_t i = 0, j = 0;
+      while (i < sorted_.size() && j < sorted2_.size()) {
+        if (sorted_[i] == sorted2_[j]) return KV_EDUP;
+        sorted_[i] < sorted2_[j] ? i++ : j++;
+      }
+    } else {
+      mark_.assign((size_t)((N_ + 63) / 64), 0);
+      for (int64_t i = 0; i < n; i++) mark_[(size_t)(src[i] >> 6)] |= 1ull << (src[i] & 63);
+      for (int64_t i = 0; i < n; i++)
+        if (mark_[(size_t)(dst[i] >> 6)] >> (dst[i] & 63) & 1) return KV_EDUP;
+    }
     for (int64_t i = 0; i < n; i++) out->desc.push_back({src[i], dst[i]});
     return KV_OK;
   }
@@ -274,7 +286,16 @@ class Planner {
     return KV_OK;
   }
 
+  // A bitmap over all N blocks costs N/64 words per call; for a list that is short against the pool (token-level
+  // pools have millions of blocks) sorting the list is cheaper.
+  bool sparse(int64_t n) const { return n * 512 < N_; }
+
   bool has_duplicates(const int32_t* ids, int64_t n) {
+    if (sparse(n)) {
+      sorted_.assign(ids, ids + n);
+      std::sort(sorted_.begin(), sorted_.end());
+      return std::adjacent_find(sorted_.begin(), sorted_.end()) != sorted_.end();
+    }
     mark_.assign((size_t)((N_ + 63) / 64), 0);
     for (int64_t i = 0; i < n; i++) {
       uint64_t& w = mark_[(size_t)(ids[i] >> 6)];
@@ -334,6 +355,7 @@ class Planner {
   std::vector<Undo> undo_;
   std::vector<int32_t> moved_;
   std::vector<uint64_t> mark_;
+  std::vector<int32_t> sorted_, sorted2_;
   std::pair<int64_t, int64_t> last_fresh_{0, 0};
 };
 

@@ -385,3 +385,32 @@ def test_write_queue_random_against_oracle(seed):
             table[r] = new
             queued.pop(r)                                    # the library dropped its entry at the swap-in
     kp.close()
+
+
+def test_duplicate_checks_on_a_pool_of_millions_of_blocks():
+    """Token-level pools: short lists are checked by sorting, not with a bitmap over the whole pool.  Same answers."""
+    g = W.Geometry(1, 1, 8, 1, "f16", 3_000_000)
+    kp = kv.KVPool(g, flags=kv.KV_PLAN_ONLY, staging_bytes=4096 * g.S)
+    rng = np.random.default_rng(3)
+    blocks = rng.choice(g.N, size=600, replace=False).astype(np.int32)
+    assert kp.swap_out([1], [0, 300], blocks[:300], [300]) == kv.KV_OK
+    dup = blocks[300:600].copy()
+    dup[17] = dup[250]
+    assert kp.swap_in([1], [0, 300], dup) == kv.KV_EDUP
+    assert kp.query(1)[1]["swapped"] == 1                       # nothing changed
+    assert kp.swap_in([1], [0, 300], blocks[300:600]) == kv.KV_OK
+    # moves: a repeated destination, a destination that is also a source, and a clean one
+    src, dst = blocks[:100], blocks[100:200]
+    bad = dst.copy(); bad[3] = bad[99]
+    assert kp.move_blocks(src, bad) == kv.KV_EDUP
+    bad = dst.copy(); bad[50] = src[7]
+    assert kp.move_blocks(src, bad) == kv.KV_EDUP
+    assert kp.move_blocks(src, dst) == kv.KV_OK
+    phys, slot = kp.last_plan()
+    assert phys.tolist() == src.tolist() and slot.tolist() == dst.tolist()
+    # a long list on the same pool takes the bitmap again: same answers
+    big = rng.choice(g.N, size=20000, replace=False).astype(np.int32)
+    assert kp.move_blocks(big[:10000], big[10000:]) == kv.KV_OK
+    bad = big[10000:].copy(); bad[5] = big[77]
+    assert kp.move_blocks(big[:10000], bad) == kv.KV_EDUP
+    kp.close()
