@@ -327,6 +327,14 @@ def main():
                  "measured_peak_bidirectional_gbps": None if link_bidir is None else round(link_bidir, 2),
                  "kernel_out_ms": round(m["out_k"], 2), "kernel_in_ms": round(m["in_k"], 2),
                  "how": "one 1 GiB contiguous pinned hipMemcpyAsync per direction, in this run"},
+        "roofline_link": {"bound": "host-link", "kernel": "kv_move_kernel<0,4,1,true> (burst swap-out; the longest launch "
+                          "of a step, bound by the host link and not by HBM)",
+                          "achieved": round(P / m["out_k"] / 1e6, 2), "peak": 64.0, "unit": "GB/s",
+                          "frac": round(P / m["out_k"] / 1e6 / 64.0, 4), "launch_ms": round(m["out_k"], 2),
+                          "bytes_per_launch": P, "measured_peak": round(link_d2h, 2),
+                          "frac_of_measured_peak": round(P / m["out_k"] / 1e6 / link_d2h, 4),
+                          "peak_def": "PCIe Gen5 x16, 64 GB/s raw per direction; measured_peak = one contiguous "
+                                      "hipMemcpyAsync in this run"},
         "roofline": {"bound": "hbm", "kernel": "kv_move_kernel<1,1,0,true> (scatter, both ends in HBM)",
                      "achieved": round(scatter_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(scatter_gbs / HBM_PEAK_GBS, 4),
