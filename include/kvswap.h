@@ -153,7 +153,8 @@ typedef struct {
   double plan_us;   /* host time spent validating and building descriptors */
   double enqueue_us; /* host time spent inside HIP enqueue calls */
   float ms_total;   /* first enqueue to last completion on the stream (HIP events) */
-  float ms_kernel;  /* summed duration of the data kernels (HIP events around each launch) */
+  float ms_kernel;  /* summed duration of the data kernels (HIP events around each launch); a call that is a
+                       single launch and nothing else carries no events of its own and reports ms_total */
 } kv_stats;
 
 /* Create a handle over caller-owned memory.  Validates geometry, alignment and
