@@ -165,13 +165,13 @@ def test_random_history_without_host_sync(gpu, mode, seed):
     kp = kv.KVPool(g, pool, staging, bounce=bounce, flags=flags, evict_stream=evict, load_stream=load)
     # A bounded spin kernel (torch's own test utility) holds one of the two streams back while a whole chunk of
     # the history is enqueued: everything on that stream is then pending when the other stream's calls arrive, so
-    # every dependency between the streams is a live one.  Calibrated to about 40 ms.
+    # every dependency between the streams is a live one.  Calibrated to about 150 ms.
     t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0.record()
     torch.cuda._sleep(1_000_000)
     t1.record()
     t1.synchronize()
-    spin = int(40.0 / max(t0.elapsed_time(t1), 1e-3) * 1_000_000)
+    spin = int(150.0 / max(t0.elapsed_time(t1), 1e-3) * 1_000_000)
     if "events" in mode:
         assert kp.tune(kv.KV_TUNE_SEGMENT_BYTES, 2 * g.S) == kv.KV_OK
         assert kp.tune(kv.KV_TUNE_SEGMENT_MAX_BYTES, 3 * g.S) == kv.KV_OK
@@ -193,5 +193,5 @@ def test_random_history_without_host_sync(gpu, mode, seed):
         for r in h.table:
             assert kp.query(r) == ora.query(r)
     assert both.calls > 150
-    assert max(enqueue_ms) < 40.0, "the host took longer than the spin: the streams were not held back"
+    assert max(enqueue_ms) < 150.0, "the host took longer than the spin: the streams were not held back"
     kp.close()
