@@ -414,3 +414,23 @@ def test_duplicate_checks_on_a_pool_of_millions_of_blocks():
     bad = big[10000:].copy(); bad[5] = big[77]
     assert kp.move_blocks(big[:10000], bad) == kv.KV_EDUP
     kp.close()
+
+
+def test_binding_fails_loudly_without_the_library(tmp_path):
+    """No fallback path: a copy of the package without libkvswap.so must refuse to import."""
+    import shutil
+    import subprocess
+    import sys
+    pkg = tmp_path / "paper_2510_02758_amd"
+    shutil.copytree(os.path.join(ROOT, "paper_2510_02758_amd"), pkg,
+                    ignore=shutil.ignore_patterns("*.so", "__pycache__", "csrc"))
+    code = ("import sys; sys.path.insert(0, %r)\n"
+            "try:\n    import paper_2510_02758_amd.kvswap\n"
+            "except ImportError as e:\n    print('refused:', e); sys.exit(7)\n"
+            "sys.exit(0)\n" % str(tmp_path))
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300, cwd=str(tmp_path))
+    assert r.returncode == 7 and "libkvswap.so is not built" in r.stdout, r.stdout + r.stderr
+    # the scheduler binding lives in the same library and refuses too
+    code = code.replace("paper_2510_02758_amd.kvswap", "paper_2510_02758_amd.kvsched")
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300, cwd=str(tmp_path))
+    assert r.returncode == 7, r.stdout + r.stderr
