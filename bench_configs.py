@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Per-configuration figures beside bench.py (which times the Llama-3-8B burst).
 
-    python -m paper_2510_02758_amd.bench_configs --config 1|3|4|5
+    python bench_configs.py --config 1|3|4|5|6|7
 
 Each run prints one JSON line.  Synthetic seeded inputs (workloads.py); the same
 library entry points as everywhere else; the CPU oracle is timed next to it on a
@@ -31,7 +31,7 @@ import time
 
 import numpy as np
 
-ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 

@@ -434,3 +434,22 @@ def test_binding_fails_loudly_without_the_library(tmp_path):
     code = code.replace("paper_2510_02758_amd.kvswap", "paper_2510_02758_amd.kvsched")
     r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300, cwd=str(tmp_path))
     assert r.returncode == 7, r.stdout + r.stderr
+
+
+def test_oracle_and_product_do_not_know_each_other():
+    """The package (binding, workloads, simulator, native sources) never imports or includes the oracle, and the
+    oracle never imports or includes the package: only tests, the smoke entry and the benchmark scripts at the repository root bring them together."""
+    pkg = os.path.join(ROOT, "paper_2510_02758_amd")
+    for d, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".inc", ".hpp", ".cpp", ".h")):
+                text = open(os.path.join(d, f), errors="ignore").read()
+                assert not re.search(r"^\s*(from|import)\s+oracle\b|#include\s+\"[^\"]*oracle", text, flags=re.M), \
+                    "%s uses the oracle" % f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c", ".h")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert not re.search(r"^\s*(from|import)\s+paper_2510_02758_amd", text, flags=re.M), f
+            assert '#include "../paper' not in text and "csrc/" not in text.replace("paper_2510_02758_amd/csrc/scheduler.cpp", ""), f
+    for f in os.listdir(os.path.join(ROOT, "include")):
+        assert "oracle" not in open(os.path.join(ROOT, "include", f)).read()
