@@ -453,3 +453,27 @@ def test_oracle_and_product_do_not_know_each_other():
             assert '#include "../paper' not in text and "csrc/" not in text.replace("paper_2510_02758_amd/csrc/scheduler.cpp", ""), f
     for f in os.listdir(os.path.join(ROOT, "include")):
         assert "oracle" not in open(os.path.join(ROOT, "include", f)).read()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is a one-GPU benchmark: any other --gpus ends with a message and a non-zero status before
+    anything touches a GPU."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2", "--steps", "1", "--warmup", "0"],
+                       capture_output=True, text=True, timeout=300)
+    assert r.returncode != 0 and "one-GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_bench_oracle_leg_runs_on_the_cpu():
+    """The cpu_baseline leg of bench.py is the oracle and nothing else: it runs here, on a tiny sample."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("bench_module", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    wl = W.config(2)
+    lens = W.request_lengths(wl.seed, wl.n_requests, wl.length_dist)
+    off, ids, free = W.block_tables(wl.seed, wl.geom.N, W.blocks_for(lens, wl.geom.B))
+    out = bench.cpu_baseline(W, wl, lens, off, ids, 1)
+    assert out["kind"] == "oracle" and out["cores"] == 1 and out["unit"] == "GB/s" and out["value"] > 0
+    assert "first 1 of the 64 requests" in out["sample"]
