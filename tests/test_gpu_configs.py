@@ -9,6 +9,8 @@ address coded, so
     own fill must be exactly the set of destination blocks.
 Bar: bit-exact.
 """
+import os
+
 import numpy as np
 import pytest
 
@@ -327,3 +329,31 @@ def test_config5_fp8_scales_under_contention(gpu):
     assert np.array_equal(DC.changed_blocks(scale, g, g.scale_strides, sseed, dtype="raw", width=g.scale_chunk),
                           np.sort(new))
     kp.close()
+
+
+@pytest.mark.gpu
+def test_bench_line_has_the_agreed_shape(gpu):
+    """bench.py on a half-size pool (same burst, same launches): one JSON line with the agreed fields."""
+    import json
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--blocks", "20000", "--steps", "2", "--warmup", "1",
+                        "--cpu-sample", "1"], capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [ln for ln in r.stdout.splitlines() if ln.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    for k in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+              "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert k in d, k
+    assert d["n_gpus"] == 1 and d["steps"] == 2 and d["warmup"] == 1 and d["unit"] == "GB/s" and d["dtype"] == "u8"
+    assert d["higher_is_better"] is True and d["vs_baseline"] is None and d["data"] == "synthetic"
+    assert "workload" in d["config"] and "model" not in d["config"]
+    rf = d["roofline"]
+    assert rf["bound"] == "hbm" and rf["unit"] == "GB/s" and rf["peak"] == 8000.0
+    assert abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-3 and 0.3 < rf["frac"] < 1.0
+    assert "traffic" in rf and rf["bytes_per_launch"] == 2 * 9083 * (2 << 20)
+    cb = d["cpu_baseline"]
+    assert cb["kind"] == "oracle" and cb["cores"] == 1 and cb["unit"] == "GB/s" and cb["value"] > 0 and cb["sample"]
+    assert 30.0 < d["value"] < 64.0 and 30.0 < d["legs"]["d2h_gbps"] < 64.0 and 30.0 < d["legs"]["h2d_gbps"] < 64.0
