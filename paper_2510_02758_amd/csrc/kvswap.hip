@@ -981,7 +981,15 @@ int kv_sync(kv_pool* p) {
 int kv_req_reserve(kv_pool* p, uint64_t req_id, int32_t max_blocks) {
   if (!p) return KV_EINVAL;
   std::lock_guard<std::mutex> g(p->mu);
-  return p->planner.reserve(req_id, max_blocks);
+  int rc = p->planner.reserve(req_id, max_blocks);
+  if (rc || p->plan_only) return rc;
+  // The extent may lie on slots that an unfinished swap-in of their previous owner still reads: whatever
+  // this request writes there first has to wait for it, exactly as for an extent taken inside a swap-out.
+  const auto run = p->planner.last_fresh();
+  const uint64_t dep = pending_reader(p, {run});
+  if (dep && !seq_done(p, dep))
+    if (kvswap::Req* r = p->planner.find_mut(req_id)) r->in_seq = dep;
+  return KV_OK;
 }
 
 int kv_req_release(kv_pool* p, uint64_t req_id) {

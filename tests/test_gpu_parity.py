@@ -634,6 +634,45 @@ def test_control_thread_polls_while_the_main_thread_enqueues(gpu):
     kp.close()
 
 
+def test_reserved_extent_waits_for_the_previous_owners_swap_in(gpu):
+    """Request A is swapped in without KV_KEEP_STAGING (its slots are free again the moment the call returns)
+    while the load stream is held back by a bounded spin kernel; request B then reserves the same slots and is
+    swapped out into them.  B's write must wait for A's read: A's new blocks have to receive A's data."""
+    import torch
+    g = W.Geometry(8, 8, 128, 16, "bf16", 300)              # 512 KiB blocks
+    a = HostPool(g, 0xABBA, slots=64)
+    ora = a.oracle()
+    pool = torch.from_numpy(a.pool.copy()).cuda()
+    staging = torch.full((len(a.staging),), CANARY, dtype=torch.uint8).pin_memory()
+    evict, load = torch.cuda.Stream(), torch.cuda.Stream()
+    kp = kv.KVPool(g, pool, staging, evict_stream=evict, load_stream=load)
+    perm = np.random.default_rng(2).permutation(g.N).astype(np.int32)
+    A_src, A_dst, B_src = perm[:60], perm[60:120], perm[120:180]
+    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0.record(); torch.cuda._sleep(1_000_000); t1.record(); t1.synchronize()
+    spin = int(100.0 / max(t0.elapsed_time(t1), 1e-3) * 1_000_000)   # about 100 ms
+
+    def script(o, hold):
+        assert o.swap_out([1], [0, 60], A_src, [60 * g.B]) == 0
+        hold()
+        assert o.swap_in([1], [0, 60], A_dst, 0) == 0       # extent of request 1 is released here
+        assert o.reserve(2, 60) == 0                         # first fit: the same 60 slots
+        assert o.swap_out([2], [0, 60], B_src, [60 * g.B]) == 0
+
+    def hold():
+        assert kp.sync() == kv.KV_OK
+        with torch.cuda.stream(load):
+            torch.cuda._sleep(spin)
+
+    script(kp, hold)
+    assert kp.query(2)[1]["offset"] == 0                     # B really sits on A's old slots
+    assert kp.sync() == kv.KV_OK
+    script(ora, lambda: None)
+    assert np.array_equal(pool.cpu().numpy(), a.pool), "request 1 was loaded from slots request 2 had already overwritten"
+    assert np.array_equal(staging.numpy(), a.staging)
+    kp.close()
+
+
 def test_create_checks_memory_kinds(gpu):
     import torch
     g = W.Geometry(2, 4, 64, 16, "f16", 64)

@@ -149,7 +149,7 @@ class _Lib:
         return self.kp.move_blocks(src, dst)
 
 
-@pytest.mark.parametrize("seed", [1, 2])
+@pytest.mark.parametrize("seed", [1, 3])
 @pytest.mark.parametrize("mode", ["zerocopy", "dma", "events", "dma_events"])
 def test_random_history_without_host_sync(gpu, mode, seed):
     import torch
