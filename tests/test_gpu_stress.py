@@ -84,7 +84,13 @@ class History:
                 return
             self.table[r] = [self.free.pop() for _ in range(nb)]   # LIFO: the blocks freed a moment ago
             off, blk = self.csr([r])
-            both(lambda o: o.swap_in([r], off, blk, kv.KV_KEEP_STAGING))
+            if rng.random() < 0.7:
+                both(lambda o: o.swap_in([r], off, blk, kv.KV_KEEP_STAGING))
+            else:
+                # give the host image up with the load (its slots are free the moment the call returns) and take a
+                # new extent at once: first fit tends to hand back slots that the load has not read yet
+                both(lambda o: o.swap_in([r], off, blk, 0))
+                both(lambda o: o.reserve(r, self.cap))
             self.state[r] = "running"
         elif op == "move" and running:
             r = int(rng.choice(running))
