@@ -156,16 +156,17 @@ class _Lib:
 
 
 @pytest.mark.parametrize("seed", [1, 3])
-@pytest.mark.parametrize("mode", ["zerocopy", "dma", "events", "dma_events"])
+@pytest.mark.parametrize("mode", ["zerocopy", "dma", "events", "dma_events", "device_events"])
 def test_random_history_without_host_sync(gpu, mode, seed):
     import torch
     g = W.Geometry(16, 8, 128, 16, "bf16", 700)             # 1 MiB blocks
     a = HostPool(g, 0xD1CE + seed, slots=480)
     ora = a.oracle()
     pool = torch.from_numpy(a.pool.copy()).cuda()
-    staging = torch.full((len(a.staging),), CANARY, dtype=torch.uint8).pin_memory()
+    staging = torch.full((len(a.staging),), CANARY, dtype=torch.uint8)
+    staging = staging.cuda() if mode.startswith("device") else staging.pin_memory()
     flags = {"zerocopy": kv.KV_PATH_ZEROCOPY, "dma": kv.KV_PATH_DMA, "events": kv.KV_PATH_ZEROCOPY | kv.KV_REQ_EVENTS,
-             "dma_events": kv.KV_PATH_DMA | kv.KV_REQ_EVENTS}[mode]
+             "dma_events": kv.KV_PATH_DMA | kv.KV_REQ_EVENTS, "device_events": kv.KV_STAGING_DEVICE | kv.KV_REQ_EVENTS}[mode]
     bounce = torch.zeros(2 * 7 * g.S, dtype=torch.uint8, device="cuda") if "dma" in mode else None
     evict, load = torch.cuda.Stream(), torch.cuda.Stream()
     kp = kv.KVPool(g, pool, staging, bounce=bounce, flags=flags, evict_stream=evict, load_stream=load)
@@ -194,7 +195,7 @@ def test_random_history_without_host_sync(gpu, mode, seed):
         enqueue_ms.append((time.perf_counter() - t_host) * 1e3)
         both.replay()
         assert kp.sync() == kv.KV_OK
-        assert np.array_equal(staging.numpy(), a.staging), "arena differs after chunk %d" % chunk
+        assert np.array_equal(staging.cpu().numpy(), a.staging), "arena differs after chunk %d" % chunk
         assert np.array_equal(pool.cpu().numpy(), a.pool), "pool differs after chunk %d" % chunk
         for r in h.table:
             assert kp.query(r) == ora.query(r)
