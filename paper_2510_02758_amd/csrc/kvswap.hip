@@ -668,12 +668,23 @@ int close_call(kv_pool* p, Call& c) {
   return KV_OK;
 }
 
-// Newest unfinished load-stream call that still reads any slot in the given runs.
-uint64_t pending_reader(kv_pool* p, const std::vector<std::pair<int64_t, int64_t>>& runs) {
+// The call with this sequence number, if it is unfinished and runs on another stream than `stream`
+// (work of the same stream is ordered by the stream itself); 0 otherwise.
+uint64_t cross_stream(kv_pool* p, int stream, uint64_t seq) {
+  if (!seq) return 0;
+  Call* c = find_call(p, seq);
+  if (!c || c->stream == stream || seq_done(p, seq)) return 0;
+  return seq;
+}
+
+// Newest unfinished call of another stream that still uses any slot in the given runs (slots of released
+// extents and of swap-ins that gave their extent up).  Candidates of the caller's own stream are skipped
+// one by one, so that a newer same-stream entry cannot hide an older one of the other stream.
+uint64_t pending_user(kv_pool* p, int stream, const std::vector<std::pair<int64_t, int64_t>>& runs) {
   uint64_t s = 0;
   for (auto& r : runs)
     for (auto& q : p->pending)
-      if (q.lo < r.first + r.second && r.first < q.hi) s = std::max(s, q.seq);
+      if (q.lo < r.first + r.second && r.first < q.hi) s = std::max(s, cross_stream(p, stream, q.seq));
   return s;
 }
 
@@ -854,8 +865,7 @@ static int swap_out_common(kv_pool* p, int op, Plan& plan, double t0, void* wait
     return KV_OK;
   }
   // slots this call writes may still be read by an unfinished swap-in
-  uint64_t dep = std::max(plan.wait_in_seq, pending_reader(p, plan.fresh));
-  if (dep && seq_done(p, dep)) dep = 0;
+  const uint64_t dep = std::max(cross_stream(p, kEvict, plan.wait_in_seq), pending_user(p, kEvict, plan.fresh));
   if (plan.desc.empty() && !wait_event) {  // nothing to enqueue
     p->plan_stats = kv_stats{};
     fill_plan_stats(p, &p->plan_stats, op, 0, t1 - t0);
@@ -917,8 +927,7 @@ int kv_swap_in(kv_pool* p, int32_t n, const uint64_t* req_ids, const int32_t* of
     fill_plan_stats(p, &p->plan_stats, 3, plan.desc.size(), t1 - t0);
     return KV_OK;
   }
-  uint64_t dep = plan.wait_out_seq;
-  if (dep && seq_done(p, dep)) dep = 0;
+  const uint64_t dep = cross_stream(p, kLoad, plan.wait_out_seq);
   if (plan.desc.empty() && !wait_event) {
     p->plan_stats = kv_stats{};
     fill_plan_stats(p, &p->plan_stats, 3, 0, t1 - t0);
@@ -986,8 +995,8 @@ int kv_req_reserve(kv_pool* p, uint64_t req_id, int32_t max_blocks) {
   // The extent may lie on slots that an unfinished swap-in of their previous owner still reads: whatever
   // this request writes there first has to wait for it, exactly as for an extent taken inside a swap-out.
   const auto run = p->planner.last_fresh();
-  const uint64_t dep = pending_reader(p, {run});
-  if (dep && !seq_done(p, dep))
+  const uint64_t dep = pending_user(p, kEvict, {run});  // the extent's first use is a write on the evict stream
+  if (dep)
     if (kvswap::Req* r = p->planner.find_mut(req_id)) r->in_seq = dep;
   return KV_OK;
 }
@@ -999,9 +1008,9 @@ int kv_req_release(kv_pool* p, uint64_t req_id) {
   int rc = p->planner.release(req_id, &was);
   if (!rc) p->wq.erase(req_id);
   if (rc || p->plan_only) return rc;
-  // the slots may still be in use by unfinished work of either stream: later writers wait for it
-  const uint64_t s = std::max(was.in_seq, was.out_seq);
-  if (s && was.cap && !seq_done(p, s)) p->pending.push_back({was.base, was.base + was.cap, s});
+  // the slots may still be in use by unfinished work of either stream: later users wait for it
+  for (uint64_t s : {was.in_seq, was.out_seq})
+    if (s && was.cap && !seq_done(p, s)) p->pending.push_back({was.base, was.base + was.cap, s});
   return KV_OK;
 }
 

@@ -649,8 +649,9 @@ def test_reserved_extent_waits_for_the_previous_owners_swap_in(gpu):
     perm = np.random.default_rng(2).permutation(g.N).astype(np.int32)
     A_src, A_dst, B_src = perm[:60], perm[60:120], perm[120:180]
     t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0.record(); torch.cuda._sleep(1_000_000); t1.record(); t1.synchronize()
-    spin = int(100.0 / max(t0.elapsed_time(t1), 1e-3) * 1_000_000)   # about 100 ms
+    torch.cuda._sleep(1_000_000)                              # first launch of the spin kernel: not timed
+    t0.record(); torch.cuda._sleep(20_000_000); t1.record(); t1.synchronize()
+    spin = int(100.0 / max(t0.elapsed_time(t1), 1e-3) * 20_000_000)   # about 100 ms
 
     def script(o, hold):
         assert o.swap_out([1], [0, 60], A_src, [60 * g.B]) == 0
@@ -669,6 +670,53 @@ def test_reserved_extent_waits_for_the_previous_owners_swap_in(gpu):
     assert kp.sync() == kv.KV_OK
     script(ora, lambda: None)
     assert np.array_equal(pool.cpu().numpy(), a.pool), "request 1 was loaded from slots request 2 had already overwritten"
+    assert np.array_equal(staging.numpy(), a.staging)
+    kp.close()
+
+
+def test_new_extent_over_slots_of_two_previous_owners(gpu):
+    """An extent that covers the old slots of two requests: one whose swap-in (load stream, held back) still reads
+    its slots, and one whose eviction (evict stream) is the newer call.  The newer same-stream call must not hide
+    the older dependency on the other stream."""
+    import torch
+    g = W.Geometry(8, 8, 128, 16, "bf16", 400)              # 512 KiB blocks
+    a = HostPool(g, 0xD0D0, slots=80)
+    ora = a.oracle()
+    pool = torch.from_numpy(a.pool.copy()).cuda()
+    staging = torch.full((len(a.staging),), CANARY, dtype=torch.uint8).pin_memory()
+    evict, load = torch.cuda.Stream(), torch.cuda.Stream()
+    kp = kv.KVPool(g, pool, staging, evict_stream=evict, load_stream=load)
+    perm = np.random.default_rng(6).permutation(g.N).astype(np.int32)
+    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda._sleep(1_000_000)                              # first launch of the spin kernel: not timed
+    t0.record(); torch.cuda._sleep(20_000_000); t1.record(); t1.synchronize()
+    per_ms = 20_000_000 / max(t0.elapsed_time(t1), 1e-3)
+
+    def script(o, hold):
+        assert o.reserve(1, 30) == 0                                      # slots [0, 30)
+        assert o.reserve(4, 1) == 0                                       # [30, 31): keeps the two runs apart for now
+        assert o.swap_out([1], [0, 30], perm[:30], [30 * g.B]) == 0
+        hold()
+        assert o.swap_in([1], [0, 30], perm[30:60], 0) == 0               # load stream; gives [0, 30) up
+        assert o.reserve(3, 40) == 0                                      # does not fit there: [31, 71)
+        assert o.swap_out([3], [0, 40], perm[60:100], [40 * g.B]) == 0    # evict stream, the newer call
+        assert o.release(3) == 0
+        assert o.release(4) == 0
+        assert o.reserve(2, 70) == 0                                      # [0, 70): over both
+        assert o.swap_out([2], [0, 70], perm[100:170], [70 * g.B]) == 0
+
+    def hold():
+        assert kp.sync() == kv.KV_OK
+        with torch.cuda.stream(load):
+            torch.cuda._sleep(int(120 * per_ms))
+        with torch.cuda.stream(evict):
+            torch.cuda._sleep(int(20 * per_ms))
+
+    script(kp, hold)
+    assert kp.query(2)[1]["offset"] == 0 and kp.query(2)[1]["cap"] == 70
+    assert kp.sync() == kv.KV_OK
+    script(ora, lambda: None)
+    assert np.array_equal(pool.cpu().numpy(), a.pool), "request 1 was loaded from slots that request 2 had overwritten"
     assert np.array_equal(staging.numpy(), a.staging)
     kp.close()
 

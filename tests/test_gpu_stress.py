@@ -174,11 +174,12 @@ def test_random_history_without_host_sync(gpu, mode, seed):
     # the history is enqueued: everything on that stream is then pending when the other stream's calls arrive, so
     # every dependency between the streams is a live one.  Calibrated to about 150 ms.
     t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda._sleep(1_000_000)                             # first launch of the spin kernel: not timed
     t0.record()
-    torch.cuda._sleep(1_000_000)
+    torch.cuda._sleep(20_000_000)
     t1.record()
     t1.synchronize()
-    spin = int(150.0 / max(t0.elapsed_time(t1), 1e-3) * 1_000_000)
+    spin = int(150.0 / max(t0.elapsed_time(t1), 1e-3) * 20_000_000)
     if "events" in mode:
         assert kp.tune(kv.KV_TUNE_SEGMENT_BYTES, 2 * g.S) == kv.KV_OK
         assert kp.tune(kv.KV_TUNE_SEGMENT_MAX_BYTES, 3 * g.S) == kv.KV_OK
