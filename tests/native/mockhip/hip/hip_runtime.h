@@ -1,0 +1,94 @@
+// A host-only stand-in for the part of the HIP runtime that the swap library uses, for CPU tests.
+//
+// It lets the REAL host runtime (runtime.hip.inc, kvswap.hip) and the REAL kernel source (kernels.hip.inc)
+// be compiled by a host compiler and run on the CPU: streams are in-order queues of operations, events carry
+// the generation they were last recorded with, hipStreamWaitEvent captures the generation at the time of the
+// call, copies read their source when they EXECUTE (as a copy engine does), and a kernel launch runs the kernel
+// body once per (workgroup, lane) with threadIdx / blockIdx set.  Nothing executes when it is enqueued: an
+// executor picks, among the streams whose head operation may run, one according to a policy chosen by the test
+// (random, or always starving one stream), so the test decides how far the "GPU" lags behind the host and which
+// stream runs ahead.  "Device" and "pinned" memory are plain malloc blocks, so AddressSanitizer checks every
+// access the kernels make.  __syncthreads() is a no-op: lanes run to completion one after the other, so kernel
+// paths that exchange data through LDS are not emulated and the tests keep them switched off.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+#include <cstdlib>
+#include <cstring>
+#include <functional>
+
+typedef int hipError_t;
+enum { hipSuccess = 0, hipErrorInvalidValue = 1, hipErrorOutOfMemory = 2, hipErrorNotReady = 600 };
+enum { hipStreamNonBlocking = 1 };
+enum { hipHostMallocDefault = 0 };
+enum hipMemcpyKind { hipMemcpyHostToDevice = 1, hipMemcpyDeviceToHost = 2, hipMemcpyDeviceToDevice = 3 };
+enum hipMemoryType { hipMemoryTypeHost = 1, hipMemoryTypeDevice = 2 };
+typedef void* hipDeviceptr_t;
+struct hipPointerAttribute_t { int type; void* devicePointer; void* hostPointer; };
+struct hipDeviceProp_t { int multiProcessorCount; };
+struct dim3 { unsigned x, y, z; dim3(unsigned a = 1, unsigned b = 1, unsigned c = 1) : x(a), y(b), z(c) {} };
+
+namespace mockhip {
+struct Stream;
+struct Event;
+struct Idx { unsigned x, y, z; };
+extern Idx threadIdx_, blockIdx_, gridDim_, blockDim_;
+enum Policy { kRandom = 0, kStarve0 = 1, kStarve1 = 2, kLazy = 3 };
+// test control
+void reset(uint64_t seed);
+void set_policy(int policy, Stream* starved);
+void enqueue(Stream* s, std::function<void()> fn);
+long executed_ops();
+long deadlocks();
+}  // namespace mockhip
+
+typedef mockhip::Stream* hipStream_t;
+typedef mockhip::Event* hipEvent_t;
+
+#define threadIdx mockhip::threadIdx_
+#define blockIdx mockhip::blockIdx_
+#define gridDim mockhip::gridDim_
+#define blockDim mockhip::blockDim_
+#define __global__
+#define __launch_bounds__(n)
+#define __shared__
+#define __restrict__
+inline void __syncthreads() {}
+
+hipError_t hipGetLastError();
+hipError_t hipGetDevice(int* dev);
+hipError_t hipGetDeviceProperties(hipDeviceProp_t* prop, int dev);
+hipError_t hipMalloc(void** p, size_t n);
+hipError_t hipFree(void* p);
+hipError_t hipHostMalloc(void** p, size_t n, unsigned flags);
+hipError_t hipHostFree(void* p);
+hipError_t hipMemGetAddressRange(hipDeviceptr_t* base, size_t* size, hipDeviceptr_t p);
+hipError_t hipPointerGetAttributes(hipPointerAttribute_t* at, const void* p);
+hipError_t hipStreamCreateWithFlags(hipStream_t* s, unsigned flags);
+hipError_t hipStreamDestroy(hipStream_t s);
+hipError_t hipStreamSynchronize(hipStream_t s);
+hipError_t hipStreamWaitEvent(hipStream_t s, hipEvent_t e, unsigned flags);
+hipError_t hipEventCreate(hipEvent_t* e);
+hipError_t hipEventDestroy(hipEvent_t e);
+hipError_t hipEventRecord(hipEvent_t e, hipStream_t s);
+hipError_t hipEventQuery(hipEvent_t e);
+hipError_t hipEventSynchronize(hipEvent_t e);
+hipError_t hipEventElapsedTime(float* ms, hipEvent_t a, hipEvent_t b);
+hipError_t hipMemcpyAsync(void* dst, const void* src, size_t n, hipMemcpyKind kind, hipStream_t s);
+
+// One kernel launch = one queued operation that runs the body for every lane of every workgroup.
+#define hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, ...)                      \
+  do {                                                                                     \
+    const dim3 g_ = (grid), b_ = (block);                                                  \
+    (void)(lds_bytes);                                                                     \
+    mockhip::enqueue((stream), [=]() {                                                     \
+      mockhip::gridDim_ = {g_.x, g_.y, g_.z};                                              \
+      mockhip::blockDim_ = {b_.x, b_.y, b_.z};                                             \
+      for (unsigned bx_ = 0; bx_ < g_.x; bx_++)                                            \
+        for (unsigned tx_ = 0; tx_ < b_.x; tx_++) {                                        \
+          mockhip::blockIdx_ = {bx_, 0, 0};                                                \
+          mockhip::threadIdx_ = {tx_, 0, 0};                                               \
+          kern(__VA_ARGS__);                                                               \
+        }                                                                                  \
+    });                                                                                    \
+  } while (0)

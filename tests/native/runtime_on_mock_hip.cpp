@@ -1,0 +1,338 @@
+// The swap library's host runtime AND its kernel source on the CPU, against the C oracle.
+//
+// Built by tests/test_native_sanitizers.py with a host compiler, AddressSanitizer + UBSan and the stand-in HIP
+// runtime of tests/native/mockhip: kvswap.hip (with runtime.hip.inc and kernels.hip.inc) is compiled unchanged;
+// streams are queues whose operations run when the stand-in's executor picks them, so this driver chooses how
+// far the "device" lags behind the host and which of the two streams is starved.  A seeded serving history
+// (growth with budgeted write-through, cold and warm preemption of one or several requests, resumption with and
+// without keeping the host image, compaction moves, releases, re-reservations) is played through the C ABI with
+// no synchronisation inside a chunk; blocks and slots given up by one call go to the next at once.  After every
+// chunk pool, scales and arena must equal what the oracle reaches by running the same calls one after the other,
+// and the per-request state must agree.  A missing wait between the streams shows up as a byte difference, a
+// wait that can never be satisfied as a reported deadlock, an out-of-bounds access of a kernel or of the host
+// code as a sanitizer error.
+//
+// usage: runtime_on_mock_hip <seed> <chunks>
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <map>
+#include <random>
+#include <vector>
+
+#include "kvswap.h"
+extern "C" {
+#include "../../oracle/kv_oracle.h"
+}
+
+namespace {
+
+[[noreturn]] void die(const char* what, int chunk, int step) {
+  std::fprintf(stderr, "MISMATCH in chunk %d at step %d: %s\n", chunk, step, what);
+  std::exit(1);
+}
+
+struct Geo {
+  int L, H, D, B, e, dtype;
+  int64_t N, chunk, block_bytes, scale_chunk, S, ls, ks, bs, sls, sks, sbs;
+};
+
+}  // namespace
+
+int main(int argc, char** argv) {
+  const uint64_t seed = argc > 1 ? std::strtoull(argv[1], nullptr, 10) : 1;
+  const int chunks = argc > 2 ? std::atoi(argv[2]) : 8;
+  std::mt19937_64 rng(seed * 7919 + 13);
+  auto rnd = [&](int64_t lo, int64_t hi) { return lo + (int64_t)(rng() % (uint64_t)(hi - lo + 1)); };
+  mockhip::reset(seed);
+
+  // ---- configuration of this run, all from the seed ----
+  Geo g;
+  switch (seed % 4) {
+    case 0: g = {2, 2, 8, 2, 2, KV_F16, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}; break;       // 64-byte chunks: several per job
+    case 1: g = {1, 4, 64, 8, 2, KV_BF16, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}; break;     // 4 KiB chunks: one piece each
+    case 2: g = {2, 4, 72, 16, 2, KV_F16, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}; break;     // 9 KiB chunks: ragged pieces
+    default: g = {3, 4, 32, 4, 1, KV_FP8_E4M3, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}; break; // fp8, 512-byte chunks, scales
+  }
+  const bool scales = seed % 4 == 3;
+  g.N = rnd(90, 140);
+  g.chunk = (int64_t)g.B * g.H * g.D * g.e;
+  g.block_bytes = 2 * g.L * g.chunk;
+  g.scale_chunk = scales ? g.H * 4 : 0;
+  g.S = g.block_bytes + 2 * g.L * g.scale_chunk;
+  const bool padded = (seed / 4) % 2 == 1;
+  g.bs = g.chunk + (padded ? 48 : 0);
+  g.ks = g.N * g.bs + (padded ? 32 : 0);
+  g.ls = 2 * g.ks + (padded ? 64 : 0);
+  g.sbs = g.scale_chunk + (padded ? 8 : 0);
+  g.sks = g.N * g.sbs + (padded ? 4 : 0);
+  g.sls = 2 * g.sks + (padded ? 12 : 0);
+  const int mode = (int)((seed / 8) % 3);            // 0 zero-copy, 1 copy engines, 2 device arena
+  const bool events = (seed / 24) % 2 == 1;
+  const int policy = (int)((seed / 48) % 4);         // random, starve evict, starve load, lazy
+  const int64_t slots = 70;
+  const int R = 9, cap_max = 20;
+
+  const size_t pool_bytes = (size_t)(g.L * g.ls), scale_bytes = (size_t)(scales ? g.L * g.sls : 16);
+  const size_t stag_bytes = (size_t)(slots * g.S + 24);
+  std::vector<uint8_t> pool_a(pool_bytes), scale_a(scale_bytes), stag_a(stag_bytes, 0xA5);
+  for (auto& b : pool_a) b = (uint8_t)rng();
+  for (auto& b : scale_a) b = (uint8_t)rng();
+  uint8_t *pool_b = nullptr, *scale_b = nullptr, *stag_b = nullptr, *bounce = nullptr;
+  if (hipMalloc((void**)&pool_b, pool_bytes) || hipMalloc((void**)&scale_b, scale_bytes)) return 3;
+  if (mode == 2 ? hipMalloc((void**)&stag_b, stag_bytes) : hipHostMalloc((void**)&stag_b, stag_bytes, 0)) return 3;
+  const int64_t bounce_slots = rnd(1, 5);
+  if (mode == 1 && hipMalloc((void**)&bounce, (size_t)(2 * bounce_slots * g.S))) return 3;
+  std::memcpy(pool_b, pool_a.data(), pool_bytes);
+  std::memcpy(scale_b, scale_a.data(), scale_bytes);
+  std::memset(stag_b, 0xA5, stag_bytes);
+
+  ora_config oc;
+  std::memset(&oc, 0, sizeof(oc));
+  oc.L = g.L; oc.H = g.H; oc.D = g.D; oc.B = g.B; oc.elem_bytes = g.e; oc.N = g.N;
+  oc.pool = pool_a.data(); oc.layer_stride = g.ls; oc.kv_stride = g.ks; oc.block_stride = g.bs;
+  oc.scale = scales ? scale_a.data() : nullptr;
+  oc.s_layer_stride = g.sls; oc.s_kv_stride = g.sks; oc.s_block_stride = g.sbs;
+  oc.staging = stag_a.data(); oc.staging_bytes = (int64_t)stag_a.size();
+  ora_state* ora = ora_create(&oc);
+  if (!ora || ora_slot_bytes(ora) != g.S) die("oracle set-up", -1, -1);
+
+  hipStream_t evict, load;
+  hipStreamCreateWithFlags(&evict, hipStreamNonBlocking);
+  hipStreamCreateWithFlags(&load, hipStreamNonBlocking);
+  kv_pool_config kc;
+  std::memset(&kc, 0, sizeof(kc));
+  kc.struct_size = sizeof(kc);
+  kc.num_layers = g.L; kc.num_kv_heads = g.H; kc.head_dim = g.D; kc.block_size = g.B; kc.dtype = g.dtype;
+  kc.num_blocks = g.N; kc.pool_dev = pool_b; kc.layer_stride = g.ls; kc.kv_stride = g.ks; kc.block_stride = g.bs;
+  kc.scale_dev = scales ? scale_b : nullptr;
+  kc.scale_layer_stride = g.sls; kc.scale_kv_stride = g.sks; kc.scale_block_stride = g.sbs;
+  kc.staging_host = stag_b; kc.staging_bytes = (int64_t)stag_bytes;
+  kc.bounce_dev = bounce; kc.bounce_bytes = bounce ? 2 * bounce_slots * g.S : 0;
+  kc.evict_stream = evict; kc.load_stream = load;
+  kc.flags = (mode == 0 ? KV_PATH_ZEROCOPY : mode == 1 ? KV_PATH_DMA : KV_STAGING_DEVICE) | (events ? KV_REQ_EVENTS : 0);
+  kv_pool* kp = nullptr;
+  if (kv_pool_create(&kc, &kp) != KV_OK) die("kv_pool_create", -1, -1);
+  if (kv_pool_tune(kp, KV_TUNE_SCALE_LDS, 1) != KV_OK) die("tune", -1, -1);  // the LDS path has barriers: not emulated
+  if (events) {
+    kv_pool_tune(kp, KV_TUNE_SEGMENT_BYTES, rnd(1, 3) * g.S);
+    if (rnd(0, 1)) kv_pool_tune(kp, KV_TUNE_SEGMENT_MAX_BYTES, rnd(1, 4) * g.S);
+  }
+  if (rnd(0, 2) == 0) kv_pool_tune(kp, KV_TUNE_MAX_WGS_LINK, rnd(1, 5));
+  if (rnd(0, 2) == 0) kv_pool_tune(kp, KV_TUNE_MAX_WGS_DEVICE, rnd(1, 7));
+  if (mode == 1 && rnd(0, 1)) kv_pool_tune(kp, KV_TUNE_DMA_SLICE_BLOCKS, rnd(1, 3));
+
+  // ---- the serving history ----
+  std::vector<int32_t> free_list((size_t)g.N);
+  for (int64_t i = 0; i < g.N; i++) free_list[(size_t)i] = (int32_t)i;
+  std::shuffle(free_list.begin(), free_list.end(), rng);
+  std::vector<std::vector<int32_t>> table((size_t)R + 1);
+  std::vector<int32_t> length((size_t)R + 1, 0);
+  std::vector<int> state((size_t)R + 1, 0);  // 0 idle, 1 running, 2 out
+  std::vector<int> cap((size_t)R + 1, 0);    // extent sizes differ, so that a new extent can lie over parts of several old ones
+  long calls = 0;
+
+  auto both = [&](int rc_lib, int rc_ora, const char* what, int chunk, int step) {
+    if (rc_lib != rc_ora || rc_lib != 0) {
+      std::fprintf(stderr, "%s: library %d oracle %d\n", what, rc_lib, rc_ora);
+      die("return code", chunk, step);
+    }
+    calls++;
+  };
+  auto csr = [&](const std::vector<int>& rs, std::vector<uint64_t>& ids, std::vector<int32_t>& off,
+                 std::vector<int32_t>& blk, std::vector<int32_t>& tok) {
+    ids.clear(); off.assign(1, 0); blk.clear(); tok.clear();
+    for (int r : rs) {
+      ids.push_back((uint64_t)r);
+      blk.insert(blk.end(), table[(size_t)r].begin(), table[(size_t)r].end());
+      off.push_back((int32_t)blk.size());
+      tok.push_back(length[(size_t)r]);
+    }
+  };
+  // a reservation may find no run of free slots long enough: both sides must say so, and nothing has changed then
+  auto reserve = [&](int r, int64_t n, const char* what, int chunk, int step) {
+    const int rc_lib = kv_req_reserve(kp, (uint64_t)r, n), rc_ora = ora_req_reserve(ora, (uint64_t)r, n);
+    if (rc_lib != rc_ora || (rc_lib != 0 && rc_lib != KV_ENOSPC)) {
+      std::fprintf(stderr, "%s: library %d oracle %d\n", what, rc_lib, rc_ora);
+      die("return code", chunk, step);
+    }
+    calls++;
+    return rc_lib == 0;
+  };
+  auto give_up = [&](int r) {
+    free_list.insert(free_list.end(), table[(size_t)r].begin(), table[(size_t)r].end());
+    table[(size_t)r].clear();
+  };
+
+  for (int chunk = 0; chunk < chunks; chunk++) {
+    // who lags in this chunk
+    const int pol = policy == 0 ? mockhip::kRandom : policy == 3 ? mockhip::kLazy : (chunk + policy) % 2 ? mockhip::kStarve0 : mockhip::kStarve1;
+    mockhip::set_policy(pol, pol == mockhip::kStarve0 ? evict : pol == mockhip::kStarve1 ? load : nullptr);
+    std::vector<int32_t> held;
+    if (chunk == 0) {
+      // A fixed opening on the empty arena: request 1 (slots 0..3) is swapped out and resumed without keeping its image,
+      // so its slots are still being read by the load stream; request 2 (slots 4..6) is swapped out AFTER that and
+      // released, so its slots are still being written by the evict stream; request 3 then reserves slots 0..6 and
+      // writes them at once.  That write has to wait for the older call on the other stream, not for the newer one
+      // on its own.
+      std::vector<uint64_t> ids;
+      std::vector<int32_t> off, blk, tok;
+      auto fill = [&](int r, int n) {
+        if (!reserve(r, n, "opening reserve", 0, -1)) die("opening reserve", 0, -1);
+        cap[(size_t)r] = n; state[(size_t)r] = 1; length[(size_t)r] = (int32_t)(n * g.B);
+        for (int j = 0; j < n; j++) { table[(size_t)r].push_back(free_list.back()); free_list.pop_back(); }
+      };
+      auto cold_out = [&](int r) {
+        csr({r}, ids, off, blk, tok);
+        both(kv_swap_out(kp, 1, ids.data(), off.data(), blk.data(), tok.data(), nullptr),
+             ora_swap_out(ora, 1, ids.data(), off.data(), blk.data(), tok.data()), "opening swap_out", 0, -1);
+        give_up(r);
+        state[(size_t)r] = 2;
+      };
+      fill(1, 4);
+      fill(2, 3);
+      cold_out(1);
+      for (int j = 0; j < 4; j++) { table[1].push_back(free_list.back()); free_list.pop_back(); }
+      csr({1}, ids, off, blk, tok);
+      both(kv_swap_in(kp, 1, ids.data(), off.data(), blk.data(), 0, nullptr), ora_swap_in(ora, 1, ids.data(), off.data(), blk.data(), 0),
+           "opening swap_in", 0, -1);
+      held = table[1];  // kept out of circulation until the chunk's comparison: what the swap-in wrote must still be there
+      table[1].clear();
+      length[1] = 0; state[1] = 0;
+      cold_out(2);
+      give_up(2);
+      length[2] = 0; state[2] = 0;
+      both(kv_req_release(kp, 2), ora_req_release(ora, 2), "opening release", 0, -1);
+      fill(3, 7);
+      csr({3}, ids, off, blk, tok);
+      std::vector<int32_t> ma(1), mb(1);
+      both(kv_swap_out_delta(kp, 1, ids.data(), off.data(), blk.data(), tok.data(), 0, 0, mb.data(), nullptr),
+           ora_swap_out_delta(ora, 1, ids.data(), off.data(), blk.data(), tok.data(), 0, 0, ma.data()), "opening delta", 0, -1);
+      if (ma != mb) die("blocks_moved", 0, -1);
+    }
+    for (int step = 0; step < 45; step++) {
+      std::vector<int> running, out, idle;
+      for (int r = 1; r <= R; r++) (state[(size_t)r] == 1 ? running : state[(size_t)r] == 2 ? out : idle).push_back(r);
+      std::vector<uint64_t> ids;
+      std::vector<int32_t> off, blk, tok;
+      int op = (int)rnd(0, 10);
+      if (op == 0 && !idle.empty() && free_list.size() > 8) {  // start
+        const int r = idle[(size_t)rnd(0, (int64_t)idle.size() - 1)];
+        cap[(size_t)r] = (int)rnd(3, cap_max);
+        if (!reserve(r, cap[(size_t)r], "reserve", chunk, step)) continue;
+        state[(size_t)r] = 1; length[(size_t)r] = 0; table[(size_t)r].clear();
+        running.assign(1, r);
+        op = 1;
+      }
+      if ((op == 1 || op == 2) && !running.empty()) {  // grow + budgeted write-through
+        std::shuffle(running.begin(), running.end(), rng);
+        std::vector<int> rs(running.begin(), running.begin() + rnd(1, (int64_t)running.size()));
+        std::vector<int> with;
+        for (int r : rs) {
+          const int32_t want = (int32_t)std::min<int64_t>(length[(size_t)r] + rnd(1, 3 * g.B), (int64_t)cap[(size_t)r] * g.B);
+          while ((int64_t)table[(size_t)r].size() * g.B < want && !free_list.empty()) {
+            table[(size_t)r].push_back(free_list.back());
+            free_list.pop_back();
+          }
+          length[(size_t)r] = (int32_t)std::min<int64_t>(want, (int64_t)table[(size_t)r].size() * g.B);
+          if (!table[(size_t)r].empty()) with.push_back(r);
+        }
+        if (!with.empty()) {
+          csr(with, ids, off, blk, tok);
+          const int64_t budget = rnd(0, 5);
+          std::vector<int32_t> ma(with.size(), -1), mb(with.size(), -1);
+          both(kv_swap_out_delta(kp, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), budget, 0, mb.data(), nullptr),
+               ora_swap_out_delta(ora, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), budget, 0, ma.data()),
+               "delta", chunk, step);
+          if (ma != mb) die("blocks_moved", chunk, step);
+        }
+      } else if ((op == 3 || op == 4 || op == 5) && !running.empty()) {  // preempt: warm, cold, several at once
+        std::shuffle(running.begin(), running.end(), rng);
+        std::vector<int> rs;
+        for (int r : running)
+          if (!table[(size_t)r].empty() && (int)rs.size() < (op == 5 ? 3 : 1)) rs.push_back(r);
+        if (rs.empty()) continue;
+        csr(rs, ids, off, blk, tok);
+        if (op == 4) {
+          both(kv_swap_out(kp, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), nullptr),
+               ora_swap_out(ora, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data()), "swap_out", chunk, step);
+        } else {
+          std::vector<int32_t> ma(rs.size()), mb(rs.size());
+          both(kv_swap_out_delta(kp, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), 0, KV_DELTA_INCLUDE_TAIL, mb.data(), nullptr),
+               ora_swap_out_delta(ora, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), 0, KV_DELTA_INCLUDE_TAIL, ma.data()),
+               "tail delta", chunk, step);
+        }
+        for (int r : rs) { give_up(r); state[(size_t)r] = 2; }
+      } else if ((op == 6 || op == 7) && !out.empty()) {  // resume one or several, with or without the host image
+        std::shuffle(out.begin(), out.end(), rng);
+        std::vector<int> rs;
+        size_t need = 0;
+        for (int r : out) {
+          const size_t nb = (size_t)((length[(size_t)r] + g.B - 1) / g.B);
+          if ((int)rs.size() < (op == 7 ? 3 : 1) && need + nb <= free_list.size()) { rs.push_back(r); need += nb; }
+        }
+        if (rs.empty()) continue;
+        for (int r : rs) {
+          const size_t nb = (size_t)((length[(size_t)r] + g.B - 1) / g.B);
+          for (size_t j = 0; j < nb; j++) { table[(size_t)r].push_back(free_list.back()); free_list.pop_back(); }  // LIFO
+        }
+        csr(rs, ids, off, blk, tok);
+        const bool keep = rnd(0, 9) < 7;
+        both(kv_swap_in(kp, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), keep ? KV_KEEP_STAGING : 0, nullptr),
+             ora_swap_in(ora, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), keep ? KV_KEEP_STAGING : 0), "swap_in", chunk, step);
+        for (int r : rs) {
+          state[(size_t)r] = 1;
+          if (!keep && (rnd(0, 9) < 4 || !reserve(r, cap[(size_t)r], "re-reserve", chunk, step))) {
+            // the request ends here, by choice or for want of room (the swap-in has already dropped its record):
+            // its old slots stay in use by that swap-in until whoever reserves them next
+            give_up(r);
+            length[(size_t)r] = 0; state[(size_t)r] = 0;
+          }
+        }
+      } else if (op == 8 && !running.empty()) {  // compaction move
+        const int r = running[(size_t)rnd(0, (int64_t)running.size() - 1)];
+        const size_t k = std::min<size_t>({table[(size_t)r].size(), free_list.size(), (size_t)rnd(1, 4)});
+        if (!k) continue;
+        std::vector<int32_t> src(table[(size_t)r].begin(), table[(size_t)r].begin() + (long)k), dst;
+        for (size_t j = 0; j < k; j++) { dst.push_back(free_list.back()); free_list.pop_back(); }
+        both(kv_move_blocks(kp, (int64_t)k, src.data(), dst.data(), nullptr), ora_move_blocks(ora, (int64_t)k, src.data(), dst.data()),
+             "move", chunk, step);
+        std::copy(dst.begin(), dst.end(), table[(size_t)r].begin());
+        free_list.insert(free_list.end(), src.begin(), src.end());
+      } else if (op == 9 && running.size() + out.size() > 0) {  // finish
+        std::vector<int> live(running);
+        live.insert(live.end(), out.begin(), out.end());
+        const int r = live[(size_t)rnd(0, (int64_t)live.size() - 1)];
+        give_up(r);
+        length[(size_t)r] = 0; state[(size_t)r] = 0;
+        both(kv_req_release(kp, (uint64_t)r), ora_req_release(ora, (uint64_t)r), "release", chunk, step);
+      } else if (op == 10 && events && !running.empty()) {  // a control thread's poll: must not disturb anything
+        const int rc = kv_req_poll(kp, (uint64_t)running[0]);
+        if (rc != 0 && rc != 1) die("kv_req_poll", chunk, step);
+      }
+    }
+    if (kv_sync(kp) != KV_OK) die("kv_sync", chunk, -1);
+    if (std::memcmp(pool_a.data(), pool_b, pool_bytes)) die("pool bytes", chunk, -1);
+    if (std::memcmp(stag_a.data(), stag_b, stag_bytes)) die("arena bytes", chunk, -1);
+    if (scales && std::memcmp(scale_a.data(), scale_b, scale_bytes)) die("scale bytes", chunk, -1);
+    free_list.insert(free_list.end(), held.begin(), held.end());
+    for (int r = 1; r <= R; r++) {
+      int64_t oa = -1, ob = -1;
+      int32_t ca = -1, sa = -1, wa = -1, xa = -1, cb = -1, sb = -1, wb = -1, xb = -1;
+      const int qa = ora_req_query(ora, (uint64_t)r, &oa, &ca, &sa, &wa, &xa);
+      const int qb = kv_req_query(kp, (uint64_t)r, &ob, &cb, &sb, &wb, &xb);
+      if (qa != qb || (qa == 0 && (oa != ob || ca != cb || sa != sb || wa != wb || xa != xb))) die("request state", chunk, r);
+    }
+  }
+  if (kv_pool_destroy(kp) != KV_OK) die("kv_pool_destroy", -1, -1);
+  ora_destroy(ora);
+  hipStreamDestroy(evict);
+  hipStreamDestroy(load);
+  hipFree(pool_b); hipFree(scale_b);
+  mode == 2 ? hipFree(stag_b) : hipHostFree(stag_b);
+  if (bounce) hipFree(bounce);
+  std::printf("seed %llu: %ld calls, %ld device operations, geometry %d mode %d events %d policy %d: equal to the oracle\n",
+              (unsigned long long)seed, calls, mockhip::executed_ops(), (int)(seed % 4), mode, (int)events, policy);
+  return calls > 40 ? 0 : 2;
+}

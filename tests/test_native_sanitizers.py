@@ -3,8 +3,10 @@
 tests/native/planner_vs_oracle.cpp drives the GPU library's planner (pure C++) and the C oracle
 through the same random operation sequences in one instrumented executable; tests/native/sched_stress.cpp
 does the same for the scheduler and the metrics (invariants instead of an oracle: the oracle is Python);
-tests/native/abi_from_c.c is a C99 client of both headers against the built library, in plan-only mode.
-See their headers.
+tests/native/abi_from_c.c is a C99 client of both headers against the built library, in plan-only mode;
+tests/native/runtime_on_mock_hip.cpp runs the library's host runtime and its kernel source, unchanged, on a
+host-only stand-in for the HIP runtime (tests/native/mockhip) whose executor decides which stream lags, and
+compares random serving histories with the oracle.  See their headers.
 """
 import os
 import subprocess
@@ -57,3 +59,77 @@ def test_c_abi_from_plain_c(tmp_path):
                            "-Wl,-rpath," + pkg, "-Wl,-rpath,/opt/rocm/lib"])
     r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
     assert r.returncode == 0 and "C ABI ok" in r.stdout, r.stdout + r.stderr
+
+
+# ---- the real runtime and the real kernel source on a stand-in HIP runtime, on the CPU ----
+CLANGXX = os.environ.get("HOST_CLANGXX", "/opt/rocm/llvm/bin/clang++")   # the kernel source uses clang builtins
+CSRC = os.path.join(ROOT, "paper_2510_02758_amd", "csrc")
+MOCK = os.path.join(HERE, "native", "mockhip")
+
+
+def _build_on_mock(out_dir, name, csrc_dir, flags):
+    obj = os.path.join(out_dir, "kv_oracle_%s.o" % name)
+    exe = os.path.join(out_dir, name)
+    subprocess.check_call(["gcc", "-std=c99", "-c"] + flags + ["-o", obj, os.path.join(ROOT, "oracle", "kv_oracle.c")])
+    subprocess.check_call([CLANGXX, "-std=c++17", "-Wall"] + flags +
+                          ["-I", MOCK, "-I", os.path.join(ROOT, "include"), "-x", "c++", os.path.join(csrc_dir, "kvswap.hip"),
+                           os.path.join(MOCK, "mockhip.cpp"), os.path.join(HERE, "native", "runtime_on_mock_hip.cpp"),
+                           "-x", "none", obj, "-o", exe])
+    return exe
+
+
+@pytest.fixture(scope="module")
+def mock_driver(tmp_path_factory):
+    if not os.path.exists(CLANGXX):
+        pytest.skip("no host clang++ for the kernel source")
+    return _build_on_mock(str(tmp_path_factory.mktemp("mockhip")), "runtime_on_mock_hip", CSRC, SAN)
+
+
+@pytest.mark.parametrize("first", [0, 48, 96, 144])
+def test_runtime_and_kernels_on_the_stand_in_hip_runtime(mock_driver, first):
+    """Seeds first .. first+47 cover every geometry x padding x path x events combination under one lag policy
+    (0: random progress, 48: the evict stream starved, 96: the load stream starved, 144: nothing runs until a wait)."""
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    for seed in range(first, first + 48):
+        r = subprocess.run([mock_driver, str(seed), "6"], capture_output=True, text=True, timeout=300, env=env)
+        assert r.returncode == 0, "seed %d\n%s%s" % (seed, r.stdout[-2000:], r.stderr[-4000:])
+        assert "equal to the oracle" in r.stdout
+
+
+# One ordering rule of the runtime is taken out at a time (in a copy of the sources); the same histories must then
+# end in a byte difference for some seed: the harness above is able to see what it is meant to see.
+RUNTIME_MUTANTS = [
+    ("reserved_extent_forgets_the_pending_reader",
+     "  if (dep)\n    if (kvswap::Req* r = p->planner.find_mut(req_id)) r->in_seq = dep;\n", "  (void)dep;\n"),
+    ("device_block_hazards_off", "  if (p->blk_reader.empty() || n == 0) return nullptr;", "  return nullptr;"),
+    ("staging_slot_waits_off", "  if (wait_seq) {", "  if (false && wait_seq) {"),
+    ("newest_call_hides_the_other_stream",
+     "s = std::max(s, cross_stream(p, stream, q.seq));", "s = std::max(s, q.seq);"),
+]
+
+
+@pytest.mark.parametrize("name,find,repl", RUNTIME_MUTANTS, ids=[m[0] for m in RUNTIME_MUTANTS])
+def test_a_missing_ordering_rule_is_noticed(tmp_path, name, find, repl):
+    if not os.path.exists(CLANGXX):
+        pytest.skip("no host clang++ for the kernel source")
+    import shutil
+    src = tmp_path / "csrc"
+    shutil.copytree(CSRC, src)
+    hits = 0
+    for f in ("runtime.hip.inc", "kvswap.hip"):
+        text = open(src / f).read()
+        hits += text.count(find)
+        open(src / f, "w").write(text.replace(find, repl))
+    assert hits == 1, "mutation site of %s found %d times" % (name, hits)
+    # planner.hpp names the public header by a relative path: keep that path valid for the copy
+    text = open(src / "planner.hpp").read().replace('"../../include/kvswap.h"', '"kvswap.h"')
+    open(src / "planner.hpp", "w").write(text)
+    exe = _build_on_mock(str(tmp_path), "mutant", str(src), ["-O1", "-g"])
+    failed_at = None
+    for seed in range(48, 400):
+        r = subprocess.run([exe, str(seed), "6"], capture_output=True, text=True, timeout=300)
+        if r.returncode != 0:
+            assert "MISMATCH" in r.stderr, r.stderr[-2000:]
+            failed_at = seed
+            break
+    assert failed_at is not None, "no history notices the planted mistake '%s'" % name
