@@ -265,8 +265,10 @@ int64_t kv_last_plan(kv_pool* p, int32_t* phys, int64_t* slot, int64_t cap);
  * through events; Section 5.3: blocks of a request whose eviction has finished can be reused while
  * the rest of the burst is still moving).
  * kv_req_poll: 1 when no transfer of this request is in flight (or none was ever enqueued), 0 while
- * its last enqueued segment is unfinished.  kv_req_wait blocks until then.  Without KV_REQ_EVENTS
- * both answer for the whole call the request was part of. */
+ * its last enqueued segment is unfinished.  kv_req_wait blocks until then; it does not hold the
+ * handle's lock while it blocks, so another thread may go on enqueuing calls meanwhile (kv_sync does
+ * hold it: it is the call that stops everything).  Without KV_REQ_EVENTS both answer for the whole
+ * call the request was part of. */
 int kv_req_poll(kv_pool* p, uint64_t req_id);
 int kv_req_wait(kv_pool* p, uint64_t req_id);
 /* Completion times of the requests of the most recent swap call, in milliseconds of stream time

@@ -395,10 +395,24 @@ int kv_req_poll(kv_pool* p, uint64_t req_id) {
 
 int kv_req_wait(kv_pool* p, uint64_t req_id) {
   if (!p) return KV_EINVAL;
-  std::lock_guard<std::mutex> g(p->mu);
-  if (p->plan_only) return KV_OK;
-  hipEvent_t ev = req_event(p, req_id);
-  if (ev) HIPCHK(p, hipEventSynchronize(ev));
+  hipEvent_t ev;
+  {
+    std::lock_guard<std::mutex> g(p->mu);
+    if (p->plan_only) return KV_OK;
+    ev = req_event(p, req_id);
+  }
+  if (!ev) return KV_OK;
+  // The wait runs without the handle's lock: a thread that waits for one request does not hold up the thread
+  // that enqueues the next calls.  An event returns to the free list only after its work has finished; should
+  // another call record it again meanwhile, this wait ends later than it had to, never earlier than the
+  // request's own transfer.
+  const hipError_t e = hipEventSynchronize(ev);
+  if (e != hipSuccess) {
+    std::lock_guard<std::mutex> g(p->mu);
+    p->last_hip = (int)e;
+    (void)hipGetLastError();
+    return KV_EHIP;
+  }
   return KV_OK;
 }
 

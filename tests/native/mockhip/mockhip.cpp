@@ -4,6 +4,7 @@
 #include <cstdio>
 #include <deque>
 #include <map>
+#include <mutex>
 #include <random>
 #include <vector>
 
@@ -41,6 +42,10 @@ static double clock_ms = 0;
 static long n_exec = 0, n_deadlock = 0;
 static hipError_t last_error = hipSuccess;
 static Stream null_stream;
+// One lock around the whole stand-in: the program under test may call from several threads.  A blocking wait
+// takes it once per step of the "GPU", so that other threads get in between the steps as they would on hardware.
+static std::recursive_mutex api_mu;
+#define API_LOCK std::lock_guard<std::recursive_mutex> api_guard(api_mu)
 
 static Stream* S(hipStream_t s) { return s ? s : &null_stream; }
 
@@ -83,7 +88,9 @@ static bool step() {
 
 template <class Pred>
 static void drive(Pred done) {
-  while (!done()) {
+  for (;;) {
+    API_LOCK;
+    if (done()) return;
     if (!step()) {
       n_deadlock++;
       std::fprintf(stderr, "mockhip: DEADLOCK: a wait can never be satisfied\n");
@@ -102,26 +109,36 @@ static void progress() {
 }
 
 void reset(uint64_t seed) {
+  API_LOCK;
   rng.seed(seed);
   policy = kRandom;
   starved = nullptr;
 }
 void set_policy(int p, Stream* s) {
+  API_LOCK;
   policy = p;
   starved = s;
 }
 void enqueue(Stream* s, std::function<void()> fn) {
+  API_LOCK;
   S(s)->q.push_back({0, std::move(fn), nullptr, 0});
   progress();
 }
-long executed_ops() { return n_exec; }
-long deadlocks() { return n_deadlock; }
+long executed_ops() {
+  API_LOCK;
+  return n_exec;
+}
+long deadlocks() {
+  API_LOCK;
+  return n_deadlock;
+}
 
 }  // namespace mockhip
 
 using namespace mockhip;
 
 hipError_t hipGetLastError() {
+  API_LOCK;
   hipError_t e = last_error;
   last_error = hipSuccess;
   return e;
@@ -130,6 +147,7 @@ hipError_t hipGetDevice(int* dev) { *dev = 0; return hipSuccess; }
 hipError_t hipGetDeviceProperties(hipDeviceProp_t* prop, int) { prop->multiProcessorCount = 256; return hipSuccess; }
 
 static hipError_t alloc_any(void** p, size_t n, int type) {
+  API_LOCK;
   char* m = (char*)std::malloc(n ? n : 1);
   if (!m) return last_error = hipErrorOutOfMemory;
   std::memset(m, 0xCD, n);
@@ -138,6 +156,7 @@ static hipError_t alloc_any(void** p, size_t n, int type) {
   return hipSuccess;
 }
 static hipError_t free_any(void* p) {
+  API_LOCK;
   auto it = allocs.find((char*)p);
   if (it == allocs.end()) return last_error = hipErrorInvalidValue;
   allocs.erase(it);
@@ -157,6 +176,7 @@ static const std::pair<char* const, Alloc>* find_alloc(const void* p) {
   return &*it;
 }
 hipError_t hipMemGetAddressRange(hipDeviceptr_t* base, size_t* size, hipDeviceptr_t p) {
+  API_LOCK;
   auto* a = find_alloc(p);
   if (!a) return last_error = hipErrorInvalidValue;
   *base = a->first;
@@ -164,6 +184,7 @@ hipError_t hipMemGetAddressRange(hipDeviceptr_t* base, size_t* size, hipDevicept
   return hipSuccess;
 }
 hipError_t hipPointerGetAttributes(hipPointerAttribute_t* at, const void* p) {
+  API_LOCK;
   auto* a = find_alloc(p);
   if (!a) return last_error = hipErrorInvalidValue;
   at->type = a->second.type;
@@ -173,11 +194,13 @@ hipError_t hipPointerGetAttributes(hipPointerAttribute_t* at, const void* p) {
 }
 
 hipError_t hipStreamCreateWithFlags(hipStream_t* s, unsigned) {
+  API_LOCK;
   *s = new Stream;
   streams.push_back(*s);
   return hipSuccess;
 }
 hipError_t hipStreamDestroy(hipStream_t s) {
+  API_LOCK;
   drive([&] { return s->q.empty(); });
   for (size_t i = 0; i < streams.size(); i++)
     if (streams[i] == s) streams.erase(streams.begin() + (long)i);
@@ -191,6 +214,7 @@ hipError_t hipStreamSynchronize(hipStream_t s) {
   return hipSuccess;
 }
 hipError_t hipStreamWaitEvent(hipStream_t s, hipEvent_t e, unsigned) {
+  API_LOCK;
   if (e->recorded == 0) return hipSuccess;  // never recorded: nothing to wait for
   S(s)->q.push_back({2, nullptr, e, e->recorded});
   progress();
@@ -198,6 +222,7 @@ hipError_t hipStreamWaitEvent(hipStream_t s, hipEvent_t e, unsigned) {
 }
 hipError_t hipEventCreate(hipEvent_t* e) { *e = new Event; return hipSuccess; }
 hipError_t hipEventDestroy(hipEvent_t e) {
+  API_LOCK;
   // operations that still name the event are a use after free in the program under test
   for (Stream* s : streams)
     for (Op& o : s->q)
@@ -209,18 +234,27 @@ hipError_t hipEventDestroy(hipEvent_t e) {
   return hipSuccess;
 }
 hipError_t hipEventRecord(hipEvent_t e, hipStream_t s) {
+  API_LOCK;
   e->recorded++;
   S(s)->q.push_back({1, nullptr, e, e->recorded});
   progress();
   return hipSuccess;
 }
-hipError_t hipEventQuery(hipEvent_t e) { return e->completed >= e->recorded ? hipSuccess : hipErrorNotReady; }
+hipError_t hipEventQuery(hipEvent_t e) {
+  API_LOCK;
+  return e->completed >= e->recorded ? hipSuccess : hipErrorNotReady;
+}
 hipError_t hipEventSynchronize(hipEvent_t e) {
-  const uint64_t gen = e->recorded;
+  uint64_t gen;
+  {
+    API_LOCK;
+    gen = e->recorded;
+  }
   drive([&] { return e->completed >= gen; });
   return hipSuccess;
 }
 hipError_t hipEventElapsedTime(float* ms, hipEvent_t a, hipEvent_t b) {
+  API_LOCK;
   if (a->completed < a->recorded || b->completed < b->recorded || !a->recorded || !b->recorded)
     return last_error = hipErrorNotReady;
   *ms = (float)(b->t - a->t);

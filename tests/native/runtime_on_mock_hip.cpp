@@ -12,11 +12,17 @@
 // wait that can never be satisfied as a reported deadlock, an out-of-bounds access of a kernel or of the host
 // code as a sanitizer error.
 //
-// usage: runtime_on_mock_hip <seed> <chunks>
+// With a third argument a second thread polls the handle (request state, statistics, queue length) all through
+// every chunk: built with ThreadSanitizer this checks that every entry point takes the handle's lock, and the
+// comparison with the oracle that such readers change nothing.
+//
+// usage: runtime_on_mock_hip <seed> <chunks> [poller]
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstdio>
+#include <thread>
 #include <map>
 #include <random>
 #include <vector>
@@ -43,6 +49,7 @@ struct Geo {
 int main(int argc, char** argv) {
   const uint64_t seed = argc > 1 ? std::strtoull(argv[1], nullptr, 10) : 1;
   const int chunks = argc > 2 ? std::atoi(argv[2]) : 8;
+  const bool poller = argc > 3;
   std::mt19937_64 rng(seed * 7919 + 13);
   auto rnd = [&](int64_t lo, int64_t hi) { return lo + (int64_t)(rng() % (uint64_t)(hi - lo + 1)); };
   mockhip::reset(seed);
@@ -211,6 +218,33 @@ int main(int argc, char** argv) {
            ora_swap_out_delta(ora, 1, ids.data(), off.data(), blk.data(), tok.data(), 0, 0, ma.data()), "opening delta", 0, -1);
       if (ma != mb) die("blocks_moved", 0, -1);
     }
+    std::atomic<bool> stop{false};
+    std::atomic<long> polls{0};
+    std::thread side;
+    if (poller)
+      side = std::thread([&] {
+        uint64_t x = seed * 977 + (uint64_t)chunk;
+        while (!stop.load()) {
+          x = x * 6364136223846793005ull + 1442695040888963407ull;
+          const uint64_t r = 1 + (x >> 33) % (uint64_t)R;
+          int64_t o, blocks;
+          int32_t a, b, c, d, reqs;
+          kv_io_stats io;
+          kv_stats st;
+          std::memset(&io, 0, sizeof(io)); io.struct_size = sizeof(io);
+          std::memset(&st, 0, sizeof(st)); st.struct_size = sizeof(st);
+          switch ((x >> 20) % 6) {
+            case 0: (void)kv_req_poll(kp, r); break;
+            case 1: (void)kv_req_query(kp, r, &o, &a, &b, &c, &d); break;
+            case 2: (void)kv_io_stats_get(kp, &io); break;
+            case 3: (void)kv_last_stats(kp, &st); break;
+            case 4: if (kv_req_wait(kp, r) != KV_OK) die("kv_req_wait", chunk, -2); break;
+            default: (void)kv_wq_pending(kp, &blocks, &reqs); break;
+          }
+          polls++;
+          std::this_thread::yield();
+        }
+      });
     for (int step = 0; step < 45; step++) {
       std::vector<int> running, out, idle;
       for (int r = 1; r <= R; r++) (state[(size_t)r] == 1 ? running : state[(size_t)r] == 2 ? out : idle).push_back(r);
@@ -311,6 +345,11 @@ int main(int argc, char** argv) {
         const int rc = kv_req_poll(kp, (uint64_t)running[0]);
         if (rc != 0 && rc != 1) die("kv_req_poll", chunk, step);
       }
+    }
+    if (poller) {
+      while (polls.load() < 50) std::this_thread::yield();  // the reader has really run beside the history
+      stop = true;
+      side.join();
     }
     if (kv_sync(kp) != KV_OK) die("kv_sync", chunk, -1);
     if (std::memcmp(pool_a.data(), pool_b, pool_bytes)) die("pool bytes", chunk, -1);

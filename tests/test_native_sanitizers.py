@@ -71,7 +71,7 @@ def _build_on_mock(out_dir, name, csrc_dir, flags):
     obj = os.path.join(out_dir, "kv_oracle_%s.o" % name)
     exe = os.path.join(out_dir, name)
     subprocess.check_call(["gcc", "-std=c99", "-c"] + flags + ["-o", obj, os.path.join(ROOT, "oracle", "kv_oracle.c")])
-    subprocess.check_call([CLANGXX, "-std=c++17", "-Wall"] + flags +
+    subprocess.check_call([CLANGXX, "-std=c++17", "-Wall", "-pthread"] + flags +
                           ["-I", MOCK, "-I", os.path.join(ROOT, "include"), "-x", "c++", os.path.join(csrc_dir, "kvswap.hip"),
                            os.path.join(MOCK, "mockhip.cpp"), os.path.join(HERE, "native", "runtime_on_mock_hip.cpp"),
                            "-x", "none", obj, "-o", exe])
@@ -133,3 +133,41 @@ def test_a_missing_ordering_rule_is_noticed(tmp_path, name, find, repl):
             failed_at = seed
             break
     assert failed_at is not None, "no history notices the planted mistake '%s'" % name
+
+
+# ---- the same harness under ThreadSanitizer, with a second thread that polls the handle ----
+TSAN = ["-fsanitize=thread", "-g", "-O1"]
+
+
+def test_entry_points_from_two_threads_under_tsan(tmp_path):
+    """A reader thread (kv_req_poll / kv_req_wait / kv_req_query / kv_io_stats_get / kv_last_stats / kv_wq_pending)
+    runs beside the serving history: no data race, and the history still ends equal to the oracle."""
+    if not os.path.exists(CLANGXX):
+        pytest.skip("no host clang++ for the kernel source")
+    exe = _build_on_mock(str(tmp_path), "runtime_tsan", CSRC, TSAN)
+    for seed in range(0, 192, 8):
+        r = subprocess.run([exe, str(seed + seed // 8 % 4), "4", "poller"], capture_output=True, text=True, timeout=300)
+        assert r.returncode == 0, "seed %d\n%s%s" % (seed, r.stdout[-2000:], r.stderr[-4000:])
+        assert "equal to the oracle" in r.stdout
+
+
+def test_tsan_notices_an_entry_point_without_the_lock(tmp_path):
+    if not os.path.exists(CLANGXX):
+        pytest.skip("no host clang++ for the kernel source")
+    import shutil
+    src = tmp_path / "csrc"
+    shutil.copytree(CSRC, src)
+    text = open(src / "kvswap.hip").read()
+    at = text.index("int kv_req_query(")
+    lock = "std::lock_guard<std::mutex> g(p->mu);"
+    at = text.index(lock, at)
+    open(src / "kvswap.hip", "w").write(text[:at] + text[at + len(lock):])
+    text = open(src / "planner.hpp").read().replace('"../../include/kvswap.h"', '"kvswap.h"')
+    open(src / "planner.hpp", "w").write(text)
+    exe = _build_on_mock(str(tmp_path), "mutant_tsan", str(src), TSAN)
+    for seed in range(0, 64):
+        r = subprocess.run([exe, str(seed), "4", "poller"], capture_output=True, text=True, timeout=300)
+        if r.returncode != 0:
+            assert "ThreadSanitizer: data race" in r.stderr, r.stderr[-3000:]
+            return
+    raise AssertionError("the unlocked kv_req_query was not reported")
