@@ -49,9 +49,11 @@
  *   - Every entry point returns 0 (KV_OK) or a negative KV_E* code.  No C++
  *     exception crosses the boundary.
  *   - All-or-nothing: a call checks every request and every block id before it
- *     changes any state or enqueues any work.  KV_EHIP is the exception: a HIP runtime failure
- *     in the middle of enqueuing leaves bookkeeping and streams out of step; the only call that is
- *     still meaningful on such a handle is kv_pool_destroy.
+ *     changes any state or enqueues any work.  KV_EHIP and KV_ENOMEM are the exception: a HIP
+ *     runtime failure or an allocation failure in the middle of a call leaves bookkeeping and
+ *     streams out of step.  The handle remembers it: every later call that would change state or
+ *     enqueue work returns KV_EHIP without doing anything; queries (kv_req_query, kv_last_stats,
+ *     kv_io_stats_get, kv_last_hip_error) still answer, and kv_pool_destroy releases everything.
  *   - Calls are asynchronous.  Swap-out / delta / move work is enqueued on the evict stream,
  *     swap-in work on the load stream, in issue order.  The library inserts every cross-stream
  *     wait the two streams need between themselves: for staging slots (a swap-in reads slots an
@@ -98,7 +100,8 @@ enum {
   KV_EEXIST = -5, /* request already swapped out (kv_swap_out twice, or delta after swap-out) */
   KV_ENOSPC = -6, /* staging arena cannot hold the extent (or cannot grow it in place) */
   KV_EHIP = -7,   /* a HIP runtime call failed; kv_last_hip_error() returns its code */
-  KV_ESTATE = -8  /* token count below the watermark (a request never shrinks) */
+  KV_ESTATE = -8, /* token count below the watermark (a request never shrinks) */
+  KV_ENOMEM = -9  /* host memory for the library's own bookkeeping could not be allocated */
 };
 
 /* kv_pool_config.flags */

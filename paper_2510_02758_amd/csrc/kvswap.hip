@@ -11,6 +11,15 @@
 // on-device gather/scatter.
 #include "runtime.hip.inc"
 
+// Entry of a call that changes state or enqueues work: takes the handle's lock and refuses a handle on which an
+// earlier call failed half-way (KV_EHIP, KV_ENOMEM): its bookkeeping no longer describes what the streams hold.
+#define KV_ENTER(p)                       \
+  std::lock_guard<std::mutex> g((p)->mu); \
+  if ((p)->broken) return KV_EHIP
+// Every entry point is a function-try-block that ends in this handler: no exception leaves through the C boundary.
+#define KV_CATCH(p) \
+  catch (...) { return on_exception(p); }
+
 extern "C" {
 
 int kv_pool_create(const kv_pool_config* cfg, kv_pool** out) {
@@ -52,107 +61,112 @@ int kv_pool_create(const kv_pool_config* cfg, kv_pool** out) {
 #undef REJECT
 
   kv_pool* p = new (std::nothrow) kv_pool;
-  if (!p) return KV_EINVAL;
-  p->cfg = *cfg;
-  p->plan_only = plan_only;
-  p->dev_staging = (cfg->flags & KV_STAGING_DEVICE) != 0;
-  p->req_events = (cfg->flags & KV_REQ_EVENTS) != 0;
-  p->chunk = chunk;
-  p->block_bytes = 2 * (int64_t)cfg->num_layers * chunk;
-  p->scale_chunk = scale_chunk;
-  p->block_scale_bytes = 2 * (int64_t)cfg->num_layers * scale_chunk;
-  p->S = p->block_bytes + p->block_scale_bytes;
-  p->slots = cfg->staging_bytes / p->S;
-  if (p->slots > INT32_MAX) p->slots = INT32_MAX;
-  if (!scales) p->cfg.scale_dev = nullptr;
-  p->planner.init(cfg->num_blocks, cfg->block_size, p->slots);
-  if ((cfg->flags & KV_PATH_DMA) && (!cfg->bounce_dev || (cfg->bounce_bytes / 2) / p->S < 1)) {
-    KVDBG("rejected: the DMA path needs a bounce buffer of at least two slots");
-    delete p;
-    return KV_EINVAL;
-  }
-  if (plan_only) {
-    *out = p;
-    return KV_OK;
-  }
-
-  // The kernels trust these extents: refuse a pool whose strides leave its allocation.
-  const int64_t pool_need = (cfg->num_layers - 1) * cfg->layer_stride + cfg->kv_stride +
-                            (cfg->num_blocks - 1) * cfg->block_stride + chunk;
-  bool ok = range_ok(cfg->pool_dev, pool_need);
-  if (!ok) KVDBG("pool strides reach %lld bytes, past the end of the allocation", (long long)pool_need);
-  if (ok && scales) {
-    ok = range_ok(cfg->scale_dev, (cfg->num_layers - 1) * cfg->scale_layer_stride + cfg->scale_kv_stride +
-                                      (cfg->num_blocks - 1) * cfg->scale_block_stride + scale_chunk);
-    if (!ok) KVDBG("scale strides reach past the end of the allocation");
-  }
-  if (ok && !range_ok(cfg->staging_host, cfg->staging_bytes)) {
-    ok = false;
-    KVDBG("staging_bytes reaches past the end of the arena allocation");
-  }
-  if (ok && cfg->bounce_dev && !range_ok(cfg->bounce_dev, cfg->bounce_bytes)) {
-    ok = false;
-    KVDBG("bounce_bytes reaches past the end of the bounce allocation");
-  }
-  if (ok) {
-    hipPointerAttribute_t at;
-    hipError_t er = hipPointerGetAttributes(&at, cfg->pool_dev);
-    if (er != hipSuccess || at.type != hipMemoryTypeDevice) {
-      ok = false;
-      KVDBG("pool_dev is not device memory (hip error %d, memory type %d)", (int)er, er == hipSuccess ? (int)at.type : -1);
+  if (!p) return KV_ENOMEM;
+  try {
+    p->cfg = *cfg;
+    p->plan_only = plan_only;
+    p->dev_staging = (cfg->flags & KV_STAGING_DEVICE) != 0;
+    p->req_events = (cfg->flags & KV_REQ_EVENTS) != 0;
+    p->chunk = chunk;
+    p->block_bytes = 2 * (int64_t)cfg->num_layers * chunk;
+    p->scale_chunk = scale_chunk;
+    p->block_scale_bytes = 2 * (int64_t)cfg->num_layers * scale_chunk;
+    p->S = p->block_bytes + p->block_scale_bytes;
+    p->slots = cfg->staging_bytes / p->S;
+    if (p->slots > INT32_MAX) p->slots = INT32_MAX;
+    if (!scales) p->cfg.scale_dev = nullptr;
+    p->planner.init(cfg->num_blocks, cfg->block_size, p->slots);
+    if ((cfg->flags & KV_PATH_DMA) && (!cfg->bounce_dev || (cfg->bounce_bytes / 2) / p->S < 1)) {
+      KVDBG("rejected: the DMA path needs a bounce buffer of at least two slots");
+      delete p;
+      return KV_EINVAL;
     }
-    (void)hipGetLastError();
+    if (plan_only) {
+      *out = p;
+      return KV_OK;
+    }
+
+    // The kernels trust these extents: refuse a pool whose strides leave its allocation.
+    const int64_t pool_need = (cfg->num_layers - 1) * cfg->layer_stride + cfg->kv_stride +
+                              (cfg->num_blocks - 1) * cfg->block_stride + chunk;
+    bool ok = range_ok(cfg->pool_dev, pool_need);
+    if (!ok) KVDBG("pool strides reach %lld bytes, past the end of the allocation", (long long)pool_need);
+    if (ok && scales) {
+      ok = range_ok(cfg->scale_dev, (cfg->num_layers - 1) * cfg->scale_layer_stride + cfg->scale_kv_stride +
+                                        (cfg->num_blocks - 1) * cfg->scale_block_stride + scale_chunk);
+      if (!ok) KVDBG("scale strides reach past the end of the allocation");
+    }
+    if (ok && !range_ok(cfg->staging_host, cfg->staging_bytes)) {
+      ok = false;
+      KVDBG("staging_bytes reaches past the end of the arena allocation");
+    }
+    if (ok && cfg->bounce_dev && !range_ok(cfg->bounce_dev, cfg->bounce_bytes)) {
+      ok = false;
+      KVDBG("bounce_bytes reaches past the end of the bounce allocation");
+    }
     if (ok) {
-      er = hipPointerGetAttributes(&at, cfg->staging_host);
-      if (er != hipSuccess) {
-        ok = false;  // pageable or unknown memory cannot be a staging arena
-        KVDBG("staging_host is unknown to HIP (error %d): it must be pinned memory", (int)er);
-      } else if (p->dev_staging ? at.type != hipMemoryTypeDevice : at.type != hipMemoryTypeHost) {
+      hipPointerAttribute_t at;
+      hipError_t er = hipPointerGetAttributes(&at, cfg->pool_dev);
+      if (er != hipSuccess || at.type != hipMemoryTypeDevice) {
         ok = false;
-        KVDBG("staging_host has memory type %d, expected %s memory", (int)at.type, p->dev_staging ? "device" : "pinned host");
-      } else {
-        p->arena_dev = (char*)(at.devicePointer ? at.devicePointer : cfg->staging_host);
+        KVDBG("pool_dev is not device memory (hip error %d, memory type %d)", (int)er, er == hipSuccess ? (int)at.type : -1);
       }
       (void)hipGetLastError();
-    }
-  }
-  if (!ok) {
-    delete p;
-    return KV_EINVAL;
-  }
-  int dev = 0;
-  hipDeviceProp_t prop;
-  if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-    p->cu_count = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-  void* given[2] = {cfg->evict_stream, cfg->load_stream};
-  int rc = KV_OK;
-  for (int s = 0; s < 2 && !rc; s++) {
-    if (given[s]) {
-      p->stream[s] = (hipStream_t)given[s];
-    } else {
-      hipError_t er = hipStreamCreateWithFlags(&p->stream[s], hipStreamNonBlocking);
-      if (er != hipSuccess) {
-        p->last_hip = (int)er;
-        rc = KV_EHIP;
-      } else {
-        p->own_stream[s] = true;
+      if (ok) {
+        er = hipPointerGetAttributes(&at, cfg->staging_host);
+        if (er != hipSuccess) {
+          ok = false;  // pageable or unknown memory cannot be a staging arena
+          KVDBG("staging_host is unknown to HIP (error %d): it must be pinned memory", (int)er);
+        } else if (p->dev_staging ? at.type != hipMemoryTypeDevice : at.type != hipMemoryTypeHost) {
+          ok = false;
+          KVDBG("staging_host has memory type %d, expected %s memory", (int)at.type, p->dev_staging ? "device" : "pinned host");
+        } else {
+          p->arena_dev = (char*)(at.devicePointer ? at.devicePointer : cfg->staging_host);
+        }
+        (void)hipGetLastError();
       }
     }
+    if (!ok) {
+      delete p;
+      return KV_EINVAL;
+    }
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+      p->cu_count = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    void* given[2] = {cfg->evict_stream, cfg->load_stream};
+    int rc = KV_OK;
+    for (int s = 0; s < 2 && !rc; s++) {
+      if (given[s]) {
+        p->stream[s] = (hipStream_t)given[s];
+      } else {
+        hipError_t er = hipStreamCreateWithFlags(&p->stream[s], hipStreamNonBlocking);
+        if (er != hipSuccess) {
+          p->last_hip = (int)er;
+          rc = KV_EHIP;
+        } else {
+          p->own_stream[s] = true;
+        }
+      }
+    }
+    if (!rc) rc = grow_ring(p, (size_t)1 << 16);
+    if (!rc) {
+      p->blk_reader.assign((size_t)cfg->num_blocks, BlkMark{0, -1});
+      p->blk_writer.assign((size_t)cfg->num_blocks, BlkMark{0, -1});
+    }
+    if (rc) {
+      kv_pool_destroy(p);
+      return rc;
+    }
+    *out = p;
+    return KV_OK;
+  } catch (...) {  // the containers of the handle could not be allocated
+    (void)kv_pool_destroy(p);
+    return KV_ENOMEM;
   }
-  if (!rc) rc = grow_ring(p, (size_t)1 << 16);
-  if (!rc) {
-    p->blk_reader.assign((size_t)cfg->num_blocks, BlkMark{0, -1});
-    p->blk_writer.assign((size_t)cfg->num_blocks, BlkMark{0, -1});
-  }
-  if (rc) {
-    kv_pool_destroy(p);
-    return rc;
-  }
-  *out = p;
-  return KV_OK;
 }
 
-int kv_pool_destroy(kv_pool* p) {
+int kv_pool_destroy(kv_pool* p) try {
   if (!p) return KV_EINVAL;
   int rc = KV_OK;
   if (!p->plan_only) {
@@ -167,6 +181,9 @@ int kv_pool_destroy(kv_pool* p) {
   }
   delete p;
   return rc;
+}
+catch (...) {
+  return KV_ENOMEM;  // nothing in here allocates beyond the event free list; the handle is not touched again
 }
 
 static int swap_out_common(kv_pool* p, int op, Plan& plan, double t0, void* wait_event) {
@@ -200,9 +217,9 @@ static int swap_out_common(kv_pool* p, int op, Plan& plan, double t0, void* wait
 }
 
 int kv_swap_out(kv_pool* p, int32_t n, const uint64_t* req_ids, const int32_t* offsets, const int32_t* block_ids,
-                const int32_t* num_tokens, void* wait_event) {
+                const int32_t* num_tokens, void* wait_event) try {
   if (!p) return KV_EINVAL;
-  std::lock_guard<std::mutex> g(p->mu);
+  KV_ENTER(p);
   const double t0 = now_us();
   Plan plan;
   int rc = p->planner.plan_swap_out(n, req_ids, offsets, block_ids, num_tokens, &plan);
@@ -210,12 +227,13 @@ int kv_swap_out(kv_pool* p, int32_t n, const uint64_t* req_ids, const int32_t* o
   for (int32_t i = 0; i < n; i++) p->wq.erase(req_ids[i]);  // a swapped-out request has nothing left to write through
   return swap_out_common(p, 1, plan, t0, wait_event);
 }
+KV_CATCH(p)
 
 int kv_swap_out_delta(kv_pool* p, int32_t n, const uint64_t* req_ids, const int32_t* offsets,
                       const int32_t* block_ids, const int32_t* num_tokens, int64_t block_budget, uint32_t flags,
-                      int32_t* blocks_moved, void* wait_event) {
+                      int32_t* blocks_moved, void* wait_event) try {
   if (!p) return KV_EINVAL;
-  std::lock_guard<std::mutex> g(p->mu);
+  KV_ENTER(p);
   const double t0 = now_us();
   Plan plan;
   int rc = p->planner.plan_delta(n, req_ids, offsets, block_ids, num_tokens, block_budget, flags, blocks_moved,
@@ -223,11 +241,12 @@ int kv_swap_out_delta(kv_pool* p, int32_t n, const uint64_t* req_ids, const int3
   if (rc) return rc;
   return swap_out_common(p, 2, plan, t0, wait_event);
 }
+KV_CATCH(p)
 
 int kv_swap_in(kv_pool* p, int32_t n, const uint64_t* req_ids, const int32_t* offsets,
-               const int32_t* new_block_ids, uint32_t flags, void* wait_event) {
+               const int32_t* new_block_ids, uint32_t flags, void* wait_event) try {
   if (!p) return KV_EINVAL;
-  std::lock_guard<std::mutex> g(p->mu);
+  KV_ENTER(p);
   const double t0 = now_us();
   Plan plan;
   int rc = p->planner.plan_swap_in(n, req_ids, offsets, new_block_ids, flags, &plan);
@@ -261,10 +280,11 @@ int kv_swap_in(kv_pool* p, int32_t n, const uint64_t* req_ids, const int32_t* of
   c->st.enqueue_us = now_us() - t1;
   return KV_OK;
 }
+KV_CATCH(p)
 
-int kv_move_blocks(kv_pool* p, int64_t n, const int32_t* src_ids, const int32_t* dst_ids, void* wait_event) {
+int kv_move_blocks(kv_pool* p, int64_t n, const int32_t* src_ids, const int32_t* dst_ids, void* wait_event) try {
   if (!p) return KV_EINVAL;
-  std::lock_guard<std::mutex> g(p->mu);
+  KV_ENTER(p);
   const double t0 = now_us();
   Plan plan;
   int rc = p->planner.plan_move(n, src_ids, dst_ids, &plan);
@@ -290,19 +310,21 @@ int kv_move_blocks(kv_pool* p, int64_t n, const int32_t* src_ids, const int32_t*
   c->st.enqueue_us = now_us() - t1;
   return KV_OK;
 }
+KV_CATCH(p)
 
-int kv_sync(kv_pool* p) {
+int kv_sync(kv_pool* p) try {
   if (!p) return KV_EINVAL;
-  std::lock_guard<std::mutex> g(p->mu);
+  KV_ENTER(p);
   if (p->plan_only) return KV_OK;
   for (int s = 0; s < 2; s++) HIPCHK(p, hipStreamSynchronize(p->stream[s]));
   retire(p);
   return KV_OK;
 }
+KV_CATCH(p)
 
-int kv_req_reserve(kv_pool* p, uint64_t req_id, int32_t max_blocks) {
+int kv_req_reserve(kv_pool* p, uint64_t req_id, int32_t max_blocks) try {
   if (!p) return KV_EINVAL;
-  std::lock_guard<std::mutex> g(p->mu);
+  KV_ENTER(p);
   int rc = p->planner.reserve(req_id, max_blocks);
   if (rc || p->plan_only) return rc;
   // The extent may lie on slots that an unfinished swap-in of their previous owner still reads: whatever
@@ -313,10 +335,11 @@ int kv_req_reserve(kv_pool* p, uint64_t req_id, int32_t max_blocks) {
     if (kvswap::Req* r = p->planner.find_mut(req_id)) r->in_seq = dep;
   return KV_OK;
 }
+KV_CATCH(p)
 
-int kv_req_release(kv_pool* p, uint64_t req_id) {
+int kv_req_release(kv_pool* p, uint64_t req_id) try {
   if (!p) return KV_EINVAL;
-  std::lock_guard<std::mutex> g(p->mu);
+  KV_ENTER(p);
   kvswap::Req was;
   int rc = p->planner.release(req_id, &was);
   if (!rc) p->wq.erase(req_id);
@@ -326,9 +349,10 @@ int kv_req_release(kv_pool* p, uint64_t req_id) {
     if (s && was.cap && !seq_done(p, s)) p->pending.push_back({was.base, was.base + was.cap, s});
   return KV_OK;
 }
+KV_CATCH(p)
 
 int kv_req_query(kv_pool* p, uint64_t req_id, int64_t* staging_offset, int32_t* cap_blocks, int32_t* blocks_staged,
-                 int32_t* watermark, int32_t* swapped) {
+                 int32_t* watermark, int32_t* swapped) try {
   if (!p) return KV_EINVAL;
   std::lock_guard<std::mutex> g(p->mu);
   const kvswap::Req* r = p->planner.find(req_id);
@@ -340,8 +364,9 @@ int kv_req_query(kv_pool* p, uint64_t req_id, int64_t* staging_offset, int32_t* 
   if (swapped) *swapped = r->swapped ? 1 : 0;
   return KV_OK;
 }
+KV_CATCH(p)
 
-int kv_last_stats(kv_pool* p, kv_stats* out) {
+int kv_last_stats(kv_pool* p, kv_stats* out) try {
   if (!p || !out) return KV_EINVAL;
   std::lock_guard<std::mutex> g(p->mu);
   if (p->plan_only || p->last_instant || p->calls.empty()) {
@@ -366,6 +391,7 @@ int kv_last_stats(kv_pool* p, kv_stats* out) {
   *out = c.st;
   return KV_OK;
 }
+KV_CATCH(p)
 
 int64_t kv_slot_bytes(const kv_pool* p) { return p ? p->S : 0; }
 
@@ -379,7 +405,7 @@ static hipEvent_t req_event(kv_pool* p, uint64_t req_id) {
   return sg >= 0 && sg < (int)c->seg_ev.size() ? c->seg_ev[(size_t)sg] : c->end;
 }
 
-int kv_req_poll(kv_pool* p, uint64_t req_id) {
+int kv_req_poll(kv_pool* p, uint64_t req_id) try {
   if (!p) return KV_EINVAL;
   std::lock_guard<std::mutex> g(p->mu);
   if (p->plan_only) return 1;
@@ -390,10 +416,12 @@ int kv_req_poll(kv_pool* p, uint64_t req_id) {
   (void)hipGetLastError();
   if (e == hipErrorNotReady) return 0;
   p->last_hip = (int)e;
+  p->broken = true;
   return KV_EHIP;
 }
+KV_CATCH(p)
 
-int kv_req_wait(kv_pool* p, uint64_t req_id) {
+int kv_req_wait(kv_pool* p, uint64_t req_id) try {
   if (!p) return KV_EINVAL;
   hipEvent_t ev;
   {
@@ -410,13 +438,15 @@ int kv_req_wait(kv_pool* p, uint64_t req_id) {
   if (e != hipSuccess) {
     std::lock_guard<std::mutex> g(p->mu);
     p->last_hip = (int)e;
+    p->broken = true;
     (void)hipGetLastError();
     return KV_EHIP;
   }
   return KV_OK;
 }
+KV_CATCH(p)
 
-int64_t kv_last_timeline(kv_pool* p, uint64_t* req_ids, float* done_ms, int64_t cap) {
+int64_t kv_last_timeline(kv_pool* p, uint64_t* req_ids, float* done_ms, int64_t cap) try {
   if (!p) return KV_EINVAL;
   std::lock_guard<std::mutex> g(p->mu);
   if (p->plan_only || p->last_instant || p->calls.empty()) return 0;
@@ -434,6 +464,7 @@ int64_t kv_last_timeline(kv_pool* p, uint64_t* req_ids, float* done_ms, int64_t 
   }
   return n;
 }
+KV_CATCH(p)
 
 static void io_snapshot(kv_pool* p, kv_io_stats* o) {
   std::memset(o, 0, sizeof(*o));
@@ -459,28 +490,30 @@ static void io_snapshot(kv_pool* p, kv_io_stats* o) {
   }
 }
 
-int kv_io_stats_get(kv_pool* p, kv_io_stats* out) {
+int kv_io_stats_get(kv_pool* p, kv_io_stats* out) try {
   if (!p || !out) return KV_EINVAL;
   std::lock_guard<std::mutex> g(p->mu);
   io_snapshot(p, out);
   return KV_OK;
 }
+KV_CATCH(p)
 
 static int64_t budget_blocks_locked(kv_pool* p, int32_t dir, double interval_us);
 
-int64_t kv_budget_blocks(kv_pool* p, int32_t dir, double interval_us) {
+int64_t kv_budget_blocks(kv_pool* p, int32_t dir, double interval_us) try {
   if (!p || (dir != 0 && dir != 1) || !(interval_us >= 0)) return KV_EINVAL;
   std::lock_guard<std::mutex> g(p->mu);
   return budget_blocks_locked(p, dir, interval_us);
 }
+KV_CATCH(p)
 
 int kv_swap_out_delta_timed(kv_pool* p, int32_t n, const uint64_t* req_ids, const int32_t* offsets,
                             const int32_t* block_ids, const int32_t* num_tokens, const float* priority,
                             double interval_us, uint32_t flags, int32_t* blocks_moved, int64_t* budget_used,
-                            void* wait_event) {
+                            void* wait_event) try {
   if (!p || !(interval_us >= 0)) return KV_EINVAL;
   if (n < 0 || (n > 0 && (!req_ids || !offsets || !num_tokens))) return KV_EINVAL;
-  std::lock_guard<std::mutex> g(p->mu);
+  KV_ENTER(p);
   const double t0 = now_us();
   const int64_t budget = budget_blocks_locked(p, 0, interval_us);
   if (budget_used) *budget_used = budget;
@@ -510,11 +543,12 @@ int kv_swap_out_delta_timed(kv_pool* p, int32_t n, const uint64_t* req_ids, cons
     for (int32_t k = 0; k < n; k++) blocks_moved[order[(size_t)k]] = moved[(size_t)k];
   return swap_out_common(p, 2, plan, t0, wait_event);
 }
+KV_CATCH(p)
 
 int kv_wq_post(kv_pool* p, int32_t n, const uint64_t* req_ids, const int32_t* offsets, const int32_t* block_ids,
-               const int32_t* num_tokens, const double* priority) {
+               const int32_t* num_tokens, const double* priority) try {
   if (!p || n < 0 || (n > 0 && (!req_ids || !offsets || !num_tokens))) return KV_EINVAL;
-  std::lock_guard<std::mutex> g(p->mu);
+  KV_ENTER(p);
   const int64_t B = p->cfg.block_size, N = p->cfg.num_blocks;
   if (n > 0 && offsets[0] < 0) return KV_EINVAL;
   for (int32_t i = 0; i < n; i++) {
@@ -539,12 +573,14 @@ int kv_wq_post(kv_pool* p, int32_t n, const uint64_t* req_ids, const int32_t* of
   }
   return KV_OK;
 }
+KV_CATCH(p)
 
-int kv_wq_remove(kv_pool* p, uint64_t req_id) {
+int kv_wq_remove(kv_pool* p, uint64_t req_id) try {
   if (!p) return KV_EINVAL;
-  std::lock_guard<std::mutex> g(p->mu);
+  KV_ENTER(p);
   return p->wq.erase(req_id) ? KV_OK : KV_ENOENT;
 }
+KV_CATCH(p)
 
 // Full blocks the queued requests have not written through yet.
 static void wq_count(kv_pool* p, int64_t* blocks, int32_t* requests) {
@@ -562,17 +598,18 @@ static void wq_count(kv_pool* p, int64_t* blocks, int32_t* requests) {
   if (requests) *requests = nr;
 }
 
-int kv_wq_pending(kv_pool* p, int64_t* blocks, int32_t* requests) {
+int kv_wq_pending(kv_pool* p, int64_t* blocks, int32_t* requests) try {
   if (!p) return KV_EINVAL;
   std::lock_guard<std::mutex> g(p->mu);
   wq_count(p, blocks, requests);
   return KV_OK;
 }
+KV_CATCH(p)
 
 int kv_wq_drain(kv_pool* p, double interval_us, int64_t block_budget, uint32_t flags, int64_t* blocks_written,
-                int64_t* blocks_pending, int64_t* budget_used, void* wait_event) {
+                int64_t* blocks_pending, int64_t* budget_used, void* wait_event) try {
   if (!p || !(interval_us >= 0) || block_budget < 0) return KV_EINVAL;
-  std::lock_guard<std::mutex> g(p->mu);
+  KV_ENTER(p);
   const double t0 = now_us();
   const bool timed = block_budget == 0 && interval_us > 0;
   const int64_t budget = timed ? budget_blocks_locked(p, 0, interval_us) : block_budget;
@@ -604,6 +641,7 @@ int kv_wq_drain(kv_pool* p, double interval_us, int64_t block_budget, uint32_t f
   wq_count(p, blocks_pending, nullptr);
   return swap_out_common(p, 2, plan, t0, wait_event);
 }
+KV_CATCH(p)
 
 static int64_t budget_blocks_locked(kv_pool* p, int32_t dir, double interval_us) {
   kv_io_stats io;
@@ -616,7 +654,7 @@ static int64_t budget_blocks_locked(kv_pool* p, int32_t dir, double interval_us)
   return (int64_t)(left_us * rate * 1e3 / (double)p->S);
 }
 
-int64_t kv_last_plan(kv_pool* p, int32_t* phys, int64_t* slot, int64_t cap) {
+int64_t kv_last_plan(kv_pool* p, int32_t* phys, int64_t* slot, int64_t cap) try {
   if (!p) return KV_EINVAL;
   std::lock_guard<std::mutex> g(p->mu);
   const int64_t n = (int64_t)p->last_plan.size();
@@ -626,10 +664,11 @@ int64_t kv_last_plan(kv_pool* p, int32_t* phys, int64_t* slot, int64_t cap) {
   }
   return n;
 }
+KV_CATCH(p)
 
-int kv_pool_tune(kv_pool* p, int32_t what, int64_t value) {
+int kv_pool_tune(kv_pool* p, int32_t what, int64_t value) try {
   if (!p || value < 0) return KV_EINVAL;
-  std::lock_guard<std::mutex> g(p->mu);
+  KV_ENTER(p);
   switch (what) {
     case KV_TUNE_MAX_WGS_DEVICE:
       p->max_wgs_device = std::min<int64_t>(value, 1 << 30);
@@ -658,6 +697,7 @@ int kv_pool_tune(kv_pool* p, int32_t what, int64_t value) {
       return KV_EINVAL;
   }
 }
+KV_CATCH(p)
 
 int kv_last_hip_error(const kv_pool* p) { return p ? p->last_hip : 0; }
 
@@ -672,6 +712,7 @@ const char* kv_strerror(int code) {
     case KV_ENOSPC: return "staging arena full";
     case KV_EHIP: return "HIP runtime error";
     case KV_ESTATE: return "token count below the watermark";
+    case KV_ENOMEM: return "out of host memory for the library's bookkeeping";
     default: return "unknown status";
   }
 }

@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libkvswap.so")
 
 KV_OK, KV_EINVAL, KV_ERANGE, KV_EDUP, KV_ENOENT = 0, -1, -2, -3, -4
-KV_EEXIST, KV_ENOSPC, KV_EHIP, KV_ESTATE = -5, -6, -7, -8
+KV_EEXIST, KV_ENOSPC, KV_EHIP, KV_ESTATE, KV_ENOMEM = -5, -6, -7, -8, -9
 KV_PATH_AUTO, KV_PATH_DMA, KV_PATH_ZEROCOPY, KV_STAGING_DEVICE, KV_PLAN_ONLY, KV_REQ_EVENTS = 0, 1, 2, 4, 8, 16
 KV_DELTA_INCLUDE_TAIL = 1
 KV_KEEP_STAGING = 1

@@ -40,6 +40,11 @@ void set_policy(int policy, Stream* starved);
 void enqueue(Stream* s, std::function<void()> fn);
 long executed_ops();
 long deadlocks();
+// Failure injection: the n-th call from now, counted over the calls that can fail on a real device (event
+// creation, record, wait, query and synchronisation, stream synchronisation, copies, kernel launches), returns
+// `code` and does nothing else; n <= 0 disarms.  failure_fired() tells whether it has happened.
+void fail_after(long n, int code);
+bool failure_fired();
 }  // namespace mockhip
 
 typedef mockhip::Stream* hipStream_t;

@@ -47,7 +47,19 @@ static Stream null_stream;
 static std::recursive_mutex api_mu;
 #define API_LOCK std::lock_guard<std::recursive_mutex> api_guard(api_mu)
 
+static long fail_in = 0;
+static int fail_code = 0;
+static bool fail_fired = false;
+
 static Stream* S(hipStream_t s) { return s ? s : &null_stream; }
+
+// true when this call is the one chosen to fail
+static bool injected() {
+  if (fail_in <= 0 || --fail_in > 0) return false;
+  fail_fired = true;
+  last_error = fail_code;
+  return true;
+}
 
 static bool runnable(Stream* s) {
   if (s->q.empty()) return false;
@@ -119,10 +131,24 @@ void set_policy(int p, Stream* s) {
   policy = p;
   starved = s;
 }
-void enqueue(Stream* s, std::function<void()> fn) {
-  API_LOCK;
+static void push_fn(Stream* s, std::function<void()> fn) {
   S(s)->q.push_back({0, std::move(fn), nullptr, 0});
   progress();
+}
+void enqueue(Stream* s, std::function<void()> fn) {
+  API_LOCK;
+  if (injected()) return;  // a failed launch: hipGetLastError() reports it
+  push_fn(s, std::move(fn));
+}
+void fail_after(long n, int code) {
+  API_LOCK;
+  fail_in = n;
+  fail_code = code;
+  fail_fired = false;
+}
+bool failure_fired() {
+  API_LOCK;
+  return fail_fired;
 }
 long executed_ops() {
   API_LOCK;
@@ -209,18 +235,28 @@ hipError_t hipStreamDestroy(hipStream_t s) {
   return hipSuccess;
 }
 hipError_t hipStreamSynchronize(hipStream_t s) {
+  {
+    API_LOCK;
+    if (injected()) return fail_code;
+  }
   Stream* st = S(s);
   drive([&] { return st->q.empty(); });
   return hipSuccess;
 }
 hipError_t hipStreamWaitEvent(hipStream_t s, hipEvent_t e, unsigned) {
   API_LOCK;
+  if (injected()) return fail_code;
   if (e->recorded == 0) return hipSuccess;  // never recorded: nothing to wait for
   S(s)->q.push_back({2, nullptr, e, e->recorded});
   progress();
   return hipSuccess;
 }
-hipError_t hipEventCreate(hipEvent_t* e) { *e = new Event; return hipSuccess; }
+hipError_t hipEventCreate(hipEvent_t* e) {
+  API_LOCK;
+  if (injected()) return fail_code;
+  *e = new Event;
+  return hipSuccess;
+}
 hipError_t hipEventDestroy(hipEvent_t e) {
   API_LOCK;
   // operations that still name the event are a use after free in the program under test
@@ -235,6 +271,7 @@ hipError_t hipEventDestroy(hipEvent_t e) {
 }
 hipError_t hipEventRecord(hipEvent_t e, hipStream_t s) {
   API_LOCK;
+  if (injected()) return fail_code;
   e->recorded++;
   S(s)->q.push_back({1, nullptr, e, e->recorded});
   progress();
@@ -242,12 +279,14 @@ hipError_t hipEventRecord(hipEvent_t e, hipStream_t s) {
 }
 hipError_t hipEventQuery(hipEvent_t e) {
   API_LOCK;
+  if (injected()) return fail_code;
   return e->completed >= e->recorded ? hipSuccess : hipErrorNotReady;
 }
 hipError_t hipEventSynchronize(hipEvent_t e) {
   uint64_t gen;
   {
     API_LOCK;
+    if (injected()) return fail_code;
     gen = e->recorded;
   }
   drive([&] { return e->completed >= gen; });
@@ -261,6 +300,8 @@ hipError_t hipEventElapsedTime(float* ms, hipEvent_t a, hipEvent_t b) {
   return hipSuccess;
 }
 hipError_t hipMemcpyAsync(void* dst, const void* src, size_t n, hipMemcpyKind, hipStream_t s) {
-  mockhip::enqueue(s, [=]() { std::memcpy(dst, src, n); });
+  API_LOCK;
+  if (injected()) return fail_code;
+  push_fn(s, [=]() { std::memcpy(dst, src, n); });
   return hipSuccess;
 }

@@ -16,7 +16,12 @@
 // every chunk: built with ThreadSanitizer this checks that every entry point takes the handle's lock, and the
 // comparison with the oracle that such readers change nothing.
 //
-// usage: runtime_on_mock_hip <seed> <chunks> [poller]
+// "hipfail": in one chunk some HIP call inside the library fails (the stand-in's failure injection); "nomem": some
+// allocation made while a library call runs throws std::bad_alloc.  Either the library absorbs it and the history
+// goes on equal to the oracle, or the call returns KV_EHIP / KV_ENOMEM; from then on the handle must refuse every
+// call that changes state, still answer queries, and kv_pool_destroy must release everything (LeakSanitizer).
+//
+// usage: runtime_on_mock_hip <seed> <chunks> [poller|hipfail|nomem]
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -32,7 +37,48 @@ extern "C" {
 #include "../../oracle/kv_oracle.h"
 }
 
+// ---- allocation failures, only while a library call runs ----
+static bool g_in_lib = false;
+static long g_new_fail_in = 0;
+static bool g_new_fired = false;
+#if defined(__has_feature) && __has_feature(thread_sanitizer)
+// ThreadSanitizer brings its own operator new: the "nomem" mode is not available in that build
+#else
+void* operator new(std::size_t n) {
+  if (g_in_lib && g_new_fail_in > 0 && --g_new_fail_in == 0) {
+    g_new_fired = true;
+    throw std::bad_alloc();
+  }
+  if (void* q = std::malloc(n ? n : 1)) return q;
+  throw std::bad_alloc();
+}
+void* operator new[](std::size_t n) { return operator new(n); }
+void* operator new(std::size_t n, const std::nothrow_t&) noexcept {
+  try {
+    return operator new(n);
+  } catch (...) {
+    return nullptr;
+  }
+}
+void* operator new[](std::size_t n, const std::nothrow_t& t) noexcept { return operator new(n, t); }
+void operator delete(void* q) noexcept { std::free(q); }
+void operator delete(void* q, std::size_t) noexcept { std::free(q); }
+void operator delete[](void* q) noexcept { std::free(q); }
+void operator delete[](void* q, std::size_t) noexcept { std::free(q); }
+void operator delete(void* q, const std::nothrow_t&) noexcept { std::free(q); }
+void operator delete[](void* q, const std::nothrow_t&) noexcept { std::free(q); }
+#endif
+static int leave_lib(int rc) {
+  g_in_lib = false;
+  return rc;
+}
+#define LIB(call) (g_in_lib = true, leave_lib(call))
+
 namespace {
+
+struct Failed {  // the armed failure has surfaced as this status of a library call
+  int rc;
+};
 
 [[noreturn]] void die(const char* what, int chunk, int step) {
   std::fprintf(stderr, "MISMATCH in chunk %d at step %d: %s\n", chunk, step, what);
@@ -49,7 +95,8 @@ struct Geo {
 int main(int argc, char** argv) {
   const uint64_t seed = argc > 1 ? std::strtoull(argv[1], nullptr, 10) : 1;
   const int chunks = argc > 2 ? std::atoi(argv[2]) : 8;
-  const bool poller = argc > 3;
+  const std::string extra = argc > 3 ? argv[3] : "";
+  const bool poller = extra == "poller", hipfail = extra == "hipfail", nomem = extra == "nomem";
   std::mt19937_64 rng(seed * 7919 + 13);
   auto rnd = [&](int64_t lo, int64_t hi) { return lo + (int64_t)(rng() % (uint64_t)(hi - lo + 1)); };
   mockhip::reset(seed);
@@ -141,6 +188,7 @@ int main(int argc, char** argv) {
   long calls = 0;
 
   auto both = [&](int rc_lib, int rc_ora, const char* what, int chunk, int step) {
+    if ((rc_lib == KV_EHIP && mockhip::failure_fired()) || (rc_lib == KV_ENOMEM && g_new_fired)) throw Failed{rc_lib};
     if (rc_lib != rc_ora || rc_lib != 0) {
       std::fprintf(stderr, "%s: library %d oracle %d\n", what, rc_lib, rc_ora);
       die("return code", chunk, step);
@@ -159,7 +207,8 @@ int main(int argc, char** argv) {
   };
   // a reservation may find no run of free slots long enough: both sides must say so, and nothing has changed then
   auto reserve = [&](int r, int64_t n, const char* what, int chunk, int step) {
-    const int rc_lib = kv_req_reserve(kp, (uint64_t)r, n), rc_ora = ora_req_reserve(ora, (uint64_t)r, n);
+    const int rc_lib = LIB(kv_req_reserve(kp, (uint64_t)r, n)), rc_ora = ora_req_reserve(ora, (uint64_t)r, n);
+    if ((rc_lib == KV_EHIP && mockhip::failure_fired()) || (rc_lib == KV_ENOMEM && g_new_fired)) throw Failed{rc_lib};
     if (rc_lib != rc_ora || (rc_lib != 0 && rc_lib != KV_ENOSPC)) {
       std::fprintf(stderr, "%s: library %d oracle %d\n", what, rc_lib, rc_ora);
       die("return code", chunk, step);
@@ -172,7 +221,16 @@ int main(int argc, char** argv) {
     table[(size_t)r].clear();
   };
 
+  const int fail_chunk = hipfail || nomem ? (int)rnd(0, chunks - 1) : -1;
+  const long fail_at = hipfail ? (long)rnd(1, 60) : (long)rnd(1, 300);
+  bool handled = false;
+  int handled_rc = 0;
+  try {
   for (int chunk = 0; chunk < chunks; chunk++) {
+    if (chunk == fail_chunk) {
+      if (hipfail) mockhip::fail_after(fail_at, 999);
+      if (nomem) g_new_fail_in = fail_at;
+    }
     // who lags in this chunk
     const int pol = policy == 0 ? mockhip::kRandom : policy == 3 ? mockhip::kLazy : (chunk + policy) % 2 ? mockhip::kStarve0 : mockhip::kStarve1;
     mockhip::set_policy(pol, pol == mockhip::kStarve0 ? evict : pol == mockhip::kStarve1 ? load : nullptr);
@@ -192,7 +250,7 @@ int main(int argc, char** argv) {
       };
       auto cold_out = [&](int r) {
         csr({r}, ids, off, blk, tok);
-        both(kv_swap_out(kp, 1, ids.data(), off.data(), blk.data(), tok.data(), nullptr),
+        both(LIB(kv_swap_out(kp, 1, ids.data(), off.data(), blk.data(), tok.data(), nullptr)),
              ora_swap_out(ora, 1, ids.data(), off.data(), blk.data(), tok.data()), "opening swap_out", 0, -1);
         give_up(r);
         state[(size_t)r] = 2;
@@ -202,7 +260,7 @@ int main(int argc, char** argv) {
       cold_out(1);
       for (int j = 0; j < 4; j++) { table[1].push_back(free_list.back()); free_list.pop_back(); }
       csr({1}, ids, off, blk, tok);
-      both(kv_swap_in(kp, 1, ids.data(), off.data(), blk.data(), 0, nullptr), ora_swap_in(ora, 1, ids.data(), off.data(), blk.data(), 0),
+      both(LIB(kv_swap_in(kp, 1, ids.data(), off.data(), blk.data(), 0, nullptr)), ora_swap_in(ora, 1, ids.data(), off.data(), blk.data(), 0),
            "opening swap_in", 0, -1);
       held = table[1];  // kept out of circulation until the chunk's comparison: what the swap-in wrote must still be there
       table[1].clear();
@@ -210,11 +268,11 @@ int main(int argc, char** argv) {
       cold_out(2);
       give_up(2);
       length[2] = 0; state[2] = 0;
-      both(kv_req_release(kp, 2), ora_req_release(ora, 2), "opening release", 0, -1);
+      both(LIB(kv_req_release(kp, 2)), ora_req_release(ora, 2), "opening release", 0, -1);
       fill(3, 7);
       csr({3}, ids, off, blk, tok);
       std::vector<int32_t> ma(1), mb(1);
-      both(kv_swap_out_delta(kp, 1, ids.data(), off.data(), blk.data(), tok.data(), 0, 0, mb.data(), nullptr),
+      both(LIB(kv_swap_out_delta(kp, 1, ids.data(), off.data(), blk.data(), tok.data(), 0, 0, mb.data(), nullptr)),
            ora_swap_out_delta(ora, 1, ids.data(), off.data(), blk.data(), tok.data(), 0, 0, ma.data()), "opening delta", 0, -1);
       if (ma != mb) die("blocks_moved", 0, -1);
     }
@@ -276,7 +334,7 @@ int main(int argc, char** argv) {
           csr(with, ids, off, blk, tok);
           const int64_t budget = rnd(0, 5);
           std::vector<int32_t> ma(with.size(), -1), mb(with.size(), -1);
-          both(kv_swap_out_delta(kp, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), budget, 0, mb.data(), nullptr),
+          both(LIB(kv_swap_out_delta(kp, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), budget, 0, mb.data(), nullptr)),
                ora_swap_out_delta(ora, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), budget, 0, ma.data()),
                "delta", chunk, step);
           if (ma != mb) die("blocks_moved", chunk, step);
@@ -289,11 +347,11 @@ int main(int argc, char** argv) {
         if (rs.empty()) continue;
         csr(rs, ids, off, blk, tok);
         if (op == 4) {
-          both(kv_swap_out(kp, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), nullptr),
+          both(LIB(kv_swap_out(kp, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), nullptr)),
                ora_swap_out(ora, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data()), "swap_out", chunk, step);
         } else {
           std::vector<int32_t> ma(rs.size()), mb(rs.size());
-          both(kv_swap_out_delta(kp, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), 0, KV_DELTA_INCLUDE_TAIL, mb.data(), nullptr),
+          both(LIB(kv_swap_out_delta(kp, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), 0, KV_DELTA_INCLUDE_TAIL, mb.data(), nullptr)),
                ora_swap_out_delta(ora, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), 0, KV_DELTA_INCLUDE_TAIL, ma.data()),
                "tail delta", chunk, step);
         }
@@ -313,7 +371,7 @@ int main(int argc, char** argv) {
         }
         csr(rs, ids, off, blk, tok);
         const bool keep = rnd(0, 9) < 7;
-        both(kv_swap_in(kp, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), keep ? KV_KEEP_STAGING : 0, nullptr),
+        both(LIB(kv_swap_in(kp, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), keep ? KV_KEEP_STAGING : 0, nullptr)),
              ora_swap_in(ora, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), keep ? KV_KEEP_STAGING : 0), "swap_in", chunk, step);
         for (int r : rs) {
           state[(size_t)r] = 1;
@@ -330,7 +388,7 @@ int main(int argc, char** argv) {
         if (!k) continue;
         std::vector<int32_t> src(table[(size_t)r].begin(), table[(size_t)r].begin() + (long)k), dst;
         for (size_t j = 0; j < k; j++) { dst.push_back(free_list.back()); free_list.pop_back(); }
-        both(kv_move_blocks(kp, (int64_t)k, src.data(), dst.data(), nullptr), ora_move_blocks(ora, (int64_t)k, src.data(), dst.data()),
+        both(LIB(kv_move_blocks(kp, (int64_t)k, src.data(), dst.data(), nullptr)), ora_move_blocks(ora, (int64_t)k, src.data(), dst.data()),
              "move", chunk, step);
         std::copy(dst.begin(), dst.end(), table[(size_t)r].begin());
         free_list.insert(free_list.end(), src.begin(), src.end());
@@ -340,9 +398,10 @@ int main(int argc, char** argv) {
         const int r = live[(size_t)rnd(0, (int64_t)live.size() - 1)];
         give_up(r);
         length[(size_t)r] = 0; state[(size_t)r] = 0;
-        both(kv_req_release(kp, (uint64_t)r), ora_req_release(ora, (uint64_t)r), "release", chunk, step);
+        both(LIB(kv_req_release(kp, (uint64_t)r)), ora_req_release(ora, (uint64_t)r), "release", chunk, step);
       } else if (op == 10 && events && !running.empty()) {  // a control thread's poll: must not disturb anything
-        const int rc = kv_req_poll(kp, (uint64_t)running[0]);
+        const int rc = LIB(kv_req_poll(kp, (uint64_t)running[0]));
+        if ((rc == KV_EHIP && mockhip::failure_fired()) || (rc == KV_ENOMEM && g_new_fired)) throw Failed{rc};
         if (rc != 0 && rc != 1) die("kv_req_poll", chunk, step);
       }
     }
@@ -351,7 +410,13 @@ int main(int argc, char** argv) {
       stop = true;
       side.join();
     }
-    if (kv_sync(kp) != KV_OK) die("kv_sync", chunk, -1);
+    {
+      const int rc = LIB(kv_sync(kp));
+      if ((rc == KV_EHIP && mockhip::failure_fired()) || (rc == KV_ENOMEM && g_new_fired)) throw Failed{rc};
+      if (rc != KV_OK) die("kv_sync", chunk, -1);
+    }
+    mockhip::fail_after(0, 0);  // an armed failure that this chunk did not reach stays unused
+    g_new_fail_in = 0;
     if (std::memcmp(pool_a.data(), pool_b, pool_bytes)) die("pool bytes", chunk, -1);
     if (std::memcmp(stag_a.data(), stag_b, stag_bytes)) die("arena bytes", chunk, -1);
     if (scales && std::memcmp(scale_a.data(), scale_b, scale_bytes)) die("scale bytes", chunk, -1);
@@ -364,6 +429,29 @@ int main(int argc, char** argv) {
       if (qa != qb || (qa == 0 && (oa != ob || ca != cb || sa != sb || wa != wb || xa != xb))) die("request state", chunk, r);
     }
   }
+  } catch (const Failed& f) {
+    // The call in which the failure surfaced has returned KV_EHIP or KV_ENOMEM.  From here on the handle refuses
+    // whatever would change state or enqueue work, still answers queries, and can be destroyed.
+    handled = true;
+    handled_rc = f.rc;
+    mockhip::fail_after(0, 0);
+    g_new_fail_in = 0;
+    if (f.rc == KV_EHIP && kv_last_hip_error(kp) != 999) die("kv_last_hip_error after an injected failure", -1, -1);
+    uint64_t id = 1;
+    int32_t off1[2] = {0, 1}, blk1[2] = {0, 1}, tok1[1] = {1}, moved1[1];
+    int64_t a = 0, b = 0, c = 0;
+    if (kv_req_reserve(kp, 1000, 1) != KV_EHIP || kv_req_release(kp, 1) != KV_EHIP ||
+        kv_swap_out(kp, 1, &id, off1, blk1, tok1, nullptr) != KV_EHIP ||
+        kv_swap_out_delta(kp, 1, &id, off1, blk1, tok1, 0, 0, moved1, nullptr) != KV_EHIP ||
+        kv_swap_in(kp, 1, &id, off1, blk1, 0, nullptr) != KV_EHIP || kv_move_blocks(kp, 1, blk1, blk1 + 1, nullptr) != KV_EHIP ||
+        kv_wq_post(kp, 1, &id, off1, blk1, tok1, nullptr) != KV_EHIP || kv_wq_drain(kp, 0, 4, 0, &a, &b, &c, nullptr) != KV_EHIP ||
+        kv_sync(kp) != KV_EHIP || kv_pool_tune(kp, KV_TUNE_MAX_WGS_LINK, 8) != KV_EHIP)
+      die("a call was accepted by a handle that had failed", -1, -1);
+    kv_io_stats io;
+    int32_t x;
+    const int q = kv_req_query(kp, 1, &a, &x, &x, &x, &x);
+    if (kv_io_stats_get(kp, &io) != KV_OK || (q != KV_OK && q != KV_ENOENT)) die("queries after a failure", -1, -1);
+  }
   if (kv_pool_destroy(kp) != KV_OK) die("kv_pool_destroy", -1, -1);
   ora_destroy(ora);
   hipStreamDestroy(evict);
@@ -371,6 +459,11 @@ int main(int argc, char** argv) {
   hipFree(pool_b); hipFree(scale_b);
   mode == 2 ? hipFree(stag_b) : hipHostFree(stag_b);
   if (bounce) hipFree(bounce);
+  if (handled) {
+    std::printf("seed %llu: failure handled: the call returned %d, the handle then refused further work and was destroyed\n",
+                (unsigned long long)seed, handled_rc);
+    return 0;
+  }
   std::printf("seed %llu: %ld calls, %ld device operations, geometry %d mode %d events %d policy %d: equal to the oracle\n",
               (unsigned long long)seed, calls, mockhip::executed_ops(), (int)(seed % 4), mode, (int)events, policy);
   return calls > 40 ? 0 : 2;

@@ -6,7 +6,8 @@ does the same for the scheduler and the metrics (invariants instead of an oracle
 tests/native/abi_from_c.c is a C99 client of both headers against the built library, in plan-only mode;
 tests/native/runtime_on_mock_hip.cpp runs the library's host runtime and its kernel source, unchanged, on a
 host-only stand-in for the HIP runtime (tests/native/mockhip) whose executor decides which stream lags, and
-compares random serving histories with the oracle.  See their headers.
+compares random serving histories with the oracle; the same driver injects HIP errors and allocation failures,
+and runs with a second thread under ThreadSanitizer.  See their headers.
 """
 import os
 import subprocess
@@ -94,6 +95,22 @@ def test_runtime_and_kernels_on_the_stand_in_hip_runtime(mock_driver, first):
         r = subprocess.run([mock_driver, str(seed), "6"], capture_output=True, text=True, timeout=300, env=env)
         assert r.returncode == 0, "seed %d\n%s%s" % (seed, r.stdout[-2000:], r.stderr[-4000:])
         assert "equal to the oracle" in r.stdout
+
+
+@pytest.mark.parametrize("what", ["hipfail", "nomem"])
+def test_a_failure_inside_a_call_leaves_a_handle_that_refuses_work_and_can_be_destroyed(mock_driver, what):
+    """hipfail: some HIP call made by the library returns an error; nomem: some allocation made while a library
+    call runs throws.  No exception leaves the C boundary, the call returns KV_EHIP / KV_ENOMEM, every later call
+    that would change state returns KV_EHIP, queries still answer, kv_pool_destroy releases every event and
+    buffer (LeakSanitizer); a failure the library can absorb leaves the history equal to the oracle."""
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    handled = 0
+    for seed in range(0, 96):
+        r = subprocess.run([mock_driver, str(seed), "4", what], capture_output=True, text=True, timeout=300, env=env)
+        assert r.returncode == 0, "seed %d\n%s%s" % (seed, r.stdout[-2000:], r.stderr[-4000:])
+        assert "equal to the oracle" in r.stdout or "failure handled" in r.stdout
+        handled += "failure handled" in r.stdout
+    assert handled >= 40, handled
 
 
 # One ordering rule of the runtime is taken out at a time (in a copy of the sources); the same histories must then
