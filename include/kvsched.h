@@ -20,7 +20,7 @@
 extern "C" {
 #endif
 
-enum { KVS_OK = 0, KVS_EINVAL = -1 };
+enum { KVS_OK = 0, KVS_EINVAL = -1, KVS_ENOMEM = -2 /* working arrays could not be allocated */ };
 
 /* ------------------------------------------------------------------ metrics */
 

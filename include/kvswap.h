@@ -52,8 +52,8 @@
  *     changes any state or enqueues any work.  KV_EHIP and KV_ENOMEM are the exception: a HIP
  *     runtime failure or an allocation failure in the middle of a call leaves bookkeeping and
  *     streams out of step.  The handle remembers it: every later call that would change state or
- *     enqueue work returns KV_EHIP without doing anything; queries (kv_req_query, kv_last_stats,
- *     kv_io_stats_get, kv_last_hip_error) still answer, and kv_pool_destroy releases everything.
+ *     enqueue work returns KV_EHIP without doing anything; kv_req_query, kv_io_stats_get and
+ *     kv_last_hip_error still answer, and kv_pool_destroy releases everything.
  *   - Calls are asynchronous.  Swap-out / delta / move work is enqueued on the evict stream,
  *     swap-in work on the load stream, in issue order.  The library inserts every cross-stream
  *     wait the two streams need between themselves: for staging slots (a swap-in reads slots an

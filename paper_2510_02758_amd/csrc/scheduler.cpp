@@ -19,7 +19,7 @@ double kv_metric_token_weight(double B, double tau, double alpha) {
 }
 
 int kv_metric_stream(int32_t L, const double* t_gen, double t_arrival, double rate, int32_t* buffer, double* t_read,
-                     double* ttft, double* rebuffer) {
+                     double* ttft, double* rebuffer) try {
   if (L < 0 || (L > 0 && !t_gen) || !(rate > 0.0)) return KVS_EINVAL;
   for (int32_t j = 1; j < L; j++)
     if (t_gen[j] < t_gen[j - 1]) return KVS_EINVAL;
@@ -51,6 +51,8 @@ int kv_metric_stream(int32_t L, const double* t_gen, double t_arrival, double ra
   if (ttft) *ttft = L > 0 ? t_gen[0] - t_arrival : 0.0;
   if (rebuffer) *rebuffer = stall;
   return KVS_OK;
+} catch (...) {
+  return KVS_ENOMEM;  // only allocations can throw in here; nothing was written that the caller may use
 }
 
 int kv_metric_weight_sum(int32_t L, const int32_t* buffer, double tau, double alpha, double* sum) {
@@ -79,7 +81,7 @@ int kv_metric_qos(int32_t n, const double* weight_sum, const double* ttft, const
   return KVS_OK;
 }
 
-int kv_sched_step(const kv_sched_config* cfg, int32_t n, const kv_sched_req* req, kv_sched_out* out, int32_t* mode) {
+int kv_sched_step(const kv_sched_config* cfg, int32_t n, const kv_sched_req* req, kv_sched_out* out, int32_t* mode) try {
   if (!cfg || cfg->struct_size != sizeof(kv_sched_config) || n < 0 || (n > 0 && (!req || !out)) || !mode)
     return KVS_EINVAL;
   if (!(cfg->interval > 0.0) || !(cfg->gen_rate > 0.0) || cfg->mem_blocks < 0 || cfg->max_running < 0 ||
@@ -248,6 +250,8 @@ int kv_sched_step(const kv_sched_config* cfg, int32_t n, const kv_sched_req* req
     }
   }
   return finish(KVS_MODE_BUFFER_AWARE);
+} catch (...) {
+  return KVS_ENOMEM;  // only allocations can throw in here; nothing was written that the caller may use
 }
 
 }  // extern "C"

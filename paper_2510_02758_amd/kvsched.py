@@ -8,7 +8,7 @@ from . import kvswap as _kv
 
 _lib = _kv._lib
 
-KVS_OK, KVS_EINVAL = 0, -1
+KVS_OK, KVS_EINVAL, KVS_ENOMEM = 0, -1, -2
 KVS_NEW, KVS_RUNNING, KVS_PREEMPTED = 0, 1, 2
 KVS_KEEP, KVS_RUN, KVS_PREEMPT = 0, 1, 2
 KVS_BY_LOAD, KVS_BY_RECOMPUTE = 0, 1
