@@ -241,7 +241,8 @@ int kv_req_query(kv_pool* p, uint64_t req_id, int64_t* staging_offset, int32_t* 
  * kv_wq_drain   one kv_swap_out_delta over the queued requests in order of decreasing priority (ties:
  *               order of posting).  Budget: block_budget > 0: that many blocks; else interval_us > 0:
  *               kv_budget_blocks(p, 0, interval_us), where 0 means nothing moves; both 0: unlimited.
- *               flags as kv_swap_out_delta.  blocks_written, blocks_pending (full blocks still not
+ *               flags as kv_swap_out_delta.  An entry whose token count a direct kv_swap_out_delta has
+ *               meanwhile gone past has nothing to write and is skipped.  blocks_written, blocks_pending (full blocks still not
  *               written through, over the whole queue) and budget_used are nullable.  A planning error
  *               (KV_ENOSPC, ...) leaves queue and state unchanged.
  * kv_wq_remove  forgets a request (KV_ENOENT if it is not queued).  kv_swap_out, kv_swap_in and

@@ -616,7 +616,12 @@ int kv_wq_drain(kv_pool* p, double interval_us, int64_t block_budget, uint32_t f
   if (budget_used) *budget_used = budget;
   std::vector<std::pair<uint64_t, const kv_pool::WqEntry*>> order;
   order.reserve(p->wq.size());
-  for (auto& kvp : p->wq) order.push_back({kvp.first, &kvp.second});
+  for (auto& kvp : p->wq) {
+    // An entry posted before a direct delta went past it has nothing left to write: it is skipped, not an error.
+    const kvswap::Req* r = p->planner.find(kvp.first);
+    if (r && kvp.second.tokens < (int64_t)r->wm * p->cfg.block_size) continue;
+    order.push_back({kvp.first, &kvp.second});
+  }
   std::sort(order.begin(), order.end(), [](const auto& a, const auto& b) {
     if (a.second->priority != b.second->priority) return a.second->priority > b.second->priority;
     return a.second->order < b.second->order;

@@ -308,7 +308,7 @@ int main(int argc, char** argv) {
       for (int r = 1; r <= R; r++) (state[(size_t)r] == 1 ? running : state[(size_t)r] == 2 ? out : idle).push_back(r);
       std::vector<uint64_t> ids;
       std::vector<int32_t> off, blk, tok;
-      int op = (int)rnd(0, 10);
+      int op = (int)rnd(0, 12);
       if (op == 0 && !idle.empty() && free_list.size() > 8) {  // start
         const int r = idle[(size_t)rnd(0, (int64_t)idle.size() - 1)];
         cap[(size_t)r] = (int)rnd(3, cap_max);
@@ -399,6 +399,70 @@ int main(int argc, char** argv) {
         give_up(r);
         length[(size_t)r] = 0; state[(size_t)r] = 0;
         both(LIB(kv_req_release(kp, (uint64_t)r)), ora_req_release(ora, (uint64_t)r), "release", chunk, step);
+      } else if (op == 11 && !running.empty()) {  // the write queue: post every running request, drain under a budget
+        std::vector<int> with;
+        for (int r : running)
+          if (!table[(size_t)r].empty()) with.push_back(r);
+        if (with.empty()) continue;
+        std::shuffle(with.begin(), with.end(), rng);
+        csr(with, ids, off, blk, tok);
+        std::vector<double> prio(with.size());
+        for (auto& x : prio) x = (double)rnd(0, 3);  // few levels: ties keep the order of the post
+        both(LIB(kv_wq_post(kp, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), prio.data())), 0, "wq_post", chunk, step);
+        // what the queue promises: the same as one delta over the posted requests, highest priority first
+        std::vector<int> order(with.size());
+        for (size_t i = 0; i < order.size(); i++) order[i] = (int)i;
+        std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return prio[(size_t)a] > prio[(size_t)b]; });
+        std::vector<int> sorted;
+        for (int i : order) sorted.push_back(with[(size_t)i]);
+        csr(sorted, ids, off, blk, tok);
+        const int64_t budget = rnd(1, 6);
+        std::vector<int32_t> ma(sorted.size(), 0);
+        int64_t written = -1, pending = -1, used = -1, expect = 0;
+        both(LIB(kv_wq_drain(kp, 0.0, budget, 0, &written, &pending, &used, nullptr)),
+             ora_swap_out_delta(ora, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), budget, 0, ma.data()),
+             "wq_drain", chunk, step);
+        for (int32_t m : ma) expect += m;
+        if (written != expect || used != budget) die("wq_drain: blocks written", chunk, step);
+      } else if (op == 12) {  // calls that must be refused, with the same code on both sides and nothing changed
+        auto same = [&](int rc_lib, int rc_ora, const char* what) {
+          if ((rc_lib == KV_EHIP && mockhip::failure_fired()) || (rc_lib == KV_ENOMEM && g_new_fired)) throw Failed{rc_lib};
+          if (rc_lib != rc_ora || rc_lib == 0) {
+            std::fprintf(stderr, "%s: library %d oracle %d\n", what, rc_lib, rc_ora);
+            die("refusal", chunk, step);
+          }
+          calls++;
+        };
+        const int which = (int)rnd(0, 3);
+        if (which == 0 && !out.empty() && length[(size_t)out[0]] > g.B && free_list.size() > 4) {  // one destination twice
+          const int r = out[0];
+          const size_t nb = (size_t)((length[(size_t)r] + g.B - 1) / g.B);
+          std::vector<int32_t> dst(nb, free_list.back());
+          uint64_t id = (uint64_t)r;
+          int32_t o2[2] = {0, (int32_t)nb};
+          same(LIB(kv_swap_in(kp, 1, &id, o2, dst.data(), 0, nullptr)), ora_swap_in(ora, 1, &id, o2, dst.data(), 0), "duplicate destination");
+        } else if (which == 1 && !running.empty() && !table[(size_t)running[0]].empty()) {  // a block id outside the pool
+          const int r = running[0];
+          csr({r}, ids, off, blk, tok);
+          blk.back() = (int32_t)g.N;
+          same(LIB(kv_swap_out(kp, 1, ids.data(), off.data(), blk.data(), tok.data(), nullptr)),
+               ora_swap_out(ora, 1, ids.data(), off.data(), blk.data(), tok.data()), "block id out of range");
+        } else if (which == 2 && free_list.size() > 2) {  // resuming a request nobody has heard of
+          uint64_t id = 999;
+          int32_t o2[2] = {0, 1}, dst[1] = {free_list.back()};
+          same(LIB(kv_swap_in(kp, 1, &id, o2, dst, 0, nullptr)), ora_swap_in(ora, 1, &id, o2, dst, 0), "swap-in of an unknown request");
+        } else if (which == 3 && !out.empty()) {  // writing through what is out
+          const int r = out[0];
+          int64_t o = 0;
+          int32_t c = 0, st = 0, w = 0, sw = 0;
+          if (ora_req_query(ora, (uint64_t)r, &o, &c, &st, &w, &sw) != 0 || !sw) continue;  // preempted warm: a delta is still legal
+          const size_t nb = (size_t)((length[(size_t)r] + g.B - 1) / g.B);
+          std::vector<int32_t> src(nb, 0);
+          uint64_t id = (uint64_t)r;
+          int32_t o2[2] = {0, (int32_t)nb}, t2[1] = {length[(size_t)r]}, ma[1], mb[1];
+          same(LIB(kv_swap_out_delta(kp, 1, &id, o2, src.data(), t2, 0, 0, mb, nullptr)),
+               ora_swap_out_delta(ora, 1, &id, o2, src.data(), t2, 0, 0, ma), "delta of a swapped-out request");
+        }
       } else if (op == 10 && events && !running.empty()) {  // a control thread's poll: must not disturb anything
         const int rc = LIB(kv_req_poll(kp, (uint64_t)running[0]));
         if ((rc == KV_EHIP && mockhip::failure_fired()) || (rc == KV_ENOMEM && g_new_fired)) throw Failed{rc};

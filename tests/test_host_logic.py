@@ -327,6 +327,20 @@ def test_write_queue_entries_follow_the_requests():
     kp.close()
 
 
+def test_a_queue_entry_that_a_direct_delta_has_overtaken_is_skipped():
+    """A request posted with 4 tokens, then written through directly up to 8 tokens: its entry has nothing left to
+    write.  The drain must serve the other requests, not fail with KV_ESTATE."""
+    g = W.Geometry(1, 1, 8, 2, "f16", 64)
+    kp = kv.KVPool(g, flags=kv.KV_PLAN_ONLY, staging_bytes=40 * g.S)
+    assert kp.wq_post([1, 2], [0, 2, 4], [0, 1, 2, 3], [4, 4]) == kv.KV_OK
+    rc, moved = kp.swap_out_delta([1], [0, 4], [0, 1, 8, 9], [8])
+    assert rc == kv.KV_OK and list(moved) == [4]
+    rc, wrote, pend, _ = kp.wq_drain()
+    assert (rc, wrote, pend) == (kv.KV_OK, 2, 0)
+    assert kp.query(1)[1]["wm"] == 4 and kp.query(2)[1]["wm"] == 2     # watermarks: untouched, written
+    kp.close()
+
+
 @pytest.mark.parametrize("seed", range(4))
 def test_write_queue_random_against_oracle(seed):
     """Random growth, posts, budgets and preempt / resume cycles: after every drain the staged bytes and the
