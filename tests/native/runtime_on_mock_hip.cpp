@@ -5,7 +5,8 @@
 // streams are queues whose operations run when the stand-in's executor picks them, so this driver chooses how
 // far the "device" lags behind the host and which of the two streams is starved.  A seeded serving history
 // (growth with budgeted write-through, cold and warm preemption of one or several requests, resumption with and
-// without keeping the host image, compaction moves, releases, re-reservations) is played through the C ABI with
+// without keeping the host image, compaction moves, releases, re-reservations, write-queue rounds, calls that
+// must be refused) is played through the C ABI with
 // no synchronisation inside a chunk; blocks and slots given up by one call go to the next at once.  After every
 // chunk pool, scales and arena must equal what the oracle reaches by running the same calls one after the other,
 // and the per-request state must agree.  A missing wait between the streams shows up as a byte difference, a
@@ -152,9 +153,14 @@ int main(int argc, char** argv) {
   ora_state* ora = ora_create(&oc);
   if (!ora || ora_slot_bytes(ora) != g.S) die("oracle set-up", -1, -1);
 
-  hipStream_t evict, load;
+  hipStream_t evict, load, compute;  // compute: the "model", which writes KV into the pool on a stream of its own
   hipStreamCreateWithFlags(&evict, hipStreamNonBlocking);
   hipStreamCreateWithFlags(&load, hipStreamNonBlocking);
+  hipStreamCreateWithFlags(&compute, hipStreamNonBlocking);
+  hipEvent_t ev_evict, ev_load, ev_compute;
+  hipEventCreate(&ev_evict);
+  hipEventCreate(&ev_load);
+  hipEventCreate(&ev_compute);
   kv_pool_config kc;
   std::memset(&kc, 0, sizeof(kc));
   kc.struct_size = sizeof(kc);
@@ -184,10 +190,23 @@ int main(int argc, char** argv) {
   std::vector<std::vector<int32_t>> table((size_t)R + 1);
   std::vector<int32_t> length((size_t)R + 1, 0);
   std::vector<int> state((size_t)R + 1, 0);  // 0 idle, 1 running, 2 out
+  std::vector<uint64_t> trace_ids;  // what the last csr() built, for DRIVER_TRACE
+  std::vector<int32_t> trace_off, trace_blk;
   std::vector<int> cap((size_t)R + 1, 0);    // extent sizes differ, so that a new extent can lie over parts of several old ones
   long calls = 0;
 
+  const bool trace = std::getenv("DRIVER_TRACE") != nullptr;
   auto both = [&](int rc_lib, int rc_ora, const char* what, int chunk, int step) {
+    if (trace) {
+      std::fprintf(stderr, "[%d.%d] %s:", chunk, step, what);
+      for (size_t i = 0; i + 1 < trace_off.size(); i++) {
+        std::fprintf(stderr, " r%llu{", (unsigned long long)trace_ids[i]);
+        for (int32_t j = trace_off[i]; j < trace_off[i + 1]; j++) std::fprintf(stderr, "%d ", trace_blk[(size_t)j]);
+        std::fprintf(stderr, "}");
+      }
+      std::fprintf(stderr, "\n");
+      trace_ids.clear(); trace_off.clear(); trace_blk.clear();
+    }
     if ((rc_lib == KV_EHIP && mockhip::failure_fired()) || (rc_lib == KV_ENOMEM && g_new_fired)) throw Failed{rc_lib};
     if (rc_lib != rc_ora || rc_lib != 0) {
       std::fprintf(stderr, "%s: library %d oracle %d\n", what, rc_lib, rc_ora);
@@ -204,6 +223,7 @@ int main(int argc, char** argv) {
       off.push_back((int32_t)blk.size());
       tok.push_back(length[(size_t)r]);
     }
+    trace_ids = ids; trace_off = off; trace_blk = blk;
   };
   // a reservation may find no run of free slots long enough: both sides must say so, and nothing has changed then
   auto reserve = [&](int r, int64_t n, const char* what, int chunk, int step) {
@@ -235,6 +255,9 @@ int main(int argc, char** argv) {
     const int pol = policy == 0 ? mockhip::kRandom : policy == 3 ? mockhip::kLazy : (chunk + policy) % 2 ? mockhip::kStarve0 : mockhip::kStarve1;
     mockhip::set_policy(pol, pol == mockhip::kStarve0 ? evict : pol == mockhip::kStarve1 ? load : nullptr);
     std::vector<int32_t> held;
+    // Once the model has written on its own stream, the calls that WRITE pool blocks (swap-in, move) name the
+    // model's latest event, as an engine does when it hands blocks the model has touched to another owner.
+    void* after_model = nullptr;
     if (chunk == 0) {
       // A fixed opening on the empty arena: request 1 (slots 0..3) is swapped out and resumed without keeping its image,
       // so its slots are still being read by the load stream; request 2 (slots 4..6) is swapped out AFTER that and
@@ -308,7 +331,7 @@ int main(int argc, char** argv) {
       for (int r = 1; r <= R; r++) (state[(size_t)r] == 1 ? running : state[(size_t)r] == 2 ? out : idle).push_back(r);
       std::vector<uint64_t> ids;
       std::vector<int32_t> off, blk, tok;
-      int op = (int)rnd(0, 12);
+      int op = (int)rnd(0, 13);
       if (op == 0 && !idle.empty() && free_list.size() > 8) {  // start
         const int r = idle[(size_t)rnd(0, (int64_t)idle.size() - 1)];
         cap[(size_t)r] = (int)rnd(3, cap_max);
@@ -371,7 +394,7 @@ int main(int argc, char** argv) {
         }
         csr(rs, ids, off, blk, tok);
         const bool keep = rnd(0, 9) < 7;
-        both(LIB(kv_swap_in(kp, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), keep ? KV_KEEP_STAGING : 0, nullptr)),
+        both(LIB(kv_swap_in(kp, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), keep ? KV_KEEP_STAGING : 0, after_model)),
              ora_swap_in(ora, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), keep ? KV_KEEP_STAGING : 0), "swap_in", chunk, step);
         for (int r : rs) {
           state[(size_t)r] = 1;
@@ -388,7 +411,7 @@ int main(int argc, char** argv) {
         if (!k) continue;
         std::vector<int32_t> src(table[(size_t)r].begin(), table[(size_t)r].begin() + (long)k), dst;
         for (size_t j = 0; j < k; j++) { dst.push_back(free_list.back()); free_list.pop_back(); }
-        both(LIB(kv_move_blocks(kp, (int64_t)k, src.data(), dst.data(), nullptr)), ora_move_blocks(ora, (int64_t)k, src.data(), dst.data()),
+        both(LIB(kv_move_blocks(kp, (int64_t)k, src.data(), dst.data(), after_model)), ora_move_blocks(ora, (int64_t)k, src.data(), dst.data()),
              "move", chunk, step);
         std::copy(dst.begin(), dst.end(), table[(size_t)r].begin());
         free_list.insert(free_list.end(), src.begin(), src.end());
@@ -424,6 +447,32 @@ int main(int argc, char** argv) {
              "wq_drain", chunk, step);
         for (int32_t m : ma) expect += m;
         if (written != expect || used != budget) die("wq_drain: blocks written", chunk, step);
+      } else if (op == 13 && !running.empty() && !hipfail && !nomem) {
+        // The model overwrites a chunk of a request's last block on its own stream, after whatever the swap streams
+        // still do; the write-through that follows names the model's event and must carry the new bytes.
+        std::shuffle(running.begin(), running.end(), rng);
+        const int r = running[0];
+        if (table[(size_t)r].empty()) continue;
+        const int32_t b = table[(size_t)r].back();
+        const int l = (int)rnd(0, g.L - 1), c = (int)rnd(0, 1);
+        const size_t at = (size_t)(l * g.ls + c * g.ks + (int64_t)b * g.bs);
+        std::vector<uint8_t> fresh((size_t)g.chunk);
+        for (auto& x : fresh) x = (uint8_t)rng();
+        std::memcpy(pool_a.data() + at, fresh.data(), fresh.size());  // the oracle's pool has it at once
+        hipEventRecord(ev_evict, evict);
+        hipEventRecord(ev_load, load);
+        hipStreamWaitEvent(compute, ev_evict, 0);
+        hipStreamWaitEvent(compute, ev_load, 0);
+        uint8_t* dst = pool_b + at;
+        mockhip::enqueue(compute, [dst, fresh]() { std::memcpy(dst, fresh.data(), fresh.size()); });
+        hipEventRecord(ev_compute, compute);
+        after_model = ev_compute;
+        csr({r}, ids, off, blk, tok);
+        std::vector<int32_t> ma(1), mb(1);
+        both(LIB(kv_swap_out_delta(kp, 1, ids.data(), off.data(), blk.data(), tok.data(), 0, KV_DELTA_INCLUDE_TAIL, mb.data(), ev_compute)),
+             ora_swap_out_delta(ora, 1, ids.data(), off.data(), blk.data(), tok.data(), 0, KV_DELTA_INCLUDE_TAIL, ma.data()),
+             "delta after the model", chunk, step);
+        if (ma != mb) die("blocks_moved", chunk, step);
       } else if (op == 12) {  // calls that must be refused, with the same code on both sides and nothing changed
         auto same = [&](int rc_lib, int rc_ora, const char* what) {
           if ((rc_lib == KV_EHIP && mockhip::failure_fired()) || (rc_lib == KV_ENOMEM && g_new_fired)) throw Failed{rc_lib};
@@ -479,9 +528,16 @@ int main(int argc, char** argv) {
       if ((rc == KV_EHIP && mockhip::failure_fired()) || (rc == KV_ENOMEM && g_new_fired)) throw Failed{rc};
       if (rc != KV_OK) die("kv_sync", chunk, -1);
     }
+    hipStreamSynchronize(compute);
     mockhip::fail_after(0, 0);  // an armed failure that this chunk did not reach stays unused
     g_new_fail_in = 0;
-    if (std::memcmp(pool_a.data(), pool_b, pool_bytes)) die("pool bytes", chunk, -1);
+    if (std::memcmp(pool_a.data(), pool_b, pool_bytes)) {
+      size_t at = 0;
+      while (pool_a[at] == pool_b[at]) at++;
+      const int64_t l = (int64_t)at / g.ls, c = ((int64_t)at % g.ls) / g.ks, b = (((int64_t)at % g.ls) % g.ks) / g.bs;
+      std::fprintf(stderr, "first difference at byte %zu: layer %lld, %s, block %lld\n", at, (long long)l, c ? "V" : "K", (long long)b);
+      die("pool bytes", chunk, -1);
+    }
     if (std::memcmp(stag_a.data(), stag_b, stag_bytes)) die("arena bytes", chunk, -1);
     if (scales && std::memcmp(scale_a.data(), scale_b, scale_bytes)) die("scale bytes", chunk, -1);
     free_list.insert(free_list.end(), held.begin(), held.end());
@@ -520,6 +576,10 @@ int main(int argc, char** argv) {
   ora_destroy(ora);
   hipStreamDestroy(evict);
   hipStreamDestroy(load);
+  hipStreamDestroy(compute);
+  hipEventDestroy(ev_evict);
+  hipEventDestroy(ev_load);
+  hipEventDestroy(ev_compute);
   hipFree(pool_b); hipFree(scale_b);
   mode == 2 ? hipFree(stag_b) : hipHostFree(stag_b);
   if (bounce) hipFree(bounce);

@@ -120,6 +120,7 @@ RUNTIME_MUTANTS = [
      "  if (dep)\n    if (kvswap::Req* r = p->planner.find_mut(req_id)) r->in_seq = dep;\n", "  (void)dep;\n"),
     ("device_block_hazards_off", "  if (p->blk_reader.empty() || n == 0) return nullptr;", "  return nullptr;"),
     ("staging_slot_waits_off", "  if (wait_seq) {", "  if (false && wait_seq) {"),
+    ("callers_event_ignored", "  if (wait_event) HIPCHK(p, hipStreamWaitEvent(st, (hipEvent_t)wait_event, 0));", ""),
     ("newest_call_hides_the_other_stream",
      "s = std::max(s, cross_stream(p, stream, q.seq));", "s = std::max(s, q.seq);"),
 ]
