@@ -704,7 +704,7 @@ int kv_pool_tune(kv_pool* p, int32_t what, int64_t value) try {
 }
 KV_CATCH(p)
 
-int kv_last_hip_error(const kv_pool* p) { return p ? p->last_hip : 0; }
+int kv_last_hip_error(const kv_pool* p) { return p ? p->last_hip.load() : 0; }
 
 const char* kv_strerror(int code) {
   switch (code) {
