@@ -68,14 +68,35 @@ CSRC = os.path.join(ROOT, "paper_2510_02758_amd", "csrc")
 MOCK = os.path.join(HERE, "native", "mockhip")
 
 
+_COMMON = {}   # flags -> objects of everything but the library: built once per flag set
+
+
+def _common_objects(flags):
+    key = tuple(flags)
+    if key not in _COMMON:
+        import tempfile
+        d = tempfile.mkdtemp(prefix="mockhip_obj_")
+        objs = []
+        subprocess.check_call(["gcc", "-std=c99", "-c"] + flags + ["-o", os.path.join(d, "kv_oracle.o"),
+                               os.path.join(ROOT, "oracle", "kv_oracle.c")])
+        objs.append(os.path.join(d, "kv_oracle.o"))
+        for src in (os.path.join(MOCK, "mockhip.cpp"), os.path.join(HERE, "native", "runtime_on_mock_hip.cpp")):
+            obj = os.path.join(d, os.path.basename(src) + ".o")
+            subprocess.check_call([CLANGXX, "-std=c++17", "-Wall", "-pthread", "-c"] + flags +
+                                  ["-I", MOCK, "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "native"),
+                                   src, "-o", obj])
+            objs.append(obj)
+        _COMMON[key] = objs
+    return _COMMON[key]
+
+
 def _build_on_mock(out_dir, name, csrc_dir, flags):
-    obj = os.path.join(out_dir, "kv_oracle_%s.o" % name)
     exe = os.path.join(out_dir, name)
-    subprocess.check_call(["gcc", "-std=c99", "-c"] + flags + ["-o", obj, os.path.join(ROOT, "oracle", "kv_oracle.c")])
-    subprocess.check_call([CLANGXX, "-std=c++17", "-Wall", "-pthread"] + flags +
+    lib = os.path.join(out_dir, name + "_kvswap.o")
+    subprocess.check_call([CLANGXX, "-std=c++17", "-Wall", "-pthread", "-c"] + flags +
                           ["-I", MOCK, "-I", os.path.join(ROOT, "include"), "-x", "c++", os.path.join(csrc_dir, "kvswap.hip"),
-                           os.path.join(MOCK, "mockhip.cpp"), os.path.join(HERE, "native", "runtime_on_mock_hip.cpp"),
-                           "-x", "none", obj, "-o", exe])
+                           "-o", lib])
+    subprocess.check_call([CLANGXX, "-pthread"] + flags + [lib] + _common_objects(flags) + ["-o", exe])
     return exe
 
 
