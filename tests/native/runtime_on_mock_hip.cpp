@@ -104,13 +104,26 @@ int main(int argc, char** argv) {
 
   // ---- configuration of this run, all from the seed ----
   Geo g;
+  bool scales = seed % 4 == 3;
+  if (seed >= 192) {
+    // beyond the 192 fixed combinations: a geometry of its own per seed, so that the kernels' piece arithmetic
+    // (pieces per chunk, chunks per job, ragged last pieces, scale words) meets shapes nobody wrote down
+    for (;;) {
+      const int e = (int)rnd(1, 2);
+      g = {(int)rnd(1, 4), (int)rnd(1, 8), 8 * (int)rnd(1, 16), (int)rnd(1, 24), e, e == 1 ? KV_FP8_E4M3 : (rnd(0, 1) ? KV_F16 : KV_BF16),
+           0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+      const int64_t chunk = (int64_t)g.B * g.H * g.D * g.e;
+      if (chunk % 16 || chunk > 20480) continue;
+      scales = e == 1 && (g.L * g.H) % 2 == 0 && rnd(0, 2) != 0;
+      break;
+    }
+  } else
   switch (seed % 4) {
     case 0: g = {2, 2, 8, 2, 2, KV_F16, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}; break;       // 64-byte chunks: several per job
     case 1: g = {1, 4, 64, 8, 2, KV_BF16, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}; break;     // 4 KiB chunks: one piece each
     case 2: g = {2, 4, 72, 16, 2, KV_F16, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}; break;     // 9 KiB chunks: ragged pieces
     default: g = {3, 4, 32, 4, 1, KV_FP8_E4M3, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}; break; // fp8, 512-byte chunks, scales
   }
-  const bool scales = seed % 4 == 3;
   g.N = rnd(90, 140);
   g.chunk = (int64_t)g.B * g.H * g.D * g.e;
   g.block_bytes = 2 * g.L * g.chunk;
@@ -182,6 +195,10 @@ int main(int argc, char** argv) {
   if (rnd(0, 2) == 0) kv_pool_tune(kp, KV_TUNE_MAX_WGS_LINK, rnd(1, 5));
   if (rnd(0, 2) == 0) kv_pool_tune(kp, KV_TUNE_MAX_WGS_DEVICE, rnd(1, 7));
   if (mode == 1 && rnd(0, 1)) kv_pool_tune(kp, KV_TUNE_DMA_SLICE_BLOCKS, rnd(1, 3));
+  if (seed >= 192 && rnd(0, 1)) {  // loads in flight per lane: every build of the kernel
+    const int64_t u[4] = {1, 2, 4, 8};
+    if (kv_pool_tune(kp, KV_TUNE_KERNEL_VARIANT, u[rnd(0, 3)]) != KV_OK) die("tune", -1, -1);
+  }
 
   // ---- the serving history ----
   std::vector<int32_t> free_list((size_t)g.N);
@@ -588,7 +605,8 @@ int main(int argc, char** argv) {
                 (unsigned long long)seed, handled_rc);
     return 0;
   }
-  std::printf("seed %llu: %ld calls, %ld device operations, geometry %d mode %d events %d policy %d: equal to the oracle\n",
-              (unsigned long long)seed, calls, mockhip::executed_ops(), (int)(seed % 4), mode, (int)events, policy);
+  std::printf("seed %llu: %ld calls, %ld device operations, L %d H %d D %d B %d e %d%s mode %d events %d policy %d: equal to the oracle\n",
+              (unsigned long long)seed, calls, mockhip::executed_ops(), g.L, g.H, g.D, g.B, g.e, scales ? " +scales" : "", mode,
+              (int)events, policy);
   return calls > 40 ? 0 : 2;
 }

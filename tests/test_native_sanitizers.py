@@ -118,6 +118,17 @@ def test_runtime_and_kernels_on_the_stand_in_hip_runtime(mock_driver, first):
         assert "equal to the oracle" in r.stdout
 
 
+def test_kernel_arithmetic_on_geometries_nobody_wrote_down(mock_driver):
+    """Seeds from 192 on draw L, H, D, B, element size, scales and the kernel's unroll variant at random (chunks of 16
+    bytes to 20 KiB): every access of every lane of the real kernel source stays inside its buffers (AddressSanitizer)
+    and the bytes equal the oracle's."""
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    for seed in range(192, 288):
+        r = subprocess.run([mock_driver, str(seed), "4"], capture_output=True, text=True, timeout=300, env=env)
+        assert r.returncode == 0, "seed %d\n%s%s" % (seed, r.stdout[-2000:], r.stderr[-4000:])
+        assert "equal to the oracle" in r.stdout
+
+
 @pytest.mark.parametrize("what", ["hipfail", "nomem"])
 def test_a_failure_inside_a_call_leaves_a_handle_that_refuses_work_and_can_be_destroyed(mock_driver, what):
     """hipfail: some HIP call made by the library returns an error; nomem: some allocation made while a library
