@@ -8,8 +8,8 @@
 // executor picks, among the streams whose head operation may run, one according to a policy chosen by the test
 // (random, or always starving one stream), so the test decides how far the "GPU" lags behind the host and which
 // stream runs ahead.  "Device" and "pinned" memory are plain malloc blocks, so AddressSanitizer checks every
-// access the kernels make.  __syncthreads() is a no-op: lanes run to completion one after the other, so kernel
-// paths that exchange data through LDS are not emulated and the tests keep them switched off.
+// access the kernels make.  Launches that ask for dynamic LDS run the lanes of a workgroup as fibers, so that
+// __syncthreads() is a real barrier and data exchanged through LDS is emulated too (see run_grid below).
 #pragma once
 #include <cstddef>
 #include <cstdint>
@@ -45,6 +45,13 @@ long deadlocks();
 // `code` and does nothing else; n <= 0 disarms.  failure_fired() tells whether it has happened.
 void fail_after(long n, int code);
 bool failure_fired();
+// Runs `lane` once per (workgroup, lane) of the grid with threadIdx / blockIdx set.  A launch without dynamic
+// LDS runs its lanes to completion one after the other (its kernels have no barrier on that path).  A launch
+// WITH dynamic LDS runs the lanes of a workgroup as fibers: __syncthreads() parks a lane until every lane of
+// the workgroup has arrived, as on the device; a barrier that only some lanes reach aborts the program.
+void run_grid(dim3 grid, dim3 block, size_t lds_bytes, const std::function<void()>& lane);
+void barrier();
+bool fibers_available();  // false in a ThreadSanitizer build: launches with LDS must then be avoided
 }  // namespace mockhip
 
 typedef mockhip::Stream* hipStream_t;
@@ -58,7 +65,7 @@ typedef mockhip::Event* hipEvent_t;
 #define __launch_bounds__(n)
 #define __shared__
 #define __restrict__
-inline void __syncthreads() {}
+inline void __syncthreads() { mockhip::barrier(); }
 
 hipError_t hipGetLastError();
 hipError_t hipGetDevice(int* dev);
@@ -82,18 +89,9 @@ hipError_t hipEventElapsedTime(float* ms, hipEvent_t a, hipEvent_t b);
 hipError_t hipMemcpyAsync(void* dst, const void* src, size_t n, hipMemcpyKind kind, hipStream_t s);
 
 // One kernel launch = one queued operation that runs the body for every lane of every workgroup.
-#define hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, ...)                      \
-  do {                                                                                     \
-    const dim3 g_ = (grid), b_ = (block);                                                  \
-    (void)(lds_bytes);                                                                     \
-    mockhip::enqueue((stream), [=]() {                                                     \
-      mockhip::gridDim_ = {g_.x, g_.y, g_.z};                                              \
-      mockhip::blockDim_ = {b_.x, b_.y, b_.z};                                             \
-      for (unsigned bx_ = 0; bx_ < g_.x; bx_++)                                            \
-        for (unsigned tx_ = 0; tx_ < b_.x; tx_++) {                                        \
-          mockhip::blockIdx_ = {bx_, 0, 0};                                                \
-          mockhip::threadIdx_ = {tx_, 0, 0};                                               \
-          kern(__VA_ARGS__);                                                               \
-        }                                                                                  \
-    });                                                                                    \
+#define hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, ...)                                   \
+  do {                                                                                                  \
+    const dim3 g_ = (grid), b_ = (block);                                                               \
+    const size_t l_ = (size_t)(lds_bytes);                                                              \
+    mockhip::enqueue((stream), [=]() { mockhip::run_grid(g_, b_, l_, [=]() { kern(__VA_ARGS__); }); }); \
   } while (0)

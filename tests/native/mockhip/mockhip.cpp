@@ -305,3 +305,176 @@ hipError_t hipMemcpyAsync(void* dst, const void* src, size_t n, hipMemcpyKind, h
   push_fn(s, [=]() { std::memcpy(dst, src, n); });
   return hipSuccess;
 }
+
+// ---- workgroups with barriers: one fiber per lane ----
+#if defined(__has_feature)
+#if __has_feature(address_sanitizer)
+#define MOCKHIP_ASAN 1
+#include <sanitizer/common_interface_defs.h>
+#endif
+#if __has_feature(thread_sanitizer)
+#define MOCKHIP_TSAN 1
+#endif
+#endif
+
+#if defined(__x86_64__) && !defined(MOCKHIP_TSAN)
+#define MOCKHIP_FIBERS 1
+// Switch of stacks without a system call (swapcontext saves the signal mask on every switch, which makes a
+// launch of some thousand workgroups take seconds): the callee-saved registers go onto the old stack, the
+// stack pointers are exchanged, the registers of the new stack come back.
+extern "C" void mockhip_switch(void** save_sp, void* new_sp);
+asm(R"(
+  .text
+  .globl mockhip_switch
+  .type mockhip_switch,@function
+mockhip_switch:
+  pushq %rbp
+  pushq %rbx
+  pushq %r12
+  pushq %r13
+  pushq %r14
+  pushq %r15
+  movq %rsp, (%rdi)
+  movq %rsi, %rsp
+  popq %r15
+  popq %r14
+  popq %r13
+  popq %r12
+  popq %rbx
+  popq %rbp
+  ret
+  .size mockhip_switch, .-mockhip_switch
+)");
+#endif
+
+namespace mockhip {
+namespace {
+
+constexpr size_t kLaneStack = 128 << 10;
+struct Fibers {
+  std::vector<void*> sp;   // saved stack pointer of each parked lane
+  std::vector<char*> stack;
+  std::vector<int> state;  // 0 runnable, 1 parked at the barrier, 2 finished
+  void* sched_sp = nullptr;
+  const void* sched_bottom = nullptr;
+  size_t sched_size = 0;
+  int cur = -1;
+  const std::function<void()>* body = nullptr;
+  ~Fibers() {
+    for (char* p : stack) std::free(p);
+  }
+};
+Fibers fb;
+
+#ifdef MOCKHIP_FIBERS
+// The sanitizer has to be told about every change of stack, or it takes the fiber's frames for garbage.
+void leave(void** save, const void* bottom, size_t size) {
+#ifdef MOCKHIP_ASAN
+  __sanitizer_start_switch_fiber(save, bottom, size);
+#else
+  (void)save; (void)bottom; (void)size;
+#endif
+}
+void arrive(void* save, const void** old_bottom, size_t* old_size) {
+#ifdef MOCKHIP_ASAN
+  __sanitizer_finish_switch_fiber(save, old_bottom, old_size);
+#else
+  (void)save; (void)old_bottom; (void)old_size;
+#endif
+}
+
+[[noreturn]] void lane_main() {
+  arrive(nullptr, &fb.sched_bottom, &fb.sched_size);
+  (*fb.body)();
+  fb.state[(size_t)fb.cur] = 2;
+  leave(nullptr, fb.sched_bottom, fb.sched_size);  // nullptr: this fiber's frames are gone for good
+  mockhip_switch(&fb.sp[(size_t)fb.cur], fb.sched_sp);
+  std::abort();  // a finished lane is never resumed
+}
+#endif
+
+}  // namespace
+
+bool fibers_available() {
+#ifdef MOCKHIP_FIBERS
+  return true;
+#else
+  return false;
+#endif
+}
+
+void barrier() {
+#ifdef MOCKHIP_FIBERS
+  if (fb.cur < 0) return;  // a launch without LDS: lanes run one after the other and its kernels have no barrier
+  const int me = fb.cur;
+  fb.state[(size_t)me] = 1;
+  void* save = nullptr;
+  leave(&save, fb.sched_bottom, fb.sched_size);
+  mockhip_switch(&fb.sp[(size_t)me], fb.sched_sp);
+  arrive(save, nullptr, nullptr);
+#endif
+}
+
+void run_grid(dim3 g, dim3 b, size_t lds_bytes, const std::function<void()>& lane) {
+  gridDim_ = {g.x, g.y, g.z};
+  blockDim_ = {b.x, b.y, b.z};
+  if (lds_bytes == 0) {
+    for (unsigned bx = 0; bx < g.x; bx++)
+      for (unsigned tx = 0; tx < b.x; tx++) {
+        blockIdx_ = {bx, 0, 0};
+        threadIdx_ = {tx, 0, 0};
+        lane();
+      }
+    return;
+  }
+  if (!fibers_available() || lds_bytes > sizeof(lds)) {
+    std::fprintf(stderr, "mockhip: a launch with %zu bytes of LDS cannot be emulated in this build\n", lds_bytes);
+    std::abort();
+  }
+#ifdef MOCKHIP_FIBERS
+  const size_t n = b.x;
+  if (fb.stack.size() < n) {
+    fb.sp.resize(n);
+    fb.state.resize(n);
+    while (fb.stack.size() < n) fb.stack.push_back((char*)std::malloc(kLaneStack));  // reused by every later launch
+  }
+  fb.body = &lane;
+  for (unsigned bx = 0; bx < g.x; bx++) {
+    for (size_t t = 0; t < n; t++) {
+      // a fresh stack: six register slots, the entry point, and the slot a caller's return address would take
+      void** top = (void**)(((uintptr_t)fb.stack[t] + kLaneStack) & ~(uintptr_t)15);
+      top[-1] = nullptr;
+      top[-2] = (void*)&lane_main;
+      for (int i = 3; i <= 8; i++) top[-i] = nullptr;
+      fb.sp[t] = (void*)(top - 8);
+      fb.state[t] = 0;
+    }
+    for (;;) {
+      size_t done = 0, parked = 0;
+      for (size_t t = 0; t < n; t++) {
+        if (fb.state[t] != 0) continue;
+        fb.cur = (int)t;
+        threadIdx_ = {(unsigned)t, 0, 0};
+        blockIdx_ = {bx, 0, 0};
+        void* save = nullptr;
+        leave(&save, fb.stack[t], kLaneStack);
+        mockhip_switch(&fb.sched_sp, fb.sp[t]);
+        arrive(save, nullptr, nullptr);
+      }
+      fb.cur = -1;
+      for (size_t t = 0; t < n; t++) {
+        done += fb.state[t] == 2;
+        parked += fb.state[t] == 1;
+      }
+      if (done == n) break;
+      if (parked + done != n || done != 0) {
+        std::fprintf(stderr, "mockhip: a barrier was reached by %zu of %zu lanes of workgroup %u\n", parked, n, bx);
+        std::abort();
+      }
+      for (size_t t = 0; t < n; t++) fb.state[t] = 0;  // everybody has arrived: on to the next phase
+    }
+  }
+#endif
+}
+
+}  // namespace mockhip

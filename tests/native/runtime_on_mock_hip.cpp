@@ -187,7 +187,10 @@ int main(int argc, char** argv) {
   kc.flags = (mode == 0 ? KV_PATH_ZEROCOPY : mode == 1 ? KV_PATH_DMA : KV_STAGING_DEVICE) | (events ? KV_REQ_EVENTS : 0);
   kv_pool* kp = nullptr;
   if (kv_pool_create(&kc, &kp) != KV_OK) die("kv_pool_create", -1, -1);
-  if (kv_pool_tune(kp, KV_TUNE_SCALE_LDS, 1) != KV_OK) die("tune", -1, -1);  // the LDS path has barriers: not emulated
+  // Scale side band: the library's default (through LDS for the scatter only), never, or always.  A launch with
+  // LDS runs its lanes as fibers; a ThreadSanitizer build cannot do that and keeps to the path without LDS.
+  const int64_t lds_knob = mockhip::fibers_available() ? (int64_t)(seed % 3) : 1;
+  if (kv_pool_tune(kp, KV_TUNE_SCALE_LDS, lds_knob) != KV_OK) die("tune", -1, -1);
   if (events) {
     kv_pool_tune(kp, KV_TUNE_SEGMENT_BYTES, rnd(1, 3) * g.S);
     if (rnd(0, 1)) kv_pool_tune(kp, KV_TUNE_SEGMENT_MAX_BYTES, rnd(1, 4) * g.S);

@@ -16,6 +16,9 @@ import pytest
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
+# stack-use-after-return detection gives every fiber of the stand-in's workgroups a fake stack of its own (an mmap
+# each): switched off, or a launch of a thousand workgroups takes seconds
+ASAN_OPTS = "detect_leaks=1:abort_on_error=0:detect_stack_use_after_return=0"
 SAN = ["-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer", "-g", "-O1"]
 
 
@@ -32,7 +35,7 @@ def driver(tmp_path_factory):
 
 @pytest.mark.parametrize("seed", [1, 2, 3, 4, 5, 6])
 def test_planner_and_oracle_agree_under_sanitizers(driver, seed):
-    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    env = dict(os.environ, ASAN_OPTIONS=ASAN_OPTS, UBSAN_OPTIONS="print_stacktrace=1")
     r = subprocess.run([driver, str(seed), "4000"], capture_output=True, text=True, timeout=300, env=env)
     assert r.returncode == 0, r.stdout + r.stderr
     assert "calls agreed" in r.stdout
@@ -45,7 +48,7 @@ def test_scheduler_under_sanitizers(tmp_path_factory, seed):
     subprocess.check_call(["g++", "-std=c++17", "-Wall", "-Wextra"] + SAN +
                           ["-I", os.path.join(ROOT, "include"), "-o", exe, os.path.join(HERE, "native", "sched_stress.cpp"),
                            os.path.join(ROOT, "paper_2510_02758_amd", "csrc", "scheduler.cpp")])
-    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    env = dict(os.environ, ASAN_OPTIONS=ASAN_OPTS, UBSAN_OPTIONS="print_stacktrace=1")
     r = subprocess.run([exe, str(seed), "3000"], capture_output=True, text=True, timeout=300, env=env)
     assert r.returncode == 0, r.stdout + r.stderr
     assert "rounds ok" in r.stdout
@@ -111,7 +114,7 @@ def mock_driver(tmp_path_factory):
 def test_runtime_and_kernels_on_the_stand_in_hip_runtime(mock_driver, first):
     """Seeds first .. first+47 cover every geometry x padding x path x events combination under one lag policy
     (0: random progress, 48: the evict stream starved, 96: the load stream starved, 144: nothing runs until a wait)."""
-    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    env = dict(os.environ, ASAN_OPTIONS=ASAN_OPTS, UBSAN_OPTIONS="print_stacktrace=1")
     for seed in range(first, first + 48):
         r = subprocess.run([mock_driver, str(seed), "6"], capture_output=True, text=True, timeout=300, env=env)
         assert r.returncode == 0, "seed %d\n%s%s" % (seed, r.stdout[-2000:], r.stderr[-4000:])
@@ -122,7 +125,7 @@ def test_kernel_arithmetic_on_geometries_nobody_wrote_down(mock_driver):
     """Seeds from 192 on draw L, H, D, B, element size, scales and the kernel's unroll variant at random (chunks of 16
     bytes to 20 KiB): every access of every lane of the real kernel source stays inside its buffers (AddressSanitizer)
     and the bytes equal the oracle's."""
-    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    env = dict(os.environ, ASAN_OPTIONS=ASAN_OPTS, UBSAN_OPTIONS="print_stacktrace=1")
     for seed in range(192, 288):
         r = subprocess.run([mock_driver, str(seed), "4"], capture_output=True, text=True, timeout=300, env=env)
         assert r.returncode == 0, "seed %d\n%s%s" % (seed, r.stdout[-2000:], r.stderr[-4000:])
@@ -135,7 +138,7 @@ def test_a_failure_inside_a_call_leaves_a_handle_that_refuses_work_and_can_be_de
     call runs throws.  No exception leaves the C boundary, the call returns KV_EHIP / KV_ENOMEM, every later call
     that would change state returns KV_EHIP, queries still answer, kv_pool_destroy releases every event and
     buffer (LeakSanitizer); a failure the library can absorb leaves the history equal to the oracle."""
-    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    env = dict(os.environ, ASAN_OPTIONS=ASAN_OPTS, UBSAN_OPTIONS="print_stacktrace=1")
     handled = 0
     for seed in range(0, 96):
         r = subprocess.run([mock_driver, str(seed), "4", what], capture_output=True, text=True, timeout=300, env=env)
