@@ -161,15 +161,12 @@ RUNTIME_MUTANTS = [
 ]
 
 
-@pytest.mark.parametrize("name,find,repl", RUNTIME_MUTANTS, ids=[m[0] for m in RUNTIME_MUTANTS])
-def test_a_missing_ordering_rule_is_noticed(tmp_path, name, find, repl):
-    if not os.path.exists(CLANGXX):
-        pytest.skip("no host clang++ for the kernel source")
+def _mutated_sources(tmp_path, name, find, repl):
     import shutil
     src = tmp_path / "csrc"
     shutil.copytree(CSRC, src)
     hits = 0
-    for f in ("runtime.hip.inc", "kvswap.hip"):
+    for f in ("runtime.hip.inc", "kvswap.hip", "kernels.hip.inc"):
         text = open(src / f).read()
         hits += text.count(find)
         open(src / f, "w").write(text.replace(find, repl))
@@ -177,7 +174,14 @@ def test_a_missing_ordering_rule_is_noticed(tmp_path, name, find, repl):
     # planner.hpp names the public header by a relative path: keep that path valid for the copy
     text = open(src / "planner.hpp").read().replace('"../../include/kvswap.h"', '"kvswap.h"')
     open(src / "planner.hpp", "w").write(text)
-    exe = _build_on_mock(str(tmp_path), "mutant", str(src), ["-O1", "-g"])
+    return str(src)
+
+
+@pytest.mark.parametrize("name,find,repl", RUNTIME_MUTANTS, ids=[m[0] for m in RUNTIME_MUTANTS])
+def test_a_missing_ordering_rule_is_noticed(tmp_path, name, find, repl):
+    if not os.path.exists(CLANGXX):
+        pytest.skip("no host clang++ for the kernel source")
+    exe = _build_on_mock(str(tmp_path), "mutant", _mutated_sources(tmp_path, name, find, repl), ["-O1"])
     failed_at = None
     for seed in range(48, 400):
         r = subprocess.run([exe, str(seed), "6"], capture_output=True, text=True, timeout=300)
@@ -186,6 +190,31 @@ def test_a_missing_ordering_rule_is_noticed(tmp_path, name, find, repl):
             failed_at = seed
             break
     assert failed_at is not None, "no history notices the planted mistake '%s'" % name
+
+
+# The same for the kernels' arithmetic: a planted mistake in the kernel source must show as a byte difference (or
+# end the process, where it sends a store far outside every buffer).
+KERNEL_MUTANTS = [
+    ("ragged_last_piece_not_clipped", "        const int mine = left - lane0;", "        const int mine = left;"),
+    ("k_and_v_planes_swapped", "      const int64_t plane = (int64_t)(k >> 1) * a.ls + (int64_t)(k & 1) * a.ks;",
+     "      const int64_t plane = (int64_t)(k >> 1) * a.ls + (int64_t)((k & 1) ^ 1) * a.ks;"),
+    ("half_the_scale_vectors", "      const int vecs = a.scale_words >> 2;", "      const int vecs = a.scale_words >> 3;"),
+    ("staging_slot_of_the_wrong_block", "        dst = a.contig + (int64_t)(uint32_t)ds.b * a.S + (int64_t)k * a.chunk;",
+     "        dst = a.contig + (int64_t)(uint32_t)ds.a * a.S + (int64_t)k * a.chunk;"),
+]
+
+
+@pytest.mark.parametrize("name,find,repl", KERNEL_MUTANTS, ids=[m[0] for m in KERNEL_MUTANTS])
+def test_a_mistake_in_the_kernel_arithmetic_is_noticed(tmp_path, name, find, repl):
+    if not os.path.exists(CLANGXX):
+        pytest.skip("no host clang++ for the kernel source")
+    exe = _build_on_mock(str(tmp_path), "kmutant", _mutated_sources(tmp_path, name, find, repl), ["-O1"])
+    for seed in list(range(0, 48)) + list(range(192, 240)):
+        r = subprocess.run([exe, str(seed), "4"], capture_output=True, text=True, timeout=300)
+        if r.returncode != 0:   # a byte difference, or the wild access ended the process
+            assert "MISMATCH" in r.stderr or r.returncode < 0, r.stderr[-2000:]
+            return
+    raise AssertionError("no history notices the planted mistake '%s'" % name)
 
 
 # ---- the same harness under ThreadSanitizer, with a second thread that polls the handle ----
