@@ -35,8 +35,8 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM bytes per on-device launch of the default workload, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs of this script (summary and scale factors: profiles/kv_move_kernel_llama8b_burst64.md):
 # (18 602 483 + 18 601 139) KiB for the scatter, against 2 x 18 601 984 KiB algorithmic.
-MEASURED_TRAFFIC = {("configs[1]", 9083, "scatter"): (18602483 + 18601139) * 1024,
-                    ("configs[1]", 9083, "gather"): (18606384 + 18601128) * 1024}
+MEASURED_TRAFFIC = {("configs[1]", 9083, "scatter"): (18602483 + 18601109) * 1024,
+                    ("configs[1]", 9083, "gather"): (18606374 + 18601087) * 1024}
 
 
 def pct(xs, q):
