@@ -363,6 +363,13 @@ class KVPool:
         except Exception:
             pass
 
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+        return False
+
     # thin pass-throughs returning the C status codes
     def swap_out(self, req_ids, offsets, block_ids, num_tokens, wait_event=None):
         return kv_swap_out(self.h, req_ids, offsets, block_ids, num_tokens, wait_event)
