@@ -96,6 +96,9 @@ def main():
         sys.exit(2)
 
     import torch
+    if not os.path.exists(os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2510_02758_amd", "libkvswap.so")):
+        import __graft_entry__          # load what is built; build only a tree in which nothing is
+        __graft_entry__.build()
     from paper_2510_02758_amd import kvswap as kv
     from paper_2510_02758_amd import workloads as W
 

@@ -12,6 +12,13 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
+def pytest_sessionstart(session):
+    """The tests load the library that is built; only a tree in which nothing is built gets built here."""
+    if not os.path.exists(os.path.join(ROOT, "paper_2510_02758_amd", "libkvswap.so")):
+        import __graft_entry__
+        __graft_entry__.build()
+
+
 @pytest.fixture(scope="session")
 def gpu():
     import torch
