@@ -158,6 +158,8 @@ typedef struct {
   float ms_total;   /* first enqueue to last completion on the stream (HIP events) */
   float ms_kernel;  /* summed duration of the data kernels (HIP events around each launch); a call that is a
                        single launch and nothing else carries no events of its own and reports ms_total */
+  int32_t scatter_order; /* large scatter with both ends in HBM: 0 block by block, 1 plane by plane; -1 otherwise */
+  int32_t reserved;
 } kv_stats;
 
 /* Create a handle over caller-owned memory.  Validates geometry, alignment and
@@ -322,6 +324,9 @@ enum {
   KV_TUNE_DMA_SLICE_BLOCKS = 4, /* blocks per gather+copy slice on the DMA path */
   KV_TUNE_SEGMENT_BYTES = 5,    /* smallest segment under KV_REQ_EVENTS (default 32 MiB) */
   KV_TUNE_SCALE_LDS = 6,        /* scale side band: 0 default (LDS for the scatter), 1 word by word, 2 LDS both ways */
+  KV_TUNE_SCATTER_ORDER = 8,    /* scatter of 1024 blocks and more with both ends in HBM: 0 default (the handle times
+                                   both job orders on its first two such calls and keeps the faster), 1 always block
+                                   by block, 2 plane by plane over descriptors sorted by destination block, whatever the size */
   KV_TUNE_SEGMENT_MAX_BYTES = 7 /* under KV_REQ_EVENTS: also cut a segment inside a long request once it reaches this
                                    many bytes (0, the default: only at request ends).  Smaller segments let a swap-in
                                    follow closer behind an eviction whose blocks it reuses, at one launch each */

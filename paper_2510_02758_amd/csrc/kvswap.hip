@@ -698,6 +698,10 @@ int kv_pool_tune(kv_pool* p, int32_t what, int64_t value) try {
     case KV_TUNE_SEGMENT_MAX_BYTES:
       p->segment_max_bytes = value;
       return KV_OK;
+    case KV_TUNE_SCATTER_ORDER:
+      if (value > 2) return KV_EINVAL;
+      p->scatter_order = value;
+      return KV_OK;
     default:
       return KV_EINVAL;
   }

@@ -25,6 +25,7 @@ KV_TUNE_MAX_WGS_DEVICE, KV_TUNE_MAX_WGS_LINK, KV_TUNE_KERNEL_VARIANT, KV_TUNE_DM
 KV_TUNE_SEGMENT_BYTES = 5
 KV_TUNE_SCALE_LDS = 6
 KV_TUNE_SEGMENT_MAX_BYTES = 7
+KV_TUNE_SCATTER_ORDER = 8
 KV_F16, KV_BF16, KV_FP8_E4M3 = 0, 1, 2
 
 EXPORTS = ["kv_pool_create", "kv_pool_destroy", "kv_swap_out", "kv_swap_out_delta", "kv_swap_in", "kv_sync",
@@ -54,10 +55,10 @@ class kv_stats(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("op", C.c_int32), ("path", C.c_int32), ("launches", C.c_int32),
                 ("copies", C.c_int32), ("grid", C.c_int32), ("blocks", C.c_int64), ("bytes", C.c_int64),
                 ("plan_us", C.c_double), ("enqueue_us", C.c_double), ("ms_total", C.c_float),
-                ("ms_kernel", C.c_float)]
+                ("ms_kernel", C.c_float), ("scatter_order", C.c_int32), ("reserved", C.c_int32)]
 
     def as_dict(self):
-        return {k: getattr(self, k) for k, _ in self._fields_ if k != "struct_size"}
+        return {k: getattr(self, k) for k, _ in self._fields_ if k not in ("struct_size", "reserved")}
 
 
 class kv_io_stats(C.Structure):

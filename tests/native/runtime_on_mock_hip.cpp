@@ -198,6 +198,7 @@ int main(int argc, char** argv) {
   if (rnd(0, 2) == 0) kv_pool_tune(kp, KV_TUNE_MAX_WGS_LINK, rnd(1, 5));
   if (rnd(0, 2) == 0) kv_pool_tune(kp, KV_TUNE_MAX_WGS_DEVICE, rnd(1, 7));
   if (mode == 1 && rnd(0, 1)) kv_pool_tune(kp, KV_TUNE_DMA_SLICE_BLOCKS, rnd(1, 3));
+  if (mode == 2 && rnd(0, 1)) kv_pool_tune(kp, KV_TUNE_SCATTER_ORDER, 2);  // the plane-by-plane build of the scatter
   if (seed >= 192 && rnd(0, 1)) {  // loads in flight per lane: every build of the kernel
     const int64_t u[4] = {1, 2, 4, 8};
     if (kv_pool_tune(kp, KV_TUNE_KERNEL_VARIANT, u[rnd(0, 3)]) != KV_OK) die("tune", -1, -1);

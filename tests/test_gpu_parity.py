@@ -121,6 +121,47 @@ def test_every_piece_size(gpu, path, unroll):
     run_both(g, 0xBEE + unroll, "layer", path, 5, 4, 40, 3, tune=tune)
 
 
+@pytest.mark.parametrize("layout", ["layer", "padded"])
+def test_scatter_plane_by_plane(gpu, layout):
+    """The other job order of the on-device scatter (planes outside, descriptors sorted by destination block inside),
+    forced for every size: ragged 9 KiB chunks, few and many blocks, a workgroup cap that makes workgroups loop."""
+    g = W.Geometry(2, 4, 72, 16, "f16", 400)  # chunk = 16*4*72*2 = 9216 B: two full pieces and a ragged one
+    assert g.chunk == 9216
+    run_both(g, 0x9A7E, layout, "device", 12, 16, 400, 9, tune=((kv.KV_TUNE_SCATTER_ORDER, 2),))
+    run_both(g, 0x9A7F, layout, "device", 3, 16, 48, 2, tune=((kv.KV_TUNE_SCATTER_ORDER, 2), (kv.KV_TUNE_MAX_WGS_DEVICE, 5)))
+
+
+def test_scatter_order_is_chosen_by_timing(gpu):
+    """1024 blocks and more, both ends in HBM: the first such swap-in goes block by block, the second plane by plane,
+    the later ones use whichever was faster (kv_stats.scatter_order says which); every one of them is bit-exact."""
+    import torch
+    g = W.Geometry(1, 4, 64, 16, "bf16", 4096)  # 8 KiB chunks, 16 KiB blocks
+    seed, n_req = 0x0D3, 24
+    lens = W.request_lengths(seed, n_req, ("uniform", 48 * g.B, 80 * g.B))
+    off, ids, free = W.block_tables(seed, g.N, W.blocks_for(lens, g.B))
+    assert 1024 <= len(ids) <= len(free)
+    rid = np.arange(1, n_req + 1, dtype=np.uint64)
+    a = HostPool(g, seed, "layer", slots=len(ids) + 4)
+    ora = a.oracle()
+    b = HostPool(g, seed, "layer", slots=len(ids) + 4)
+    lib = GpuAdapter(b, kv.KV_STAGING_DEVICE)
+    orders = []
+    cur = ids
+    for it in range(6):
+        nxt = free[: len(ids)] if it % 2 == 0 else ids
+        assert ora.swap_out(rid, off, cur, lens) == ko.OK and lib.swap_out(rid, off, cur, lens) == kv.KV_OK
+        assert lib.kp.stats()["scatter_order"] == -1
+        assert ora.swap_in(rid, off, nxt) == ko.OK and lib.swap_in(rid, off, nxt) == kv.KV_OK
+        assert np.array_equal(a.pool, b.pool) and np.array_equal(a.staging, b.staging), "iteration %d" % it
+        orders.append(lib.kp.stats()["scatter_order"])
+        cur = nxt
+    assert orders[:2] == [0, 1] and all(o in (0, 1) for o in orders[2:]) and len(set(orders[2:])) == 1, orders
+    # a small swap-in is not of this kind
+    assert lib.swap_out(rid[:1], off[:2], cur[: off[1]], lens[:1]) == kv.KV_OK
+    assert lib.swap_in(rid[:1], off[:2], cur[: off[1]]) == kv.KV_OK and lib.kp.stats()["scatter_order"] == -1
+    lib.close()
+
+
 @pytest.mark.parametrize("path", list(PATHS))
 def test_fp8_with_scales(gpu, path):
     """fp8 values and fp32 scales travel together (BASELINE config 5 shape, scaled down):
