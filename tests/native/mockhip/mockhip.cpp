@@ -58,6 +58,7 @@ static bool injected() {
   if (fail_in <= 0 || --fail_in > 0) return false;
   fail_fired = true;
   last_error = fail_code;
+  if (std::getenv("MOCKHIP_TRACE")) std::fprintf(stderr, "mockhip: injected failure fires now\n");
   return true;
 }
 

@@ -156,6 +156,9 @@ RUNTIME_MUTANTS = [
     ("device_block_hazards_off", "  if (p->blk_reader.empty() || n == 0) return nullptr;", "  return nullptr;"),
     ("staging_slot_waits_off", "  if (wait_seq) {", "  if (false && wait_seq) {"),
     ("callers_event_ignored", "  if (wait_event) HIPCHK(p, hipStreamWaitEvent(st, (hipEvent_t)wait_event, 0));", ""),
+    ("stale_error_of_the_application_taken_for_a_failed_launch",
+     "  (void)hipGetLastError();\n  if (mode == 0)\n    launch_move<0>(u, grid, kind, st, a);",
+     "  if (mode == 0)\n    launch_move<0>(u, grid, kind, st, a);"),
     ("newest_call_hides_the_other_stream",
      "s = std::max(s, cross_stream(p, stream, q.seq));", "s = std::max(s, q.seq);"),
 ]
