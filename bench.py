@@ -35,8 +35,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM bytes per on-device launch of the default workload, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs of this script (summary and scale factors: profiles/kv_move_kernel_llama8b_burst64.md):
 # (18 602 483 + 18 601 139) KiB for the scatter, against 2 x 18 601 984 KiB algorithmic.
-MEASURED_TRAFFIC = {("configs[1]", 9083, "scatter"): (18602483 + 18601109) * 1024,
-                    ("configs[1]", 9083, "gather"): (18606374 + 18601087) * 1024}
+MEASURED_TRAFFIC = {("configs[1]", 9083, "scatter"): (18602495 + 18601208) * 1024,
+                    ("configs[1]", 9083, "scatter_plane_by_plane"): (18603478 + 18601147) * 1024,
+                    ("configs[1]", 9083, "gather"): (18606378 + 18601147) * 1024}
 
 
 def pct(xs, q):
@@ -338,7 +339,7 @@ def main():
                  "measured_peak_bidirectional_gbps": None if link_bidir is None else round(link_bidir, 2),
                  "kernel_out_ms": round(m["out_k"], 2), "kernel_in_ms": round(m["in_k"], 2),
                  "how": "one 1 GiB contiguous pinned hipMemcpyAsync per direction, in this run"},
-        "roofline_link": {"bound": "host-link", "kernel": "kv_move_kernel<0,4,1,true> (burst swap-out; the longest launch "
+        "roofline_link": {"bound": "host-link", "kernel": "kv_move_kernel<0,4,1,true,false> (burst swap-out; the longest launch "
                           "of a step, bound by the host link and not by HBM)",
                           "achieved": round(P / m["out_k"] / 1e6, 2), "peak": 64.0, "unit": "GB/s",
                           "frac": round(P / m["out_k"] / 1e6 / 64.0, 4), "launch_ms": round(m["out_k"], 2),
@@ -348,14 +349,15 @@ def main():
                                       "hipMemcpyAsync in this run"},
         "roofline": {"bound": "hbm",
                      "kernel": ("kv_move_kernel<1,1,0,true,true> (scatter plane by plane, both ends in HBM)" if plane_major
-                                else "kv_move_kernel<1,1,0,true> (scatter, both ends in HBM)"),
+                                else "kv_move_kernel<1,1,0,true,false> (scatter block by block, both ends in HBM)"),
                      "scatter_order_per_step": scatter_orders,
                      "achieved": round(scatter_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(scatter_gbs / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC.get(("configs[1]", total, "scatter")) if not args.blocks else None,
+                     "traffic": (MEASURED_TRAFFIC.get(("configs[1]", total, "scatter_plane_by_plane" if plane_major else "scatter"))
+                                 if not args.blocks else None),
                      "launch_ms": round(scatter_ms, 3), "bytes_per_launch": 2 * P,
                      "measured_copy_ceiling_gbps": None if copy_gbs is None else round(copy_gbs, 1)},
-        "roofline_gather": {"bound": "hbm", "kernel": "kv_move_kernel<0,1,0,true> (gather, both ends in HBM)",
+        "roofline_gather": {"bound": "hbm", "kernel": "kv_move_kernel<0,1,0,true,false> (gather, both ends in HBM)",
                             "achieved": round(gather_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                             "frac": round(gather_gbs / HBM_PEAK_GBS, 4),
                             "traffic": MEASURED_TRAFFIC.get(("configs[1]", total, "gather")) if not args.blocks else None,
