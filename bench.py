@@ -90,6 +90,7 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=40, help="requests the CPU oracle is timed on (0: skip)")
     ap.add_argument("--blocks", type=int, default=0, help="override the pool size (debugging on small boxes)")
     ap.add_argument("--variant", type=int, default=0, help="0: the configuration's own seed; 1, 2: further seeds")
+    ap.add_argument("--pool-last", action="store_true", help="allocate the pool after the other device buffers")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is a one-GPU library (no sharding, no collectives); run with --gpus 1",
@@ -121,13 +122,16 @@ def main():
     lens2 = ((nb + 1) * g.B).astype(np.int32)
 
     # ---- memory: PyTorch only allocates ----
-    # A server allocates its KV pool last, from what the weights leave free; here the device arena and the bounce
-    # buffer come first.  (Where the driver puts the pool decides which of two rates the on-device scatter runs at
-    # for the life of the process; a pool that is the process's first allocation lands in the slower one more often.)
-    dev_arena = torch.empty(total * g.S, dtype=torch.uint8, device=dev)
-    bounce = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
+    # Where in device memory the driver puts the pool decides how fast scattered writes into it go (the
+    # on-device kernels); --pool-last allocates it after the other device buffers, as a server does after its weights.
+    if args.pool_last:
+        dev_arena = torch.empty(total * g.S, dtype=torch.uint8, device=dev)
+        bounce = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
     pool = torch.empty(g.pool_bytes, dtype=torch.uint8, device=dev)
     W.fill_buffer_torch(wl.seed, pool, g.dtype)
+    if not args.pool_last:
+        dev_arena = torch.empty(total * g.S, dtype=torch.uint8, device=dev)
+        bounce = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
     staging = torch.empty((total + n) * g.S, dtype=torch.uint8, pin_memory=True)
     staging.view(torch.int64)[::512] = 0          # touch every page before timing
     flags = {"auto": kv.KV_PATH_AUTO, "zerocopy": kv.KV_PATH_ZEROCOPY, "dma": kv.KV_PATH_DMA}[args.path]
