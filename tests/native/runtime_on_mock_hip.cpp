@@ -23,6 +23,8 @@
 // call that changes state, still answer queries, and kv_pool_destroy must release everything (LeakSanitizer).
 //
 // usage: runtime_on_mock_hip <seed> <chunks> [poller|hipfail|nomem]
+// DRIVER_TRACE=1 in the environment prints every call with its block tables, MOCKHIP_TRACE=1 the moment an injected
+// failure fires; a mismatch in the pool names the first differing layer, K or V, and block.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
