@@ -59,8 +59,9 @@
  *     wait the two streams need between themselves: for staging slots (a swap-in reads slots an
  *     unfinished swap-out writes; a swap-out reuses slots an unfinished swap-in still reads) and
  *     for device blocks (a swap-in is handed blocks an unfinished swap-out or move still reads;
- *     a swap-out or move reads blocks an unfinished swap-in still writes).  Section 5.3 lets
- *     eviction and loading overlap "while maintaining memory safety": this is that guarantee.
+ *     a swap-out or move reads blocks an unfinished swap-in still writes).  Section 5.3 runs
+ *     eviction and loading at the same time and requires that no block or slot is reused before
+ *     its previous user has finished: these waits are what keeps that true here.
  *     Each segment of a transfer (the whole call without KV_REQ_EVENTS) waits only for the newest
  *     conflicting segment of the other stream, so a swap-in may be handed the blocks of a request
  *     whose eviction has just been enqueued and fills them piece by piece behind it.
@@ -337,8 +338,8 @@ int kv_last_hip_error(const kv_pool* p);
 const char* kv_strerror(int code);
 
 /* ------------------------------------------------------------ measurement helpers
- * Ceilings the swap is compared against (Section 7's bandwidth figures are quoted against the link);
- * no pool handle needed.  All three are synchronous and return the mean milliseconds per iteration, or
+ * Ceilings the swap is compared against (the paper prints no bandwidth figure; Section 5.2 only asks that
+ * writes use the link fully, so the link's own measured rate is the yardstick); no pool handle needed.  All three are synchronous and return the mean milliseconds per iteration, or
  * a negative number for bad arguments (-1), a failed HIP resource (-2) or a failed wait (-3).
  *   kv_bench_copy        contiguous device-to-device copy kernel of `bytes` (multiple of 16 KiB) on `stream`:
  *                        the HBM copy ceiling.  grid 0: one workgroup per 4 KiB piece (the launch shape of

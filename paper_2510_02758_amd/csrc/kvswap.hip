@@ -195,8 +195,15 @@ static int swap_out_common(kv_pool* p, int op, Plan& plan, double t0, void* wait
     return KV_OK;
   }
   // slots this call writes may still be read by an unfinished swap-in
-  const uint64_t dep = std::max(cross_stream(p, kEvict, plan.wait_in_seq), pending_user(p, kEvict, plan.fresh));
+  const uint64_t fresh_dep = pending_user(p, kEvict, plan.fresh);
+  const uint64_t dep = std::max(cross_stream(p, kEvict, plan.wait_in_seq), fresh_dep);
   if (plan.desc.empty() && !wait_event) {  // nothing to enqueue
+    // The call may still have taken slots (a new request below one block, a request that grew into a new partial
+    // block).  Nothing is written to them now, so no stream waits here; the requests remember the reader instead,
+    // and their next write-through waits for it, as after kv_req_reserve.
+    if (fresh_dep)
+      for (uint64_t id : plan.fresh_ids)
+        if (kvswap::Req* r = p->planner.find_mut(id)) r->in_seq = std::max(r->in_seq, fresh_dep);
     p->plan_stats = kv_stats{};
     fill_plan_stats(p, &p->plan_stats, op, 0, t1 - t0);
     p->last_instant = true;

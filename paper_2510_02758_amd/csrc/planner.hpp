@@ -95,6 +95,7 @@ struct Req {
 struct Plan {
   std::vector<Desc> desc;                           // (phys, staging slot) in launch order
   std::vector<std::pair<int64_t, int64_t>> fresh;   // slot runs newly taken from the arena
+  std::vector<uint64_t> fresh_ids;                  // the request each of those runs went to
   std::vector<std::pair<int64_t, int64_t>> freed;   // slot runs given back (swap-in without keep)
   std::vector<uint64_t> touched;                    // request ids whose slots the call reads/writes
   std::vector<std::pair<uint64_t, size_t>> req_end; // (request id, end of its descriptors in `desc`), call order
@@ -155,7 +156,7 @@ class Planner {
       if (len < 0 || row != (len + B_ - 1) / B_) { rc = KV_EINVAL; break; }
       Req* r = touch(ids[i]);
       if (r->swapped) { rc = KV_EEXIST; break; }
-      rc = ensure_cap(r, row, out);
+      rc = ensure_cap(ids[i], r, row, out);
       if (rc) break;
       for (int64_t j = 0; j < row; j++) out->desc.push_back({blk[off[i] + j], (int32_t)(r->base + j)});
       if (row) out->req_end.push_back({ids[i], out->desc.size()});
@@ -188,7 +189,7 @@ class Planner {
       Req* r = touch(ids[i]);
       if (r->swapped) { rc = KV_EEXIST; break; }
       if (len < (int64_t)r->wm * B_) { rc = KV_ESTATE; break; }
-      rc = ensure_cap(r, row, out);
+      rc = ensure_cap(ids[i], r, row, out);
       if (rc) break;
       const int64_t full = len / B_;
       const int64_t hi = (flags & KV_DELTA_INCLUDE_TAIL) ? (len + B_ - 1) / B_ : full;
@@ -322,7 +323,7 @@ class Planner {
     undo_.push_back({id, true, it->second});
     return &it->second;
   }
-  int ensure_cap(Req* r, int64_t need, Plan* out) {
+  int ensure_cap(uint64_t id, Req* r, int64_t need, Plan* out) {
     if (need <= r->cap) return KV_OK;
     if (r->cap == 0) {
       int64_t at = alloc_.alloc(need);
@@ -334,6 +335,7 @@ class Planner {
       if (!alloc_.take(r->base + r->cap, need - r->cap)) return KV_ENOSPC;
       out->fresh.push_back({r->base + r->cap, need - r->cap});
     }
+    out->fresh_ids.push_back(id);
     r->cap = (int32_t)need;
     return KV_OK;
   }

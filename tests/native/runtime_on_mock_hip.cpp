@@ -302,6 +302,51 @@ int main(int argc, char** argv) {
         give_up(r);
         state[(size_t)r] = 2;
       };
+      // Before that, twice: a write-through call that takes slots and moves nothing.  Request 4 is swapped out and resumed
+      // without keeping its image, so the load stream still reads its old slots.  (a) Request 5, unknown so far, is written
+      // through below one block: it gets the extent request 4 gave up and nothing is enqueued.  (b) Request 6 sits in the
+      // slot before another such extent and grows into a new partial block: its extent grows over it in place, again with
+      // nothing to enqueue.  The next delta of either completes the block and writes the slot: it must wait for the swap-in.
+      if (g.B >= 2) {
+        std::vector<int32_t> ma(1), mb(1);
+        auto delta_of = [&](int r, int blocks, int32_t tokens, const char* what) {
+          while ((int)table[(size_t)r].size() < blocks) { table[(size_t)r].push_back(free_list.back()); free_list.pop_back(); }
+          length[(size_t)r] = tokens;
+          csr({r}, ids, off, blk, tok);
+          both(LIB(kv_swap_out_delta(kp, 1, ids.data(), off.data(), blk.data(), tok.data(), 0, 0, mb.data(), nullptr)),
+               ora_swap_out_delta(ora, 1, ids.data(), off.data(), blk.data(), tok.data(), 0, 0, ma.data()), what, 0, -1);
+          if (ma != mb) die("blocks_moved", 0, -1);
+        };
+        auto out_and_back = [&](int r, int n) {  // afterwards the load stream reads the n slots the request has just given up
+          fill(r, n);
+          cold_out(r);
+          for (int j = 0; j < n; j++) { table[(size_t)r].push_back(free_list.back()); free_list.pop_back(); }
+          csr({r}, ids, off, blk, tok);
+          both(LIB(kv_swap_in(kp, 1, ids.data(), off.data(), blk.data(), 0, nullptr)), ora_swap_in(ora, 1, ids.data(), off.data(), blk.data(), 0),
+               "opening swap_in", 0, -1);
+          held.insert(held.end(), table[(size_t)r].begin(), table[(size_t)r].end());
+          table[(size_t)r].clear();
+          length[(size_t)r] = 0; state[(size_t)r] = 0;
+        };
+        auto finish = [&](int r) {
+          give_up(r);
+          length[(size_t)r] = 0; state[(size_t)r] = 0;
+          both(LIB(kv_req_release(kp, (uint64_t)r)), ora_req_release(ora, (uint64_t)r), "opening release", 0, -1);
+        };
+        // (a)
+        out_and_back(4, 2);                                           // slots 0..1
+        delta_of(5, 1, 1, "delta below one block");                   // takes slot 0, moves nothing
+        if (mb[0] != 0) die("a delta below one block moved something", 0, -1);
+        delta_of(5, 1, (int32_t)g.B, "delta that completes the block");  // writes slot 0
+        finish(5);
+        // (b)
+        delta_of(6, 1, (int32_t)g.B, "delta of one full block");      // slot 0
+        out_and_back(4, 2);                                           // slots 1..2
+        delta_of(6, 2, (int32_t)g.B + 1, "growth into a partial block");  // the extent grows over slot 1, nothing moves
+        if (mb[0] != 0) die("growth into a partial block moved something", 0, -1);
+        delta_of(6, 2, 2 * (int32_t)g.B, "delta that completes the second block");  // writes slot 1
+        finish(6);
+      }
       fill(1, 4);
       fill(2, 3);
       cold_out(1);
@@ -309,7 +354,7 @@ int main(int argc, char** argv) {
       csr({1}, ids, off, blk, tok);
       both(LIB(kv_swap_in(kp, 1, ids.data(), off.data(), blk.data(), 0, nullptr)), ora_swap_in(ora, 1, ids.data(), off.data(), blk.data(), 0),
            "opening swap_in", 0, -1);
-      held = table[1];  // kept out of circulation until the chunk's comparison: what the swap-in wrote must still be there
+      held.insert(held.end(), table[1].begin(), table[1].end());  // kept out of circulation until the chunk's comparison: what the swap-in wrote must still be there
       table[1].clear();
       length[1] = 0; state[1] = 0;
       cold_out(2);

@@ -161,6 +161,8 @@ RUNTIME_MUTANTS = [
      "  if (mode == 0)\n    launch_move<0>(u, grid, kind, st, a);"),
     ("newest_call_hides_the_other_stream",
      "s = std::max(s, cross_stream(p, stream, q.seq));", "s = std::max(s, q.seq);"),
+    ("write_through_that_moves_nothing_forgets_the_pending_reader",
+     "        if (kvswap::Req* r = p->planner.find_mut(id)) r->in_seq = std::max(r->in_seq, fresh_dep);", "        (void)id;"),
 ]
 
 
