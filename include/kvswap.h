@@ -102,7 +102,8 @@ enum {
   KV_ENOSPC = -6, /* staging arena cannot hold the extent (or cannot grow it in place) */
   KV_EHIP = -7,   /* a HIP runtime call failed; kv_last_hip_error() returns its code */
   KV_ESTATE = -8, /* token count below the watermark (a request never shrinks) */
-  KV_ENOMEM = -9  /* host memory for the library's own bookkeeping could not be allocated */
+  KV_ENOMEM = -9, /* host memory for the library's own bookkeeping could not be allocated */
+  KV_E2BIG = -10  /* kv_move_blocks_noalloc: more than KV_NOALLOC_MAX_BLOCKS blocks in one call */
 };
 
 /* kv_pool_config.flags */
@@ -219,6 +220,26 @@ int kv_sync(kv_pool* p);
  * pool-to-pool form of the gather/scatter whose both ends are in HBM. */
 int kv_move_blocks(kv_pool* p, int64_t n, const int32_t* src_ids, const int32_t* dst_ids,
                    void* wait_event);
+
+/* kv_move_blocks for callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, same result in the pool, same kernel.  The call makes no hipMalloc,
+ * hipFree, hipHostMalloc, event or stream creation and no host-heap allocation: its descriptors travel through a
+ * pinned buffer the handle owns since kv_pool_create into a fixed device array that is part of the library's code
+ * object (KV_NOALLOC_MAX_BLOCKS descriptors of 8 bytes = 512 KiB per GPU, held until the process ends).
+ *   - n > KV_NOALLOC_MAX_BLOCKS returns KV_E2BIG and does nothing; split the list.
+ *   - Runs on the evict stream after everything enqueued on either stream of this handle before it; load-stream
+ *     calls made while it is unfinished wait for it as a whole (it keeps no per-block marks).
+ *   - All calls on one GPU share that GPU's array.  Calls through one handle are ordered by its evict stream.
+ *     Calls through DIFFERENT handles on the same GPU that overlap in time race for the array: the caller must
+ *     order them (kv_sync, events).  The array keeps the last call's descriptors; each call overwrites the part
+ *     it reads, nothing has to start at zero.
+ *   - The host may wait inside the call for the descriptor upload of the call before the previous one (two
+ *     pinned buffers take turns), never for a kernel.
+ *   - kv_last_stats afterwards reports blocks, bytes, grid and host times, no stream times (no events are taken).
+ * Errors: KV_EINVAL, KV_ERANGE, KV_EDUP as kv_move_blocks; KV_E2BIG; KV_EHIP. */
+#define KV_NOALLOC_MAX_BLOCKS 65536
+int kv_move_blocks_noalloc(kv_pool* p, int64_t n, const int32_t* src_ids, const int32_t* dst_ids,
+                           void* wait_event);
 
 /* ---- helpers (bookkeeping, statistics, tuning) ---- */
 

@@ -20,6 +20,56 @@
 #define KV_CATCH(p) \
   catch (...) { return on_exception(p); }
 
+// ---- the fixed descriptor array of kv_move_blocks_noalloc ----
+// One array per GPU the library runs on, part of the loaded code object until the process ends
+// (KV_NOALLOC_MAX_BLOCKS descriptors of 8 bytes = 512 KiB).  In host code the name `scratch` is only a stand-in
+// for the symbol: the address the kernels and copies use is looked up once per device, with that device current,
+// and kept in kScratchOn[device]; each GPU holds its own copy at its own address.
+static __device__ __align__(256) kvswap::Desc scratch[KV_NOALLOC_MAX_BLOCKS];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+Desc* kScratchOn[kMaxDevices] = {};
+
+// Address of `scratch` on the current device (looked up on first use); *dev_out receives the device.
+hipError_t scratch_on_current_device(Desc** out, int* dev_out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidValue;
+  std::lock_guard<std::mutex> g(g_scratch_mu);
+  if (!kScratchOn[dev]) {
+    Desc* ptr = nullptr;
+    e = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidValue;
+    kScratchOn[dev] = ptr;
+  }
+  *out = kScratchOn[dev];
+  *dev_out = dev;
+  return hipSuccess;
+}
+}  // namespace
+
+// Everything kv_move_blocks_noalloc will need, taken once when the handle is created: the address of the
+// descriptor array on this GPU, two pinned upload buffers, four events and the duplicate bitmap.
+static int noalloc_setup(kv_pool* p) {
+  hipError_t e = scratch_on_current_device(&p->na_dev, &p->device);
+  if (e != hipSuccess) {
+    p->last_hip = (int)e;
+    return KV_EHIP;
+  }
+  for (int i = 0; i < 2; i++) {
+    HIPCHK(p, hipHostMalloc((void**)&p->na_host[i], (size_t)KV_NOALLOC_MAX_BLOCKS * sizeof(Desc), hipHostMallocDefault));
+    HIPCHK(p, hipEventCreate(&p->na_up_ev[i]));
+  }
+  HIPCHK(p, hipEventCreate(&p->na_fence_ev));
+  HIPCHK(p, hipEventCreate(&p->na_done_ev));
+  p->na_mark.assign((size_t)((p->cfg.num_blocks + 63) / 64), 0);
+  return KV_OK;
+}
+
 extern "C" {
 
 int kv_pool_create(const kv_pool_config* cfg, kv_pool** out) {
@@ -154,6 +204,7 @@ int kv_pool_create(const kv_pool_config* cfg, kv_pool** out) {
       p->blk_reader.assign((size_t)cfg->num_blocks, BlkMark{0, -1});
       p->blk_writer.assign((size_t)cfg->num_blocks, BlkMark{0, -1});
     }
+    if (!rc) rc = noalloc_setup(p);
     if (rc) {
       kv_pool_destroy(p);
       return rc;
@@ -176,6 +227,12 @@ int kv_pool_destroy(kv_pool* p) try {
     for (auto ev : p->ev_free) (void)hipEventDestroy(ev);
     if (p->ring_host) (void)hipHostFree(p->ring_host);
     if (p->ring_dev) (void)hipFree(p->ring_dev);
+    for (int i = 0; i < 2; i++) {
+      if (p->na_host[i]) (void)hipHostFree(p->na_host[i]);
+      if (p->na_up_ev[i]) (void)hipEventDestroy(p->na_up_ev[i]);
+    }
+    if (p->na_fence_ev) (void)hipEventDestroy(p->na_fence_ev);
+    if (p->na_done_ev) (void)hipEventDestroy(p->na_done_ev);
     for (int s = 0; s < 2; s++)
       if (p->own_stream[s]) (void)hipStreamDestroy(p->stream[s]);
   }
@@ -315,6 +372,78 @@ int kv_move_blocks(kv_pool* p, int64_t n, const int32_t* src_ids, const int32_t*
   rc = close_call(p, *c);
   if (rc) return rc;
   c->st.enqueue_us = now_us() - t1;
+  return KV_OK;
+}
+KV_CATCH(p)
+
+// kv_move_blocks for callers that cannot allocate.  Uses only what kv_pool_create set up: no hipMalloc, hipFree,
+// hipHostMalloc, event or stream creation, and no host heap either (the descriptors are written straight into a
+// pinned buffer of the handle, duplicates are found with the handle's bitmap).  The kernel is the one
+// kv_move_blocks launches; it reads its descriptors from the library's fixed device array instead of the
+// growable ring.
+int kv_move_blocks_noalloc(kv_pool* p, int64_t n, const int32_t* src_ids, const int32_t* dst_ids, void* wait_event) try {
+  if (!p) return KV_EINVAL;
+  KV_ENTER(p);
+  const double t0 = now_us();
+  if (n < 0) return KV_EINVAL;
+  if (n > KV_NOALLOC_MAX_BLOCKS) return KV_E2BIG;
+  if (n > 0 && (!src_ids || !dst_ids)) return KV_EINVAL;
+  const int64_t N = p->cfg.num_blocks;
+  for (int64_t i = 0; i < n; i++)
+    if (src_ids[i] < 0 || src_ids[i] >= N || dst_ids[i] < 0 || dst_ids[i] >= N) return KV_ERANGE;
+  if (p->na_mark.empty() && n > 0) p->na_mark.assign((size_t)((N + 63) / 64), 0);  // plan-only handles: first use
+  // destinations must be distinct and must not be sources: sources set their bit (twice is fine), then every
+  // destination must find its bit clear and sets it
+  bool dup = false;
+  uint64_t* mark = p->na_mark.data();
+  for (int64_t i = 0; i < n; i++) mark[src_ids[i] >> 6] |= 1ull << (src_ids[i] & 63);
+  for (int64_t i = 0; i < n; i++) {
+    uint64_t& w = mark[dst_ids[i] >> 6];
+    const uint64_t bit = 1ull << (dst_ids[i] & 63);
+    if (w & bit) dup = true;
+    w |= bit;
+  }
+  for (int64_t i = 0; i < n; i++) {  // all zero again for the next call
+    mark[src_ids[i] >> 6] = 0;
+    mark[dst_ids[i] >> 6] = 0;
+  }
+  if (dup) return KV_EDUP;
+  p->plan_stats = kv_stats{};
+  fill_plan_stats(p, &p->plan_stats, 4, (size_t)n, now_us() - t0);
+  p->plan_stats.path = KV_PATH_ZEROCOPY;
+  p->last_instant = true;  // no call record: kv_last_stats reports the plan figures
+  if (p->plan_only || (n == 0 && !wait_event)) return KV_OK;
+
+  hipStream_t st = p->stream[kEvict];
+  // after everything the load stream has been given so far (it may still write blocks this move reads, or read
+  // blocks it overwrites), and after the caller's event
+  HIPCHK(p, hipEventRecord(p->na_fence_ev, p->stream[kLoad]));
+  HIPCHK(p, hipStreamWaitEvent(st, p->na_fence_ev, 0));
+  hipEvent_t callers = (hipEvent_t)wait_event;
+  if (callers) HIPCHK(p, hipStreamWaitEvent(st, callers, 0));
+  if (n > 0) {
+    const int slot = (int)(p->na_calls++ & 1);
+    if (p->na_up_used[slot]) HIPCHK(p, hipEventSynchronize(p->na_up_ev[slot]));  // the upload of two calls ago has left this buffer
+    Desc* h = p->na_host[slot];
+    for (int64_t i = 0; i < n; i++) h[i] = {src_ids[i], dst_ids[i]};
+    // the array keeps the previous call's descriptors: [0, n) is overwritten here, in stream order behind the
+    // previous call's kernel, and nothing beyond n is read
+    HIPCHK(p, hipMemcpyAsync(p->na_dev, h, (size_t)n * sizeof(Desc), hipMemcpyHostToDevice, st));
+    HIPCHK(p, hipEventRecord(p->na_up_ev[slot], st));
+    p->na_up_used[slot] = true;
+    MoveArgs a;
+    int u = 1;
+    const int grid = build_move_args(p, 2, (size_t)n, nullptr, 0, false, &a, &u);
+    a.desc = p->na_dev;
+    (void)hipGetLastError();
+    launch_move<2>(u, grid, 0, st, a);
+    HIPCHK(p, hipGetLastError());
+    p->plan_stats.launches = 1;
+    p->plan_stats.grid = grid;
+  }
+  HIPCHK(p, hipEventRecord(p->na_done_ev, st));
+  p->na_pending = true;
+  p->plan_stats.enqueue_us = now_us() - t0 - p->plan_stats.plan_us;
   return KV_OK;
 }
 KV_CATCH(p)
@@ -729,6 +858,7 @@ const char* kv_strerror(int code) {
     case KV_EHIP: return "HIP runtime error";
     case KV_ESTATE: return "token count below the watermark";
     case KV_ENOMEM: return "out of host memory for the library's bookkeeping";
+    case KV_E2BIG: return "more blocks than the fixed descriptor array of the allocation-free entry point holds";
     default: return "unknown status";
   }
 }

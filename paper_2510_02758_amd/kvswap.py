@@ -17,7 +17,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libkvswap.so")
 
 KV_OK, KV_EINVAL, KV_ERANGE, KV_EDUP, KV_ENOENT = 0, -1, -2, -3, -4
-KV_EEXIST, KV_ENOSPC, KV_EHIP, KV_ESTATE, KV_ENOMEM = -5, -6, -7, -8, -9
+KV_EEXIST, KV_ENOSPC, KV_EHIP, KV_ESTATE, KV_ENOMEM, KV_E2BIG = -5, -6, -7, -8, -9, -10
+KV_NOALLOC_MAX_BLOCKS = 65536
 KV_PATH_AUTO, KV_PATH_DMA, KV_PATH_ZEROCOPY, KV_STAGING_DEVICE, KV_PLAN_ONLY, KV_REQ_EVENTS = 0, 1, 2, 4, 8, 16
 KV_DELTA_INCLUDE_TAIL = 1
 KV_KEEP_STAGING = 1
@@ -29,7 +30,7 @@ KV_TUNE_SCATTER_ORDER = 8
 KV_F16, KV_BF16, KV_FP8_E4M3 = 0, 1, 2
 
 EXPORTS = ["kv_pool_create", "kv_pool_destroy", "kv_swap_out", "kv_swap_out_delta", "kv_swap_in", "kv_sync",
-           "kv_move_blocks", "kv_req_reserve", "kv_req_release", "kv_req_query", "kv_last_stats",
+           "kv_move_blocks", "kv_move_blocks_noalloc", "kv_req_reserve", "kv_req_release", "kv_req_query", "kv_last_stats",
            "kv_slot_bytes", "kv_last_plan", "kv_pool_tune", "kv_last_hip_error", "kv_strerror",
            "kv_io_stats_get", "kv_budget_blocks", "kv_req_poll", "kv_req_wait", "kv_last_timeline",
            "kv_swap_out_delta_timed", "kv_bench_copy", "kv_bench_link", "kv_bench_link_bidir",
@@ -85,6 +86,7 @@ _sig = {
     "kv_swap_in": (C.c_int, [_vp, _i32, _vp, _vp, _vp, _u32, _vp]),
     "kv_sync": (C.c_int, [_vp]),
     "kv_move_blocks": (C.c_int, [_vp, _i64, _vp, _vp, _vp]),
+    "kv_move_blocks_noalloc": (C.c_int, [_vp, _i64, _vp, _vp, _vp]),
     "kv_req_reserve": (C.c_int, [_vp, _u64, _i32]),
     "kv_req_release": (C.c_int, [_vp, _u64]),
     "kv_req_query": (C.c_int, [_vp, _u64, _vp, _vp, _vp, _vp, _vp]),
@@ -222,6 +224,13 @@ def kv_move_blocks(h, src_ids, dst_ids, wait_event=None):
     if len(s) != len(d):
         return KV_EINVAL
     return _lib.kv_move_blocks(h, len(s), _p(s), _p(d), wait_event)
+
+
+def kv_move_blocks_noalloc(h, src_ids, dst_ids, wait_event=None):
+    s, d = _i32a(src_ids), _i32a(dst_ids)
+    if len(s) != len(d):
+        return KV_EINVAL
+    return _lib.kv_move_blocks_noalloc(h, len(s), _p(s), _p(d), wait_event)
 
 
 def kv_req_reserve(h, req_id, max_blocks):
@@ -400,6 +409,9 @@ class KVPool:
 
     def move_blocks(self, src_ids, dst_ids, wait_event=None):
         return kv_move_blocks(self.h, src_ids, dst_ids, wait_event)
+
+    def move_blocks_noalloc(self, src_ids, dst_ids, wait_event=None):
+        return kv_move_blocks_noalloc(self.h, src_ids, dst_ids, wait_event)
 
     def sync(self):
         return kv_sync(self.h)

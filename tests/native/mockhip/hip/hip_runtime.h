@@ -40,6 +40,9 @@ void set_policy(int policy, Stream* starved);
 void enqueue(Stream* s, std::function<void()> fn);
 long executed_ops();
 long deadlocks();
+// Calls so far that take or give back a resource on a real device: hipMalloc, hipHostMalloc, hipFree, hipHostFree,
+// event and stream creation and destruction.  An entry point that promises not to allocate leaves it unchanged.
+long resource_calls();
 // Failure injection: the n-th call from now, counted over the calls that can fail on a real device (event
 // creation, record, wait, query and synchronisation, stream synchronisation, copies, kernel launches), returns
 // `code` and does nothing else; n <= 0 disarms.  failure_fired() tells whether it has happened.
@@ -62,6 +65,9 @@ typedef mockhip::Event* hipEvent_t;
 #define gridDim mockhip::gridDim_
 #define blockDim mockhip::blockDim_
 #define __global__
+#define __device__
+#define __align__(n) __attribute__((aligned(n)))
+#define HIP_SYMBOL(x) x
 #define __launch_bounds__(n)
 #define __shared__
 #define __restrict__
@@ -87,6 +93,12 @@ hipError_t hipEventQuery(hipEvent_t e);
 hipError_t hipEventSynchronize(hipEvent_t e);
 hipError_t hipEventElapsedTime(float* ms, hipEvent_t a, hipEvent_t b);
 hipError_t hipMemcpyAsync(void* dst, const void* src, size_t n, hipMemcpyKind kind, hipStream_t s);
+// A `__device__` variable is an ordinary global here, so its "device address" is its address.
+template <class T>
+hipError_t hipGetSymbolAddress(void** ptr, const T& symbol) {
+  *ptr = (void*)&symbol;
+  return hipSuccess;
+}
 
 // One kernel launch = one queued operation that runs the body for every lane of every workgroup.
 #define hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, ...)                                   \

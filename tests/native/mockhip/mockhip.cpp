@@ -1,4 +1,5 @@
 // Implementation of the host-only HIP stand-in (see hip/hip_runtime.h in this directory).
+#include <atomic>
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
@@ -155,6 +156,9 @@ long executed_ops() {
   API_LOCK;
   return n_exec;
 }
+static std::atomic<long> n_resource{0};
+long resource_calls() { return n_resource.load(); }
+
 long deadlocks() {
   API_LOCK;
   return n_deadlock;
@@ -175,6 +179,7 @@ hipError_t hipGetDeviceProperties(hipDeviceProp_t* prop, int) { prop->multiProce
 
 static hipError_t alloc_any(void** p, size_t n, int type) {
   API_LOCK;
+  n_resource++;
   char* m = (char*)std::malloc(n ? n : 1);
   if (!m) return last_error = hipErrorOutOfMemory;
   std::memset(m, 0xCD, n);
@@ -184,6 +189,7 @@ static hipError_t alloc_any(void** p, size_t n, int type) {
 }
 static hipError_t free_any(void* p) {
   API_LOCK;
+  n_resource++;
   auto it = allocs.find((char*)p);
   if (it == allocs.end()) return last_error = hipErrorInvalidValue;
   allocs.erase(it);
@@ -222,12 +228,14 @@ hipError_t hipPointerGetAttributes(hipPointerAttribute_t* at, const void* p) {
 
 hipError_t hipStreamCreateWithFlags(hipStream_t* s, unsigned) {
   API_LOCK;
+  n_resource++;
   *s = new Stream;
   streams.push_back(*s);
   return hipSuccess;
 }
 hipError_t hipStreamDestroy(hipStream_t s) {
   API_LOCK;
+  n_resource++;
   drive([&] { return s->q.empty(); });
   for (size_t i = 0; i < streams.size(); i++)
     if (streams[i] == s) streams.erase(streams.begin() + (long)i);
@@ -254,12 +262,14 @@ hipError_t hipStreamWaitEvent(hipStream_t s, hipEvent_t e, unsigned) {
 }
 hipError_t hipEventCreate(hipEvent_t* e) {
   API_LOCK;
+  n_resource++;
   if (injected()) return fail_code;
   *e = new Event;
   return hipSuccess;
 }
 hipError_t hipEventDestroy(hipEvent_t e) {
   API_LOCK;
+  n_resource++;
   // operations that still name the event are a use after free in the program under test
   for (Stream* s : streams)
     for (Op& o : s->q)

@@ -489,6 +489,14 @@ int main(int argc, char** argv) {
         if (!k) continue;
         std::vector<int32_t> src(table[(size_t)r].begin(), table[(size_t)r].begin() + (long)k), dst;
         for (size_t j = 0; j < k; j++) { dst.push_back(free_list.back()); free_list.pop_back(); }
+        if (rnd(0, 1)) {
+          // the entry point for callers that cannot allocate: same result, and the HIP runtime is asked for no memory,
+          // event or stream while it runs (the stand-in's own queues use the host heap, so that is not counted)
+          const long res0 = mockhip::resource_calls();
+          both(LIB(kv_move_blocks_noalloc(kp, (int64_t)k, src.data(), dst.data(), after_model)),
+               ora_move_blocks(ora, (int64_t)k, src.data(), dst.data()), "move without allocation", chunk, step);
+          if (mockhip::resource_calls() != res0) die("kv_move_blocks_noalloc allocated", chunk, step);
+        } else
         both(LIB(kv_move_blocks(kp, (int64_t)k, src.data(), dst.data(), after_model)), ora_move_blocks(ora, (int64_t)k, src.data(), dst.data()),
              "move", chunk, step);
         std::copy(dst.begin(), dst.end(), table[(size_t)r].begin());
@@ -575,7 +583,14 @@ int main(int argc, char** argv) {
           }
           calls++;
         };
-        const int which = (int)rnd(0, 3);
+        const int which = (int)rnd(0, 4);
+        if (which == 4) {  // more blocks than the allocation-free move takes in one call: refused before anything is looked at
+          static std::vector<int32_t> many((size_t)KV_NOALLOC_MAX_BLOCKS + 1, 0);
+          const int rc = LIB(kv_move_blocks_noalloc(kp, (int64_t)many.size(), many.data(), many.data(), nullptr));
+          if ((rc == KV_EHIP && mockhip::failure_fired()) || (rc == KV_ENOMEM && g_new_fired)) throw Failed{rc};
+          if (rc != KV_E2BIG) die("kv_move_blocks_noalloc accepted more blocks than its array holds", chunk, step);
+          calls++;
+        }
         if (which == 0 && !out.empty() && length[(size_t)out[0]] > g.B && free_list.size() > 4) {  // one destination twice
           const int r = out[0];
           const size_t nb = (size_t)((length[(size_t)r] + g.B - 1) / g.B);
@@ -657,6 +672,7 @@ int main(int argc, char** argv) {
         kv_swap_out(kp, 1, &id, off1, blk1, tok1, nullptr) != KV_EHIP ||
         kv_swap_out_delta(kp, 1, &id, off1, blk1, tok1, 0, 0, moved1, nullptr) != KV_EHIP ||
         kv_swap_in(kp, 1, &id, off1, blk1, 0, nullptr) != KV_EHIP || kv_move_blocks(kp, 1, blk1, blk1 + 1, nullptr) != KV_EHIP ||
+        kv_move_blocks_noalloc(kp, 1, blk1, blk1 + 1, nullptr) != KV_EHIP ||
         kv_wq_post(kp, 1, &id, off1, blk1, tok1, nullptr) != KV_EHIP || kv_wq_drain(kp, 0, 4, 0, &a, &b, &c, nullptr) != KV_EHIP ||
         kv_sync(kp) != KV_EHIP || kv_pool_tune(kp, KV_TUNE_MAX_WGS_LINK, 8) != KV_EHIP)
       die("a call was accepted by a handle that had failed", -1, -1);

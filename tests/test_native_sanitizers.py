@@ -161,6 +161,10 @@ RUNTIME_MUTANTS = [
      "  if (mode == 0)\n    launch_move<0>(u, grid, kind, st, a);"),
     ("newest_call_hides_the_other_stream",
      "s = std::max(s, cross_stream(p, stream, q.seq));", "s = std::max(s, q.seq);"),
+    ("allocation_free_move_not_ordered_after_the_load_stream",
+     "  HIPCHK(p, hipStreamWaitEvent(st, p->na_fence_ev, 0));", ""),
+    ("load_stream_does_not_wait_for_an_allocation_free_move",
+     "      HIPCHK(p, hipStreamWaitEvent(st, p->na_done_ev, 0));", ""),
     ("write_through_that_moves_nothing_forgets_the_pending_reader",
      "        if (kvswap::Req* r = p->planner.find_mut(id)) r->in_seq = std::max(r->in_seq, fresh_dep);", "        (void)id;"),
 ]
