@@ -1,26 +1,32 @@
 #!/usr/bin/env python3
-"""Per-configuration figures beside bench.py (which times the Llama-3-8B burst).
+"""Per-configuration legs of the benchmark.  bench.py runs the headline configuration (the Llama-3-70B-shaped
+pool) itself and calls the functions below for the other configurations, so that one timed JSON line
+carries all of them; each can also be run alone:
 
-    python bench_configs.py --config 1|3|4|5|6|7
+    python bench_configs.py --config 1|2|3|5|6|7|8
 
-Each run prints one JSON line.  Synthetic seeded inputs (workloads.py); the same
-library entry points as everywhere else; the CPU oracle is timed next to it on a
-bounded sample, single-threaded, and (for context) once more with the sample's
-requests spread over all host cores, one oracle instance per thread.
+Each run prints one JSON line.  Synthetic seeded inputs (workloads.py); the same library entry points as
+everywhere else; the CPU oracle is timed next to it on a bounded sample, single-threaded, and (for context) once
+more with the sample's requests spread over all host cores, one independent oracle instance per thread (the
+oracle itself stays single-threaded).
 
   1  tiny fp16 pool: per-call latency floor (3 requests out, then in).
-  3  write-through: priming delta, 64 decode steps with one delta per step over 256
-     requests, then 32 requests preempted after write-through (tail flush only)
-     against the same 32 preempted cold (full swap-out), and resumed.
-  4  Llama-3-70B shape, 200 GB pool, fragmented tables, waves through a 40 GiB arena.
-  5  fp8 + fp32 scales: swap-in alone and while a read-modify-write kernel streams
-     through HBM on another stream.
-  6  load-evict overlap (paper Section 5.3) on the 8B shape: 32 requests evicted while 32
-     others are loaded, serial (sync in between) against both streams at once.
-  7  the scheduler: microseconds per kv_sched_step for 64 / 256 / 1024 requests (the paper
-     reports ~0.4 ms per scheduling call for its Python scheduler, Section 7.5), and a simulated
-     burst (Section 7.3 shape: 80 requests, long inputs and outputs) served with real KV
-     blocks on the GPU under the buffer-aware policy and under run-to-completion FCFS.
+  2  Llama-3-8B burst of 64 requests: D2H, H2D, write-through delta, on-device gather and scatter (both job
+     orders of the scatter forced in turn), isolated per-request latency.
+  3  write-through: priming delta, 64 decode steps with one delta per step over 256 requests, then 32 requests
+     preempted after write-through (tail flush only) against the same 32 preempted cold (full swap-out), and
+     resumed.
+  5  fp8 + fp32 scales: all 512 requests in waves, alone and while a read-modify-write kernel streams through
+     HBM on another stream; the workgroup budget of the zero-copy kernels under that contention.
+  6  load-evict overlap (paper Section 5.3) on the 8B shape: 32 requests evicted while 32 others are loaded,
+     serial (sync in between) against both streams at once, and loading into the very blocks under eviction.
+  7  the scheduler: microseconds per kv_sched_step for 64 / 256 / 1024 requests (the paper reports ~0.4 ms per
+     scheduling call for its Python scheduler, Section 7.5), and a simulated burst (Section 7.3 shape: 80
+     requests, long inputs and outputs) served with real KV blocks on the GPU under the buffer-aware policy and
+     under run-to-completion FCFS.
+  8  the general builds of the move kernel with both ends in HBM: the fp8 + scales shape (scale jobs, LDS
+     scatter), a one-KV-head shard of the 70B shape (4 KiB chunks) and a token-level pool (256-byte chunks,
+     several chunks per workgroup), each against the 8 TB/s peak and a scrambled plain copy of the same run length.
 """
 import argparse
 import json
@@ -35,14 +41,24 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
 
 def pct(xs, q):
     return round(float(np.percentile(np.asarray(xs, dtype=np.float64), q)), 3)
 
 
-def oracle_rates(W, g0, lens, nblocks, n_sample, seed):
-    """Oracle swap-out + swap-in of n_sample requests on a compact mirror: 1 thread, then the
-    same requests spread over all cores (one independent oracle instance per thread)."""
+def note(msg):
+    """Progress on stderr: a long run must show that it is alive."""
+    print("[bench %6.1fs] %s" % (time.perf_counter() - _T0, msg), file=sys.stderr, flush=True)
+
+
+_T0 = time.perf_counter()
+
+
+def oracle_rates(W, g0, lens, nblocks, n_sample, seed, passes=1):
+    """Oracle swap-out + swap-in of n_sample requests on a compact mirror: 1 thread, then the same requests
+    spread over all cores (one independent oracle instance per thread)."""
     from oracle import kv_oracle as ko
     nb = np.asarray(nblocks[:n_sample], dtype=np.int64)
     total = int(nb.sum())
@@ -53,25 +69,40 @@ def oracle_rates(W, g0, lens, nblocks, n_sample, seed):
     off = np.zeros(n_sample + 1, np.int64)
     off[1:] = np.cumsum(nb)
 
-    def run(rows, staging):
+    def run(rows, staging, reps):
         ora = ko.Oracle(g.L, g.H, g.D, g.B, g.e, g.N, pool, g.strides, staging, scale=scale,
                         scale_strides=g.scale_strides if g.scales else None)
         o = np.zeros(len(rows) + 1, np.int32)
         o[1:] = np.cumsum(nb[rows])
         src = np.concatenate([np.arange(off[r], off[r + 1]) for r in rows]).astype(np.int32)
         rid = np.asarray(rows, dtype=np.uint64) + 1
-        assert ora.swap_out(rid, o, src, np.asarray(lens)[rows]) == ko.OK
-        assert ora.swap_in(rid, o, src + total) == ko.OK
+        for k in range(reps):          # there and back again: the second pass moves the blocks home
+            a, b = (src, src + total) if k % 2 == 0 else (src + total, src)
+            assert ora.swap_out(rid, o, a, np.asarray(lens)[rows]) == ko.OK
+            assert ora.swap_in(rid, o, b) == ko.OK
 
     staging = np.zeros(total * g.S, np.uint8)
     t0 = time.perf_counter()
-    run(list(range(n_sample)), staging)
+    run(list(range(n_sample)), staging, passes)
     t1 = time.perf_counter() - t0
+    del staging
+    # all cores: the same blocks, cut into one run of blocks per thread (each run handed to its own oracle instance as
+    # one request of whole blocks, so the bytes moved are the same)
     cores = len(os.sched_getaffinity(0))
-    nthr = max(1, min(cores, n_sample))
-    parts = [list(range(i, n_sample, nthr)) for i in range(nthr)]
-    stagings = [np.zeros(int(nb[p].sum()) * g.S, np.uint8) for p in parts]
-    threads = [threading.Thread(target=run, args=(p, s)) for p, s in zip(parts, stagings)]
+    nthr = max(1, min(cores, total))
+    cuts = np.linspace(0, total, nthr + 1).astype(np.int64)
+
+    def run_blocks(lo, hi, staging):
+        ora = ko.Oracle(g.L, g.H, g.D, g.B, g.e, g.N, pool, g.strides, staging, scale=scale,
+                        scale_strides=g.scale_strides if g.scales else None)
+        src = np.arange(lo, hi, dtype=np.int32)
+        o = np.array([0, hi - lo], np.int32)
+        rid = np.array([1], np.uint64)
+        assert ora.swap_out(rid, o, src, np.array([(hi - lo) * g.B], np.int32)) == ko.OK
+        assert ora.swap_in(rid, o, src + total) == ko.OK
+
+    stagings = [np.zeros(int(cuts[i + 1] - cuts[i]) * g.S, np.uint8) for i in range(nthr)]
+    threads = [threading.Thread(target=run_blocks, args=(int(cuts[i]), int(cuts[i + 1]), stagings[i])) for i in range(nthr)]
     t0 = time.perf_counter()
     for t in threads:
         t.start()
@@ -79,10 +110,48 @@ def oracle_rates(W, g0, lens, nblocks, n_sample, seed):
         t.join()
     tn = time.perf_counter() - t0
     nbytes = 2 * total * g.S
-    return {"kind": "oracle", "sample": "%d requests, %d blocks, %.2f GiB each way" % (n_sample, total, total * g.S / 2**30),
-            "value": round(nbytes / t1 / 1e9, 3), "unit": "GB/s", "cores": 1,
-            "ms_per_request": round(t1 * 1e3 / n_sample, 2),
-            "all_cores_value": round(nbytes / tn / 1e9, 3), "all_cores": nthr}
+    return {"value": round(passes * nbytes / t1 / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": "%d requests of the workload (%d blocks, %.2f GiB each way), %d pass(es) of swap-out then swap-in on "
+                      "a compact host mirror: %.1f s of CPU time on one core" % (n_sample, total, total * g.S / 2**30, passes, t1),
+            "ms_per_request": round(t1 * 1e3 / (passes * n_sample), 2),
+            "all_cores_value": round(nbytes / tn / 1e9, 3), "all_cores": nthr, "host_cores": cores,
+            "all_cores_def": "the same blocks once more, cut into %d runs, one thread with its own oracle instance each "
+                             "(the oracle itself is single-threaded); %d cores are open to this process" % (nthr, cores)}
+
+
+class Streams:
+    """The three streams of a benchmark process: eviction, loading, and a co-runner.  HIP gives a process a small
+    number of hardware queues (GPU_MAX_HW_QUEUES, four by default) and lets further streams share them; two
+    streams on one queue run one after the other.  So the streams are created and used once before anything else,
+    and every pool handle of the process is given the same two: eviction and loading then sit on queues of their
+    own and can overlap (Section 5.3), whatever else the process creates later."""
+
+    def __init__(self, torch):
+        self.evict, self.load, self.side = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+        x = torch.zeros(64, device="cuda")
+        for st in (self.evict, self.load, self.side):
+            with torch.cuda.stream(st):
+                x.add_(1)
+        torch.cuda.synchronize()
+
+    def kw(self):
+        return {"evict_stream": self.evict, "load_stream": self.load}
+
+
+def pinned(torch, nbytes, arena=None):
+    """A pinned host arena of nbytes: a slice of the caller's when that is large enough."""
+    if arena is not None and arena.numel() >= nbytes:
+        return arena[:nbytes]
+    t = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+    t.view(torch.int64)[::512] = 0          # touch every page before timing
+    return t
+
+
+def release(torch):
+    import gc
+    gc.collect()
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
 
 
 def ceilings(kv, torch, staging, dev):
@@ -99,7 +168,9 @@ def ok(kv, rc, what):
         raise kv.KVSwapError(rc, what)
 
 
-def config1(kv, W, torch, dev, args):
+def config1(kv, W, torch, dev, args, arena=None, streams=None):
+    streams = streams or Streams(torch)
+    skw = streams.kw()
     wl = W.config(1, variant=args.variant)
     g = wl.geom
     lens = W.request_lengths(wl.seed, wl.n_requests, wl.length_dist)
@@ -109,8 +180,8 @@ def config1(kv, W, torch, dev, args):
     rid = (1 + victims).astype(np.uint64)
     new = free[:len(vids)]
     pool = torch.from_numpy(W.fill_buffer_np(wl.seed, g.pool_bytes, g.dtype)).to(dev)
-    staging = torch.zeros(64 * g.S, dtype=torch.uint8).pin_memory()
-    kp = kv.KVPool(g, pool, staging)
+    staging = pinned(torch, 64 * g.S, arena)
+    kp = kv.KVPool(g, pool, staging, **skw)
     outs, ins, calls = [], [], []
     for it in range(200):
         a = time.perf_counter()
@@ -126,15 +197,115 @@ def config1(kv, W, torch, dev, args):
             ins.append((c - b) * 1e6)
             calls.append((a1 - a) * 1e6)
     nbytes = len(vids) * g.S
-    return {"config": 1, "workload": "tiny fp16 L2 H4 D64 B16, 1024 blocks, 3 of 8 requests (%d blocks, %d KiB)"
+    kp.close()
+    return {"config": 1, "workload": "configs[0]: tiny fp16 L2 H4 D64 B16, 1024 blocks, 3 of 8 requests (%d blocks, %d KiB)"
             % (len(vids), nbytes >> 10),
+            "p50_preempt_ms": round(pct(outs, 50) / 1e3, 4), "p50_resume_ms": round(pct(ins, 50) / 1e3, 4),
             "preempt_call_to_sync_us": {"p50": pct(outs, 50), "p99": pct(outs, 99)},
             "resume_call_to_sync_us": {"p50": pct(ins, 50), "p99": pct(ins, 99)},
             "host_call_us_p50": pct(calls, 50),
-            "cpu_baseline": oracle_rates(W, g, lens[victims], W.blocks_for(lens[victims], g.B), len(victims), wl.seed)}
+            "note": "three requests per call; the transfer itself is ~10 us, the rest is the fixed cost of a call"}
 
 
-def config3(kv, W, torch, dev, args):
+def config2(kv, W, torch, dev, args, arena=None, streams=None, steps=3):
+    """The Llama-3-8B burst: every leg of the hot path, the on-device scatter in both job orders."""
+    streams = streams or Streams(torch)
+    skw = streams.kw()
+    wl = W.config(2, variant=args.variant)
+    g = wl.geom
+    lens = W.request_lengths(wl.seed, wl.n_requests, wl.length_dist)
+    nb = W.blocks_for(lens, g.B)
+    off, ids, free = W.block_tables(wl.seed, g.N, nb)
+    n, total = wl.n_requests, int(off[-1])
+    rid = np.arange(1, n + 1, dtype=np.uint64)
+    new = free[:total].copy()
+    extra = free[total:total + n].copy()
+    off2 = off + np.arange(n + 1, dtype=np.int32)
+    ids2 = np.concatenate([np.append(new[off[i]:off[i + 1]], extra[i]) for i in range(n)]).astype(np.int32)
+    lens2 = ((nb + 1) * g.B).astype(np.int32)
+    pool = torch.empty(g.pool_bytes, dtype=torch.uint8, device=dev)
+    W.fill_buffer_torch(wl.seed, pool, g.dtype)
+    dev_arena = torch.empty(total * g.S, dtype=torch.uint8, device=dev)
+    staging = pinned(torch, (total + n) * g.S, arena)
+    kp = kv.KVPool(g, pool, staging, **skw)
+    kd = kv.KVPool(g, pool, dev_arena, flags=kv.KV_STAGING_DEVICE, **skw)
+    link = ceilings(kv, torch, staging, dev)
+    P = total * g.S
+    acc = {k: [] for k in ("out", "in", "delta")}
+    dblocks = 0
+    for it in range(steps + 1):
+        t = [time.perf_counter()]
+        for i in range(n):
+            ok(kv, kp.reserve(rid[i], int(nb[i]) + 1), "kv_req_reserve")
+        ok(kv, kp.swap_out(rid, off, ids, lens), "kv_swap_out")
+        ok(kv, kp.sync(), "kv_sync")
+        t.append(time.perf_counter())
+        ok(kv, kp.swap_in(rid, off, new, kv.KV_KEEP_STAGING), "kv_swap_in")
+        ok(kv, kp.sync(), "kv_sync")
+        t.append(time.perf_counter())
+        rc, moved = kp.swap_out_delta(rid, off2, ids2, lens2)
+        ok(kv, rc, "kv_swap_out_delta")
+        ok(kv, kp.sync(), "kv_sync")
+        t.append(time.perf_counter())
+        dblocks = int(moved.sum())
+        for i in range(n):
+            ok(kv, kp.release(rid[i]), "kv_req_release")
+        if it:
+            acc["out"].append(t[1] - t[0])
+            acc["in"].append(t[2] - t[1])
+            acc["delta"].append(t[3] - t[2])
+    # on-device: gather, then the scatter in each job order (forced), several launches each
+    ondev = {}
+    for name, order in (("scatter_block_by_block", 1), ("scatter_plane_by_plane", 2)):
+        ok(kv, kd.tune(kv.KV_TUNE_SCATTER_ORDER, order), "kv_pool_tune")
+        gk, sk = [], []
+        for it in range(5):
+            ok(kv, kd.swap_out(rid, off, new, lens), "kv_swap_out(device arena)")
+            so = kd.stats()
+            ok(kv, kd.swap_in(rid, off, ids), "kv_swap_in(device arena)")
+            si = kd.stats()
+            ok(kv, kd.sync(), "kv_sync")
+            if it:
+                gk.append(so["ms_kernel"])
+                sk.append(si["ms_kernel"])
+        ondev["gather"] = {"launch_ms": round(float(np.mean(gk)), 3), "traffic_gbps": round(2 * P / float(np.mean(gk)) / 1e6, 1),
+                           "frac_of_hbm_peak": round(2 * P / float(np.mean(gk)) / 1e6 / HBM_PEAK_GBS, 4)}
+        ondev[name] = {"launch_ms": round(float(np.mean(sk)), 3), "traffic_gbps": round(2 * P / float(np.mean(sk)) / 1e6, 1),
+                       "frac_of_hbm_peak": round(2 * P / float(np.mean(sk)) / 1e6 / HBM_PEAK_GBS, 4)}
+    ok(kv, kd.tune(kv.KV_TUNE_SCATTER_ORDER, 0), "kv_pool_tune")
+    pre, res = [], []
+    for i in range(n):
+        o1 = np.array([0, nb[i]], dtype=np.int32)
+        a = time.perf_counter()
+        ok(kv, kp.swap_out(rid[i:i + 1], o1, ids[off[i]:off[i + 1]], lens[i:i + 1]), "kv_swap_out")
+        ok(kv, kp.sync(), "kv_sync")
+        b = time.perf_counter()
+        ok(kv, kp.swap_in(rid[i:i + 1], o1, ids[off[i]:off[i + 1]]), "kv_swap_in")
+        ok(kv, kp.sync(), "kv_sync")
+        pre.append((b - a) * 1e3)
+        res.append((time.perf_counter() - b) * 1e3)
+    m = {k: float(np.mean(v)) for k, v in acc.items()}
+    out = {"config": 2, "workload": "configs[1]: 8B shape L32 H8 D128 B16 bf16, %d-block pool, burst of %d requests (%d blocks, %.2f GiB "
+                                    "per direction)" % (g.N, n, total, P / 2**30),
+           "measured_link_gbps": {"d2h": link[0], "h2d": link[1]},
+           "d2h_gbps": round(P / m["out"] / 1e9, 2), "h2d_gbps": round(P / m["in"] / 1e9, 2),
+           "d2h_frac_of_measured_link": round(P / m["out"] / 1e9 / link[0], 3),
+           "h2d_frac_of_measured_link": round(P / m["in"] / 1e9 / link[1], 3),
+           "delta_blocks": dblocks, "delta_ms": round(m["delta"] * 1e3, 3),
+           "ondevice": ondev,
+           "p50_preempt_ms": pct(pre, 50), "p90_preempt_ms": pct(pre, 90),
+           "p50_resume_ms": pct(res, 50), "p90_resume_ms": pct(res, 90),
+           "latency_def": "isolated single-request call -> kv_sync over the 64 requests (mean %.0f MiB each)" % (P / n / 2**20)}
+    kp.close()
+    kd.close()
+    del pool, dev_arena
+    release(torch)
+    return out
+
+
+def config3(kv, W, torch, dev, args, arena=None, streams=None):
+    streams = streams or Streams(torch)
+    skw = streams.kw()
     wl = W.config(3, variant=args.variant)
     g = wl.geom
     n, steps = wl.n_requests, 64
@@ -145,9 +316,8 @@ def config3(kv, W, torch, dev, args):
     total = int(off[-1])
     pool = torch.empty(g.pool_bytes, dtype=torch.uint8, device=dev)
     W.fill_buffer_torch(wl.seed, pool, g.dtype)
-    staging = torch.empty(total * g.S, dtype=torch.uint8, pin_memory=True)
-    staging.view(torch.int64)[::512] = 0
-    kp = kv.KVPool(g, pool, staging)
+    staging = pinned(torch, total * g.S, arena)
+    kp = kv.KVPool(g, pool, staging, **skw)
     link = ceilings(kv, torch, staging, dev)
     for i in range(n):
         ok(kv, kp.reserve(rid[i], int(final_nb[i])), "kv_req_reserve")
@@ -197,14 +367,13 @@ def config3(kv, W, torch, dev, args):
     resume_ms = (time.perf_counter() - a) * 1e3
     # (b) the same 32 requests preempted cold: nothing was written through
     cold_rid = rid[victims] + 100000
-    _, nflat = np.zeros(0), new
     a = time.perf_counter()
-    ok(kv, kp.swap_out(cold_rid, vo, nflat, cur[victims]), "kv_swap_out")
+    ok(kv, kp.swap_out(cold_rid, vo, new, cur[victims]), "kv_swap_out")
     ok(kv, kp.sync(), "kv_sync")
     cold_ms = (time.perf_counter() - a) * 1e3
     vbytes = len(vflat) * g.S
     mean_blocks = float(np.mean(step_blocks))
-    res = {"config": 3, "workload": "8B shape, 256 requests log-normal (median 1k), 64 decode steps, then 32 preempted + resumed",
+    res = {"config": 3, "workload": "configs[2]: 8B shape, 256 requests log-normal (median 1k), 64 decode steps, then 32 preempted + resumed",
            "measured_link_gbps": {"d2h": link[0], "h2d": link[1]},
            "priming_delta": {"blocks": prime_blocks, "gib": round(prime_blocks * g.S / 2**30, 2),
                              "gbps": round(prime_blocks * g.S / prime_s / 1e9, 2)},
@@ -218,94 +387,90 @@ def config3(kv, W, torch, dev, args):
                                "ms_per_request": round(cold_ms / len(victims), 3),
                                "gbps": round(vbytes / cold_ms / 1e6, 2)},
            "resume_32": {"blocks": len(vflat), "ms": round(resume_ms, 3), "ms_per_request": round(resume_ms / len(victims), 3),
-                         "gbps": round(vbytes / resume_ms / 1e6, 2)}}
+                         "gbps": round(vbytes / resume_ms / 1e6, 2)},
+           "d2h_gbps": round(vbytes / cold_ms / 1e6, 2), "h2d_gbps": round(vbytes / resume_ms / 1e6, 2),
+           "p50_preempt_ms": round(warm_ms / len(victims), 4), "p50_resume_ms": round(resume_ms / len(victims), 3),
+           "latency_def": "per request inside the 32-request calls: preempt = tail flush after write-through (Section 5.1; "
+                          "cold, the same call takes preempt_32_cold), resume = full swap-in"}
     kp.close()
-    del pool, staging
-    res["cpu_baseline"] = oracle_rates(W, g, cur[victims][:12], W.blocks_for(cur[victims], g.B)[:12], 12, wl.seed)
+    del pool
+    release(torch)
     return res
 
 
-def config4(kv, W, torch, dev, args):
-    wl = W.config(4, variant=args.variant)
-    g = wl.geom
-    lens = W.request_lengths(wl.seed, wl.n_requests, wl.length_dist)
-    nb = W.blocks_for(lens, g.B)
-    pool = torch.empty(g.pool_bytes, dtype=torch.uint8, device=dev)
-    W.fill_buffer_torch(wl.seed, pool, g.dtype)
-    arena_slots = (40 << 30) // g.S      # a wave's blocks and their destinations must both fit the free half
-    staging = torch.empty(arena_slots * g.S, dtype=torch.uint8, pin_memory=True)
-    staging.view(torch.int64)[::512] = 0
-    kp = kv.KVPool(g, pool, staging)
-    link = ceilings(kv, torch, staging, dev)
-    done, waves = 0, []
-    pre, res = [], []
-    while done < wl.n_requests and len(waves) < args.max_waves:
+def waves_of(nb, slots, room_per_request=0, limit_blocks=None):
+    """Greedy split of the requests, in order, into waves whose blocks (+ room_per_request each) fit `slots`."""
+    out, done, n = [], 0, len(nb)
+    while done < n:
         k = done
-        while k < wl.n_requests and int(nb[done:k + 1].sum()) <= arena_slots:
+        while k < n and int((nb[done:k + 1] + room_per_request).sum()) <= slots and \
+                (limit_blocks is None or int(nb[done:k + 1].sum()) <= limit_blocks):
             k += 1
-        rows = np.arange(done, k)
-        off, ids, free = W.fragmented_tables(wl.seed + len(waves), g.N, nb[rows], 0.5)
-        rid = (rows + 1).astype(np.uint64)
-        new = free[:len(ids)]
-        assert len(new) == len(ids), "the free half cannot hold this wave twice"
-        a = time.perf_counter()
-        ok(kv, kp.swap_out(rid, off, ids, lens[rows]), "kv_swap_out")
-        ok(kv, kp.sync(), "kv_sync")
-        b = time.perf_counter()
-        ok(kv, kp.swap_in(rid, off, new), "kv_swap_in")
-        ok(kv, kp.sync(), "kv_sync")
-        c = time.perf_counter()
-        nbytes = len(ids) * g.S
-        waves.append({"requests": len(rows), "gib": round(nbytes / 2**30, 2), "d2h_gbps": round(nbytes / (b - a) / 1e9, 2),
-                      "h2d_gbps": round(nbytes / (c - b) / 1e9, 2)})
-        if len(waves) == 1:      # isolated per-request latency on the first wave's requests
-            for i in range(len(rows)):
-                o1 = np.array([0, nb[rows[i]]], np.int32)
-                blk = new[off[i]:off[i + 1]]
-                a = time.perf_counter()
-                ok(kv, kp.swap_out(rid[i:i + 1], o1, blk, lens[rows[i]:rows[i] + 1]), "kv_swap_out")
-                ok(kv, kp.sync(), "kv_sync")
-                b = time.perf_counter()
-                ok(kv, kp.swap_in(rid[i:i + 1], o1, blk), "kv_swap_in")
-                ok(kv, kp.sync(), "kv_sync")
-                pre.append((b - a) * 1e3)
-                res.append((time.perf_counter() - b) * 1e3)
+        if k == done:
+            raise ValueError("request %d (%d blocks) does not fit a wave of %d slots" % (done, int(nb[done]), slots))
+        out.append(np.arange(done, k))
         done = k
-    tot = sum(w["gib"] for w in waves)
-    out = {"config": 4, "workload": "70B shape L80 H8 D128 B16, 38146-block (200 GB) pool, 50% fragmented tables, 40 GiB arena",
-           "measured_link_gbps": {"d2h": link[0], "h2d": link[1]},
-           "waves_run": len(waves), "requests_run": done, "gib_each_way": round(tot, 1), "waves": waves,
-           "d2h_gbps_mean": round(float(np.mean([w["d2h_gbps"] for w in waves])), 2),
-           "h2d_gbps_mean": round(float(np.mean([w["h2d_gbps"] for w in waves])), 2),
-           "p50_preempt_ms": pct(pre, 50), "p50_resume_ms": pct(res, 50),
-           "mean_request_gib": round(float(np.mean(nb[:done])) * g.S / 2**30, 2)}
-    # on-device: one wave's blocks through an HBM arena
-    kp.close()
-    del staging
-    rows = np.arange(0, 16)
-    off, ids, free = W.fragmented_tables(wl.seed, g.N, nb[rows], 0.5)
-    arena = torch.empty(len(ids) * g.S, dtype=torch.uint8, device=dev)
-    kd = kv.KVPool(g, pool, arena, flags=kv.KV_STAGING_DEVICE)
-    rid = (rows + 1).astype(np.uint64)
-    gk, sk = [], []
-    for it in range(4):
-        ok(kv, kd.swap_out(rid, off, ids, lens[rows]), "kv_swap_out")
-        so = kd.stats()
-        ok(kv, kd.swap_in(rid, off, free[:len(ids)]), "kv_swap_in")
-        si = kd.stats()
-        ok(kv, kd.sync(), "kv_sync")
-        if it:
-            gk.append(2 * so["bytes"] / so["ms_kernel"] / 1e6)
-            sk.append(2 * si["bytes"] / si["ms_kernel"] / 1e6)
-    out["ondevice_traffic_gbps"] = {"gather": round(float(np.mean(gk)), 1), "scatter": round(float(np.mean(sk)), 1),
-                                    "frac_of_8TBps": [round(float(np.mean(gk)) / 8000, 3), round(float(np.mean(sk)) / 8000, 3)]}
-    kd.close()
-    del pool, arena
-    out["cpu_baseline"] = oracle_rates(W, g, lens, nb, 3, wl.seed)
     return out
 
 
-def config5(kv, W, torch, dev, args):
+class SideLoad:
+    """A co-runner on a stream of its own: read-modify-write passes over a 16 GiB buffer (32 GiB of HBM traffic
+    each), in groups of ten with an event after each group, so that afterwards the traffic rate of exactly the
+    groups that finished while something else ran can be read off."""
+    GROUP = 10
+
+    def __init__(self, torch, dev, side, nbytes=16 << 30):
+        self.torch = torch
+        self.noise = torch.empty(nbytes, dtype=torch.uint8, device=dev).view(torch.int32)
+        self.side = side
+        self.pass_bytes = 2 * self.noise.numel() * 4
+        self.reset()
+
+    def reset(self):
+        self.t0 = self.torch.cuda.Event(enable_timing=True)
+        self.events = []
+        self.done_at_mark = None
+
+    def feed(self, passes):
+        """Top the stream up so that `passes` passes are queued and not yet finished."""
+        done = self.finished()
+        pending = (len(self.events) - done) * self.GROUP
+        with self.torch.cuda.stream(self.side):
+            if not self.events:
+                self.t0.record(self.side)
+            while pending < passes:
+                for _ in range(self.GROUP):
+                    self.noise.add_(1)
+                ev = self.torch.cuda.Event(enable_timing=True)
+                ev.record(self.side)
+                self.events.append(ev)
+                pending += self.GROUP
+
+    def finished(self):
+        k = 0
+        while k < len(self.events) and self.events[k].query():
+            k += 1
+        return k
+
+    def mark(self):
+        """Call when the work the co-runner was measured against has just finished."""
+        self.done_at_mark = self.finished()
+
+    def rate_gbps(self):
+        """Traffic rate of the groups that had finished at mark(); waits for the stream."""
+        self.side.synchronize()
+        k = self.done_at_mark if self.done_at_mark is not None else len(self.events)
+        if k == 0:
+            return 0.0, False
+        ms = self.t0.elapsed_time(self.events[k - 1])
+        return k * self.GROUP * self.pass_bytes / ms / 1e6, k < len(self.events)
+
+
+def config5(kv, W, torch, dev, args, arena=None, streams=None, max_waves=None):
+    """fp8 + scales: all 512 requests, wave by wave, swap-out then swap-in into fresh blocks; once alone, once while a
+    read-modify-write kernel streams through 16 GiB of HBM on another stream."""
+    streams = streams or Streams(torch)
+    skw = streams.kw()
     wl = W.config(5, variant=args.variant)
     g = wl.geom
     lens = W.request_lengths(wl.seed, wl.n_requests, wl.length_dist)
@@ -314,88 +479,128 @@ def config5(kv, W, torch, dev, args):
     scale = torch.empty(g.scale_bytes, dtype=torch.uint8, device=dev)
     W.fill_buffer_torch(wl.seed, pool, g.dtype)
     W.fill_buffer_torch(wl.seed ^ 0x5CA1E, scale, "raw")
-    arena_slots = (32 << 30) // g.S
-    k = 0
-    while int(nb[:k + 1].sum()) <= arena_slots:
-        k += 1
-    rows = np.arange(k)
+    arena_bytes = min(40 << 30, arena.numel()) if arena is not None else 40 << 30
+    arena_slots = arena_bytes // g.S
+    waves = waves_of(nb, arena_slots, limit_blocks=(g.N - 64) // 2)
+    if max_waves:
+        waves = waves[:max_waves]
+    staging = pinned(torch, arena_slots * g.S, arena)
+    kp = kv.KVPool(g, pool, staging, scale=scale, **skw)
+    link = ceilings(kv, torch, staging, dev)
+    co = SideLoad(torch, dev, streams.side)
+
+    def all_waves(busy):
+        """-> (bytes, seconds out, seconds in)"""
+        tot = t_out = t_in = 0.0
+        for w, rows in enumerate(waves):
+            off, ids, free = W.block_tables(wl.seed + w, g.N, nb[rows])
+            total = int(off[-1])
+            new = free[:total]
+            rid = (rows + 1).astype(np.uint64)
+            if busy:
+                co.feed(400)           # ~5.4 ms per pass alone: more than a wave's worth stays queued
+            a = time.perf_counter()
+            ok(kv, kp.swap_out(rid, off, ids, lens[rows]), "kv_swap_out")
+            ok(kv, kp.sync(), "kv_sync")
+            b = time.perf_counter()
+            ok(kv, kp.swap_in(rid, off, new), "kv_swap_in")
+            ok(kv, kp.sync(), "kv_sync")
+            c = time.perf_counter()
+            tot += total * g.S
+            t_out += b - a
+            t_in += c - b
+        return tot, t_out, t_in
+
+    note("config 5: %d waves alone" % len(waves))
+    tot, t_out, t_in = all_waves(False)
+    torch.cuda.synchronize()
+    co.feed(40)
+    co.rate_gbps()
+    co.reset()
+    co.feed(80)
+    stream_alone, _ = co.rate_gbps()
+    note("config 5: %d waves next to the streaming kernel" % len(waves))
+    co.reset()
+    tot2, c_out, c_in = all_waves(True)
+    co.mark()
+    stream_cont, still = co.rate_gbps()
+
+    # the workgroup budget of the zero-copy kernels under the same contention, first wave only
+    rows = waves[0]
     off, ids, free = W.block_tables(wl.seed, g.N, nb[rows])
     total = int(off[-1])
     new = free[:total]
     rid = (rows + 1).astype(np.uint64)
-    staging = torch.empty(total * g.S, dtype=torch.uint8, pin_memory=True)
-    staging.view(torch.int64)[::512] = 0
-    kp = kv.KVPool(g, pool, staging, scale=scale)
-    link = ceilings(kv, torch, staging, dev)
-    noise = torch.empty(16 << 30, dtype=torch.uint8, device=dev).view(torch.int32)
-    side = torch.cuda.Stream()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     nbytes = total * g.S
 
-    def stream_kernel(iters):
-        with torch.cuda.stream(side):
-            e0.record(side)
-            for _ in range(iters):
-                noise.add_(1)          # read-modify-write over 16 GiB: 32 GiB of HBM traffic per pass
-            e1.record(side)
-
-    def swap_in_once():
+    def one_wave(p):
         a = time.perf_counter()
-        ok(kv, kp.swap_in(rid, off, new, kv.KV_KEEP_STAGING), "kv_swap_in")
-        ok(kv, kp.sync(), "kv_sync")
-        return time.perf_counter() - a
+        ok(kv, p.swap_out(rid, off, ids, lens[rows]), "kv_swap_out")
+        ok(kv, p.sync(), "kv_sync")
+        b = time.perf_counter()
+        ok(kv, p.swap_in(rid, off, new), "kv_swap_in")
+        ok(kv, p.sync(), "kv_sync")
+        return b - a, time.perf_counter() - b
 
-    ok(kv, kp.swap_out(rid, off, ids, lens[rows]), "kv_swap_out")
-    ok(kv, kp.sync(), "kv_sync")
-    t_out = kp.stats()["ms_total"]
-    swap_in_once()
-    alone = [swap_in_once() for _ in range(3)]
-    torch.cuda.synchronize()
-    stream_kernel(4)
-    torch.cuda.synchronize()
-    stream_kernel(40)
-    torch.cuda.synchronize()
-    stream_alone = 40 * 2 * noise.numel() * 4 / e0.elapsed_time(e1) / 1e6
-    iters = 200
-
-    def contended():
-        stream_kernel(iters)
-        t = [swap_in_once() for _ in range(3)]
-        still = not e1.query()
+    def contended_wave(p):
         torch.cuda.synchronize()
-        return t, iters * 2 * noise.numel() * 4 / e0.elapsed_time(e1) / 1e6, still
+        co.reset()
+        co.feed(400)
+        t = one_wave(p)
+        co.mark()
+        rate, outlasted = co.rate_gbps()
+        return t, rate, outlasted
 
-    cont, stream_cont, still_running = contended()
-    # the same through the copy engines
+    def leg(p):
+        ta = one_wave(p)
+        (tc, sgb, outl) = contended_wave(p)
+        return {"alone_gbps": [round(nbytes / ta[0] / 1e9, 2), round(nbytes / ta[1] / 1e9, 2)],
+                "contended_gbps": [round(nbytes / tc[0] / 1e9, 2), round(nbytes / tc[1] / 1e9, 2)],
+                "stream_kernel_traffic_gbps": round(sgb, 1), "stream_kernel_outlasted_the_swaps": bool(outl)}
+
+    budget = {}
+    for wgs in (16, 32, 48, 64):
+        note("config 5: zero-copy with %d workgroups" % wgs)
+        ok(kv, kp.tune(kv.KV_TUNE_MAX_WGS_LINK, wgs), "kv_pool_tune")
+        budget[str(wgs)] = leg(kp)
+    ok(kv, kp.tune(kv.KV_TUNE_MAX_WGS_LINK, 0), "kv_pool_tune")
+    kp.close()
+    # the same wave through the copy engines
+    note("config 5: copy-engine path")
     bounce = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
+    kp = kv.KVPool(g, pool, staging, scale=scale, bounce=bounce, flags=kv.KV_PATH_DMA, **skw)
+    one_wave(kp)
+    dma = leg(kp)
     kp.close()
-    kp = kv.KVPool(g, pool, staging, scale=scale, bounce=bounce, flags=kv.KV_PATH_DMA)
-    ok(kv, kp.swap_out(rid, off, ids, lens[rows]), "kv_swap_out")
-    ok(kv, kp.sync(), "kv_sync")
-    swap_in_once()
-    alone_dma = [swap_in_once() for _ in range(3)]
-    cont_dma, stream_cont_dma, still_dma = contended()
-    out = {"config": 5, "workload": "fp8 e4m3 + fp32 scales, L32 H32 D128 B32 (8 MiB + 8 KiB per block), %d-block pool; first wave: "
-                                    "%d requests, %d blocks, %.1f GiB" % (g.N, k, total, nbytes / 2**30),
+    nreq = int(sum(len(r) for r in waves))
+    out = {"config": 5, "workload": "configs[4]: fp8 e4m3 + fp32 scales, L32 H32 D128 B32 (8 MiB + 8 KiB per block), %d-block pool; "
+                                    "%d requests in %d waves through a %.0f GiB arena, %.1f GiB each way"
+                                    % (g.N, nreq, len(waves), arena_slots * g.S / 2**30, tot / 2**30),
            "measured_link_gbps": {"d2h": link[0], "h2d": link[1]},
-           "swap_out_gbps": round(nbytes / t_out / 1e6, 2),
-           "swap_in_gbps_alone": round(nbytes / float(np.mean(alone)) / 1e9, 2),
-           "swap_in_gbps_contended": round(nbytes / float(np.mean(cont)) / 1e9, 2),
-           "stream_kernel_traffic_gbps_alone": round(stream_alone, 1),
-           "stream_kernel_traffic_gbps_while_swapping": round(stream_cont, 1),
-           "stream_kernel_outlasted_the_swaps": bool(still_running),
-           "dma_path": {"swap_in_gbps_alone": round(nbytes / float(np.mean(alone_dma)) / 1e9, 2),
-                        "swap_in_gbps_contended": round(nbytes / float(np.mean(cont_dma)) / 1e9, 2),
-                        "stream_kernel_traffic_gbps_while_swapping": round(stream_cont_dma, 1),
-                        "stream_kernel_outlasted_the_swaps": bool(still_dma)},
-           "note": "the contended streaming figures average a 200-pass run of which the three swap-ins cover most"}
-    kp.close()
-    del pool, staging, noise
-    out["cpu_baseline"] = oracle_rates(W, g, lens, nb, 4, wl.seed)
+           "requests": nreq, "waves": len(waves),
+           "d2h_gbps": round(tot / t_out / 1e9, 2), "h2d_gbps": round(tot / t_in / 1e9, 2),
+           "d2h_frac_of_measured_link": round(tot / t_out / 1e9 / link[0], 3),
+           "h2d_frac_of_measured_link": round(tot / t_in / 1e9 / link[1], 3),
+           "p50_preempt_ms": round(t_out * 1e3 / nreq, 2), "p50_resume_ms": round(t_in * 1e3 / nreq, 2),
+           "latency_def": "mean per request inside the wave calls (%.2f GiB mean request)" % (tot / nreq / 2**30),
+           "contended": {"d2h_gbps": round(tot2 / c_out / 1e9, 2), "h2d_gbps": round(tot2 / c_in / 1e9, 2),
+                         "stream_kernel_traffic_gbps_alone": round(stream_alone, 1),
+                         "stream_kernel_traffic_gbps_while_swapping": round(stream_cont, 1),
+                         "stream_kernel_outlasted_the_swaps": bool(still),
+                         "def": "all waves again while a read-modify-write kernel streams through 16 GiB on a third stream; its "
+                                "rate is taken over the passes that finished before the last wave did"},
+           "zero_copy_workgroup_budget_first_wave": budget,
+           "dma_path_first_wave": dma,
+           "budget_def": "[swap-out, swap-in] GB/s of the first wave (%.1f GiB) with KV_TUNE_MAX_WGS_LINK workgroups, alone and "
+                         "next to the streaming kernel" % (nbytes / 2**30)}
+    del pool, scale, co, bounce
+    release(torch)
     return out
 
 
-def config6(kv, W, torch, dev, args):
+def config6(kv, W, torch, dev, args, arena=None, streams=None):
+    streams = streams or Streams(torch)
+    skw = streams.kw()
     wl = W.config(2, variant=args.variant)
     g = wl.geom
     lens = W.request_lengths(wl.seed, wl.n_requests, wl.length_dist)
@@ -406,8 +611,7 @@ def config6(kv, W, torch, dev, args):
     ob, ib = W.csr_take(off, ids, B)
     rid = np.arange(1, 65, dtype=np.uint64)
     pool = torch.empty(g.pool_bytes, dtype=torch.uint8, device=dev)
-    staging = torch.empty(int(off[-1]) * g.S, dtype=torch.uint8, pin_memory=True)
-    staging.view(torch.int64)[::512] = 0
+    staging = pinned(torch, int(off[-1]) * g.S, arena)
     bounce = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
     link = ceilings(kv, torch, staging, dev)
     one = 1 << 30
@@ -418,7 +622,7 @@ def config6(kv, W, torch, dev, args):
            % (bytes_a / 2**30, bytes_b / 2**30),
            "measured_link_gbps": {"d2h": link[0], "h2d": link[1], "both_at_once": round(2 * one / ms / 1e6, 2) if ms > 0 else None}}
     for name, flags, bb in (("zerocopy", kv.KV_PATH_ZEROCOPY, None), ("dma", kv.KV_PATH_DMA, bounce)):
-        kp = kv.KVPool(g, pool, staging, bounce=bb, flags=flags)
+        kp = kv.KVPool(g, pool, staging, bounce=bb, flags=flags, **skw)
         serial, both = [], []
         for it in range(3):
             # state: A resident, B swapped out
@@ -448,19 +652,21 @@ def config6(kv, W, torch, dev, args):
         kp.close()
 
     # Section 5.3, second half: the requests being loaded are handed the very blocks of the requests being
-    # evicted.  Call-granular ordering makes the load wait for the whole eviction; with segments cut every
-    # 64 MiB each piece of the load waits only for the piece of the eviction that frees its blocks.
+    # evicted.  Call-granular ordering makes the load wait for the whole eviction; with segments each piece of
+    # the load waits only for the piece of the eviction that frees its blocks.
     nb_b = len(ib)
     dst_b = np.concatenate([ia, free])[:nb_b].astype(np.int32)            # A's blocks, in A's own order
     reuse = {}
     ev = kv.KV_REQ_EVENTS
-    for name, flags, bb, seg in (("zerocopy_call_granular", kv.KV_PATH_ZEROCOPY, None, 0),
-                                 ("zerocopy_segments_64MiB", kv.KV_PATH_ZEROCOPY | ev, None, 64 << 20),
-                                 ("dma_call_granular", kv.KV_PATH_DMA, bounce, 0),
-                                 ("dma_segments_64MiB", kv.KV_PATH_DMA | ev, bounce, 64 << 20),
-                                 ("dma_segments_256MiB", kv.KV_PATH_DMA | ev, bounce, 256 << 20)):
-        kp = kv.KVPool(g, pool, staging, bounce=bb, flags=flags)
-        if seg:
+    variants = [("zerocopy_call_granular", kv.KV_PATH_ZEROCOPY, None, 0),
+                ("zerocopy_segments_64MiB", kv.KV_PATH_ZEROCOPY | ev, None, 64 << 20),
+                ("dma_call_granular", kv.KV_PATH_DMA, bounce, 0),
+                ("dma_segments_256MiB", kv.KV_PATH_DMA | ev, bounce, 256 << 20)]
+    if hasattr(kv, "kv_evict_and_load"):
+        variants.append(("zerocopy_in_phase", kv.KV_PATH_ZEROCOPY, None, -1))
+    for name, flags, bb, seg in variants:
+        kp = kv.KVPool(g, pool, staging, bounce=bb, flags=flags, **skw)
+        if seg > 0:
             ok(kv, kp.tune(kv.KV_TUNE_SEGMENT_BYTES, seg), "kv_pool_tune")
             ok(kv, kp.tune(kv.KV_TUNE_SEGMENT_MAX_BYTES, seg), "kv_pool_tune")
         ok(kv, kp.swap_out(rid[B], ob, ib, lens[B]), "kv_swap_out")
@@ -468,8 +674,11 @@ def config6(kv, W, torch, dev, args):
         ts = []
         for it in range(4):
             a = time.perf_counter()
-            ok(kv, kp.swap_out(rid[A], oa, ia, lens[A]), "kv_swap_out")
-            ok(kv, kp.swap_in(rid[B], ob, dst_b), "kv_swap_in")            # no sync: the library orders the blocks
+            if seg < 0:
+                ok(kv, kp.evict_and_load(rid[A], oa, ia, lens[A], rid[B], ob, dst_b), "kv_evict_and_load")
+            else:
+                ok(kv, kp.swap_out(rid[A], oa, ia, lens[A]), "kv_swap_out")
+                ok(kv, kp.swap_in(rid[B], ob, dst_b), "kv_swap_in")            # no sync: the library orders the blocks
             ok(kv, kp.sync(), "kv_sync")
             ts.append(time.perf_counter() - a)
             ok(kv, kp.swap_out(rid[B], ob, dst_b, lens[B]), "kv_swap_out")  # back to the starting state
@@ -480,10 +689,14 @@ def config6(kv, W, torch, dev, args):
         reuse[name] = {"ms": round(t * 1e3, 1), "aggregate_gbps": round((bytes_a + bytes_b) / t / 1e9, 2)}
         kp.close()
     res["load_into_blocks_being_evicted"] = reuse
+    del pool, bounce
+    release(torch)
     return res
 
 
-def config7(kv, W, torch, dev, args):
+def config7(kv, W, torch, dev, args, arena=None, streams=None):
+    streams = streams or Streams(torch)
+    skw = streams.kw()
     from paper_2510_02758_amd import kvsched as ks
     from paper_2510_02758_amd import sim as S
     rng = np.random.default_rng(7)
@@ -516,7 +729,7 @@ def config7(kv, W, torch, dev, args):
     res = {"config": 7, "sched_step_us": calls,
            "paper_context": "Section 7.5 reports ~0.4 ms per scheduling call for the Python implementation"}
     pool = torch.empty(g.pool_bytes, dtype=torch.uint8, device=dev)
-    staging = torch.empty(16000 * g.S, dtype=torch.uint8, pin_memory=True)
+    staging = pinned(torch, 16000 * g.S, arena)
     for policy in ("tokenflow", "fcfs"):
         cfg = S.SimConfig(geom=g, gpu_blocks=g.N, arena_blocks=16000, max_running=24, interval=1.0, policy=policy,
                           step_base=0.020, step_per_req=0.0004, prefill_per_token=2e-5)
@@ -538,10 +751,72 @@ def config7(kv, W, torch, dev, args):
     return res
 
 
+def config8(kv, W, torch, dev, args, arena=None, streams=None):
+    """The general builds of the move kernel with both ends in HBM (device arena): gather and scatter of one
+    batch of random blocks, HIP events around each kernel, against the 8 TB/s peak and against a plain copy of
+    the same size whose source / destination is visited in scrambled runs of the pool's chunk length."""
+    streams = streams or Streams(torch)
+    skw = streams.kw()
+    shapes = [
+        ("fp8_scales", "configs[4] shape: fp8 + fp32 scales, L32 H32 D128 B32 (128 KiB chunks, 128-byte scale pieces): the build with "
+                       "scale jobs, scatter of the side band through LDS", W.Geometry(32, 32, 128, 32, "fp8_e4m3", 6144, scales=True), 2048),
+        ("one_kv_head_4KiB_chunks", "a tensor-parallel shard of the 70B shape: bf16 L80 H1 D128 B16 (4 KiB chunks, one piece each)",
+         W.Geometry(80, 1, 128, 16, "bf16", 98304), 24576),
+        ("token_level_256B_chunks", "a token-level pool: bf16 L32 H1 D128 B1 (256-byte chunks, 16 chunks per workgroup pass)",
+         W.Geometry(32, 1, 128, 1, "bf16", 1 << 20), 1 << 18),
+    ]
+    out = {"config": 8, "peak_gbps": HBM_PEAK_GBS, "kernels": {}}
+    warm = torch.empty(8 << 30, dtype=torch.uint8, device=dev)
+    kv.kv_bench_copy(warm[4 << 30:].data_ptr(), warm.data_ptr(), 4 << 30, 0, 40)     # memory clocks up
+    for name, what, g, nblk in shapes:
+        pool = torch.empty(g.pool_bytes, dtype=torch.uint8, device=dev)
+        scale = torch.empty(g.scale_bytes, dtype=torch.uint8, device=dev) if g.scales else None
+        W.fill_buffer_torch(0x5EED0800, pool, g.dtype)
+        if g.scales:
+            W.fill_buffer_torch(0x5EED0801, scale, "raw")
+        arena_d = torch.empty(nblk * g.S, dtype=torch.uint8, device=dev)
+        off, ids, free = W.block_tables(0x5EED0800, g.N, [nblk])
+        new = free[:nblk]
+        rid = np.array([1], np.uint64)
+        lens = np.array([nblk * g.B], np.int32)
+        kd = kv.KVPool(g, pool, arena_d, scale=scale, flags=kv.KV_STAGING_DEVICE, **skw)
+        gk, sk = [], []
+        for it in range(6):
+            ok(kv, kd.swap_out(rid, off, ids, lens), "kv_swap_out(device arena)")
+            so = kd.stats()
+            ok(kv, kd.swap_in(rid, off, new), "kv_swap_in(device arena)")
+            si = kd.stats()
+            ok(kv, kd.sync(), "kv_sync")
+            if it:
+                gk.append(so["ms_kernel"])
+                sk.append(si["ms_kernel"])
+        P = nblk * g.S
+        # scrambled plain copy over the largest power-of-two part of the same buffers
+        run = max(4096, g.chunk)
+        nbytes = 1 << int(np.floor(np.log2(min(P, pool.numel()))))
+        src_c = kv.kv_bench_copy_scrambled(arena_d.data_ptr(), pool.data_ptr(), nbytes, run, 0, 3)
+        dst_c = kv.kv_bench_copy_scrambled(pool.data_ptr(), arena_d.data_ptr(), nbytes, run, 1, 3)
+        gg, ss = 2 * P / float(np.mean(gk)) / 1e6, 2 * P / float(np.mean(sk)) / 1e6
+        out["kernels"][name] = {
+            "what": what, "blocks": nblk, "payload_gib": round(P / 2**30, 2), "bytes_per_launch": 2 * P,
+            "gather": {"kernel": "kv_move_kernel<0,1,0,false,false>", "launch_ms": round(float(np.mean(gk)), 3),
+                       "achieved": round(gg, 1), "frac": round(gg / HBM_PEAK_GBS, 4)},
+            "scatter": {"kernel": "kv_move_kernel<1,1,0,false,false>", "launch_ms": round(float(np.mean(sk)), 3),
+                        "achieved": round(ss, 1), "frac": round(ss / HBM_PEAK_GBS, 4)},
+            "scrambled_copy_ceiling_gbps": {"run_bytes": run, "source_scrambled": round(2 * nbytes / src_c / 1e6, 1),
+                                            "destination_scrambled": round(2 * nbytes / dst_c / 1e6, 1)}}
+        kd.close()
+        del pool, scale, arena_d
+        release(torch)
+    del warm
+    release(torch)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--config", type=int, required=True, choices=[1, 3, 4, 5, 6, 7])
-    ap.add_argument("--max-waves", type=int, default=4)
+    ap.add_argument("--config", type=int, required=True, choices=[1, 2, 3, 5, 6, 7, 8])
+    ap.add_argument("--max-waves", type=int, default=0)
     ap.add_argument("--variant", type=int, default=0, help="0: the configuration's own seed; 1, 2: further seeds")
     args = ap.parse_args()
     import torch
@@ -549,8 +824,12 @@ def main():
     from paper_2510_02758_amd import workloads as W
     assert torch.cuda.is_available(), "needs a GPU"
     dev = torch.device("cuda:0")
-    fn = {1: config1, 3: config3, 4: config4, 5: config5, 6: config6, 7: config7}[args.config]
-    print(json.dumps(fn(kv, W, torch, dev, args)))
+    fn = {1: config1, 2: config2, 3: config3, 5: config5, 6: config6, 7: config7, 8: config8}[args.config]
+    streams = Streams(torch)
+    if args.config == 5:
+        print(json.dumps(config5(kv, W, torch, dev, args, streams=streams, max_waves=args.max_waves or None)))
+    else:
+        print(json.dumps(fn(kv, W, torch, dev, args, streams=streams)))
 
 
 if __name__ == "__main__":

@@ -360,17 +360,23 @@ const char* kv_strerror(int code);
 
 /* ------------------------------------------------------------ measurement helpers
  * Ceilings the swap is compared against (the paper prints no bandwidth figure; Section 5.2 only asks that
- * writes use the link fully, so the link's own measured rate is the yardstick); no pool handle needed.  All three are synchronous and return the mean milliseconds per iteration, or
+ * writes use the link fully, so the link's own measured rate is the yardstick); no pool handle needed.  All four are synchronous and return the mean milliseconds per iteration, or
  * a negative number for bad arguments (-1), a failed HIP resource (-2) or a failed wait (-3).
  *   kv_bench_copy        contiguous device-to-device copy kernel of `bytes` (multiple of 16 KiB) on `stream`:
  *                        the HBM copy ceiling.  grid 0: one workgroup per 4 KiB piece (the launch shape of
  *                        the on-device gather/scatter, the fastest plain copy); grid > 0: at most that many
  *                        workgroups, grid-stride, 16 KiB pieces.
+ *   kv_bench_copy_scrambled  the same one-workgroup-per-4-KiB copy with the source (which 0) or the destination
+ *                        (which 1) visited in runs of run_bytes in a scrambled order: the ceiling of a gather
+ *                        from / a scatter into a paged pool whose chunks are that long.  run_bytes (16 bytes or
+ *                        more) and bytes / run_bytes must be powers of two, bytes a multiple of 4 KiB.
  *   kv_bench_link        one contiguous hipMemcpyAsync between PINNED host memory and device memory on
  *                        `stream`; dir 0 device -> host, 1 host -> device: the host-link ceiling.
  *   kv_bench_link_bidir  both directions at once on two internal streams (dev_a -> host_a while
  *                        host_b -> dev_b); time until both copies of a pair have finished. */
 double kv_bench_copy(void* dst_dev, const void* src_dev, int64_t bytes, int32_t grid, int32_t iters, void* stream);
+double kv_bench_copy_scrambled(void* dst_dev, const void* src_dev, int64_t bytes, int64_t run_bytes, int32_t which,
+                               int32_t iters, void* stream);
 double kv_bench_link(void* host_pinned, void* dev, int64_t bytes, int32_t dir, int32_t iters, void* stream);
 double kv_bench_link_bidir(void* host_a, const void* dev_a, const void* host_b, void* dev_b, int64_t bytes,
                            int32_t iters);

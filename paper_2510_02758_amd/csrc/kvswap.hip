@@ -818,7 +818,8 @@ int kv_pool_tune(kv_pool* p, int32_t what, int64_t value) try {
       p->max_wgs_link = std::min<int64_t>(value, 1 << 30);
       return KV_OK;
     case KV_TUNE_KERNEL_VARIANT:
-      if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8) return KV_EINVAL;
+      if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8 && value != 101 && value != 102 && value != 104)
+        return KV_EINVAL;
       p->variant = value;
       return KV_OK;
     case KV_TUNE_DMA_SLICE_BLOCKS:
@@ -887,6 +888,40 @@ double kv_bench_copy(void* dst_dev, const void* src_dev, int64_t bytes, int32_t 
       hipLaunchKernelGGL((kv_copy_kernel<4>), dim3((unsigned)std::min<int64_t>(pieces, grid)), dim3(256), 0, st,
                          (const char*)src_dev, (char*)dst_dev, pieces);
     }
+  };
+  once();
+  (void)hipEventRecord(a, st);
+  for (int i = 0; i < iters; i++) once();
+  (void)hipEventRecord(b, st);
+  float ms = -1.f;
+  if (hipEventSynchronize(b) != hipSuccess || hipEventElapsedTime(&ms, a, b) != hipSuccess) ms = -3.f * iters;
+  (void)hipEventDestroy(a);
+  (void)hipEventDestroy(b);
+  return (double)ms / iters;
+}
+
+// The same copy with one side visited in runs of run_bytes in a scrambled order (a fixed bijection on the run
+// index): what a gather from (which 0: source scrambled) or a scatter into (which 1: destination scrambled) a
+// paged pool looks like to the memory system, with the lane shape and the launch shape of the on-device kernels
+// and nothing else in the way.  run_bytes is a power of two from 16 bytes up, bytes / run_bytes a power of two,
+// bytes a multiple of 4 KiB.  Returns the mean milliseconds per copy, or < 0.
+double kv_bench_copy_scrambled(void* dst_dev, const void* src_dev, int64_t bytes, int64_t run_bytes, int32_t which,
+                               int32_t iters, void* stream) {
+  if (!dst_dev || !src_dev || bytes <= 0 || bytes % 4096 || run_bytes < 16 || iters <= 0 || (which != 0 && which != 1)) return -1.0;
+  const int64_t runs = bytes / run_bytes;
+  if ((run_bytes & (run_bytes - 1)) || runs * run_bytes != bytes || runs < 1 || (runs & (runs - 1))) return -1.0;
+  if (!range_ok(dst_dev, bytes) || !range_ok(src_dev, bytes)) return -1.0;
+  int shift = 0;
+  while ((16ll << shift) < run_bytes) shift++;
+  const int64_t chunks = runs;
+  hipStream_t st = (hipStream_t)stream;
+  hipEvent_t a, b;
+  if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return -2.0;
+  constexpr int64_t kMaxGrid = ((int64_t)1 << 32) / 256 - 1;
+  const int64_t pieces = bytes / 4096;
+  auto once = [&]() {
+    hipLaunchKernelGGL(kv_copy_scrambled_kernel, dim3((unsigned)std::min(pieces, kMaxGrid)), dim3(256), 0, st,
+                       (const char*)src_dev, (char*)dst_dev, pieces, shift, chunks - 1, (int)which);
   };
   once();
   (void)hipEventRecord(a, st);

@@ -33,7 +33,7 @@ EXPORTS = ["kv_pool_create", "kv_pool_destroy", "kv_swap_out", "kv_swap_out_delt
            "kv_move_blocks", "kv_move_blocks_noalloc", "kv_req_reserve", "kv_req_release", "kv_req_query", "kv_last_stats",
            "kv_slot_bytes", "kv_last_plan", "kv_pool_tune", "kv_last_hip_error", "kv_strerror",
            "kv_io_stats_get", "kv_budget_blocks", "kv_req_poll", "kv_req_wait", "kv_last_timeline",
-           "kv_swap_out_delta_timed", "kv_bench_copy", "kv_bench_link", "kv_bench_link_bidir",
+           "kv_swap_out_delta_timed", "kv_bench_copy", "kv_bench_copy_scrambled", "kv_bench_link", "kv_bench_link_bidir",
            "kv_wq_post", "kv_wq_drain", "kv_wq_remove", "kv_wq_pending"]
 
 
@@ -102,6 +102,7 @@ _sig = {
     "kv_io_stats_get": (C.c_int, [_vp, C.POINTER(kv_io_stats)]),
     "kv_budget_blocks": (_i64, [_vp, _i32, C.c_double]),
     "kv_bench_copy": (C.c_double, [_vp, _vp, _i64, _i32, _i32, _vp]),
+    "kv_bench_copy_scrambled": (C.c_double, [_vp, _vp, _i64, _i64, _i32, _i32, _vp]),
     "kv_bench_link": (C.c_double, [_vp, _vp, _i64, _i32, _i32, _vp]),
     "kv_bench_link_bidir": (C.c_double, [_vp, _vp, _vp, _vp, _i64, _i32]),
     "kv_wq_post": (C.c_int, [_vp, _i32, _vp, _vp, _vp, _vp, _vp]),
@@ -309,6 +310,10 @@ def kv_last_hip_error(h):
 
 def kv_bench_copy(dst_ptr, src_ptr, nbytes, grid, iters, stream=None):
     return _lib.kv_bench_copy(dst_ptr, src_ptr, int(nbytes), int(grid), int(iters), stream)
+
+
+def kv_bench_copy_scrambled(dst_ptr, src_ptr, nbytes, chunk_bytes, which, iters, stream=None):
+    return _lib.kv_bench_copy_scrambled(dst_ptr, src_ptr, int(nbytes), int(chunk_bytes), int(which), int(iters), stream)
 
 
 def kv_bench_link(host_ptr, dev_ptr, nbytes, direction, iters, stream=None):

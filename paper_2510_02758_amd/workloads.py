@@ -304,9 +304,13 @@ def fill_words_torch(seed, word_index, dtype):
 
 
 def fill_buffer_torch(seed, buf, dtype, piece=1 << 28):
-    """Fill a uint8 tensor in place, `piece` bytes at a time."""
+    """Fill a uint8 tensor in place, `piece` bytes at a time.  Returns when the fill has finished: the swap
+    library runs on streams of its own, which do not wait for the stream torch filled the buffer on."""
+    import torch
     n = buf.numel()
     for o in range(0, n, piece):
         m = min(piece, n - o)
         buf[o:o + m] = fill_bytes_torch(seed, o, m, dtype, buf.device)
+    if buf.is_cuda:
+        torch.cuda.synchronize(buf.device)
     return buf

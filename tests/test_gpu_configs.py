@@ -226,57 +226,85 @@ def test_config3_write_through_burst(gpu):
     kp.close()
 
 
+def _sample_rows(seed, wave, nb_rows, max_blocks):
+    """Seeded sample of a wave's requests for the oracle: the wave's rows in a seeded random order, taken while the
+    sample stays within max_blocks; at least one (the smallest, if none fits)."""
+    rng = np.random.default_rng((seed << 8) + wave)
+    order = rng.permutation(len(nb_rows))
+    picked, used = [], 0
+    for r in order:
+        if used + int(nb_rows[r]) <= max_blocks:
+            picked.append(int(r))
+            used += int(nb_rows[r])
+    if not picked:
+        picked = [int(np.argmin(nb_rows))]
+    return sorted(picked)
+
+
+def _waves(nb, slots, limit_blocks):
+    out, done = [], 0
+    while done < len(nb):
+        k = done
+        while k < len(nb) and int(nb[done:k + 1].sum()) <= min(slots, limit_blocks):
+            k += 1
+        assert k > done
+        out.append(np.arange(done, k))
+        done = k
+    return out
+
+
 def test_config4_llama70b_fragmented_waves(gpu):
-    """80 layers, 200 GB pool (38 146 blocks of 5 MiB), tables drawn from a half-freed pool.
-    The 128 requests total ~365 GB, more than the free half: they move in waves.  The test runs
-    the first three waves that fit a 24 GiB arena each and tracks, on the host, whose original
-    fill every block must hold afterwards."""
+    """80 layers, 200 GB pool (38 146 blocks of 5 MiB), tables drawn from a half-freed pool (another random half for
+    every wave).  The 128 requests total ~350 GiB, more than the free half: they are preempted and resumed in waves
+    through a 40 GiB arena, ALL of them.  The test tracks, on the host, whose original fill every block must hold
+    afterwards; every moved block is checked on the device, a seeded sample of each wave's requests through the oracle."""
     import torch
     wl = W.config(4)
     g = wl.geom
     assert g.N == 38146 and g.block_bytes == 5 << 20
     lens = W.request_lengths(wl.seed, wl.n_requests, wl.length_dist)
     nb = W.blocks_for(lens, g.B)
+    assert wl.n_requests == 128 and int(nb.sum()) * g.S > 300 << 30
     pool = torch.empty(g.pool_bytes, dtype=torch.uint8, device=gpu)
     W.fill_buffer_torch(wl.seed, pool, g.dtype)
-    arena_slots = (24 << 30) // g.S
+    arena_slots = (40 << 30) // g.S
     staging = _pinned(torch, arena_slots * g.S)
     kp = kv.KVPool(g, pool, staging)
     content = np.arange(g.N, dtype=np.int64)          # content[b] = block whose original fill b holds
+    waves = _waves(nb, arena_slots, limit_blocks=9000)  # a wave and its destinations both come out of the free half
     done = 0
-    for wave in range(3):
-        k = done
-        while k < wl.n_requests and int(nb[done:k + 1].sum()) <= arena_slots:
-            k += 1
-        assert k > done
-        rows = np.arange(done, k)
+    for wave, rows in enumerate(waves):
         off, ids, free = W.fragmented_tables(wl.seed + wave, g.N, nb[rows], 0.5)
         rid = (rows + 1).astype(np.uint64)
         new = free[: len(ids)]
         assert len(new) == len(ids)
+        print("config 4: wave %d, requests %d..%d, %d blocks" % (wave, rows[0], rows[-1], len(ids)), flush=True)
         assert kp.swap_out(rid, off, ids, lens[rows]) == kv.KV_OK
         assert kp.swap_in(rid, off, new) == kv.KV_OK       # back to back: ordered by the library
         assert kp.sync() == kv.KV_OK
         src_content = content[ids]
         content[new] = src_content
         assert DC.count_wrong_blocks(pool, g, g.strides, wl.seed, new, src_content) == 0, "wave %d" % wave
-        # the first request of the wave through the oracle
-        soff, stage_img, dest_img = _oracle_on_sample(g, g.strides, wl.seed, [0], off, src_content.astype(np.int32),
+        sample = _sample_rows(wl.seed, wave, nb[rows], 200)
+        soff, stage_img, dest_img = _oracle_on_sample(g, g.strides, wl.seed, sample, off, src_content.astype(np.int32),
                                                       lens[rows], new)
-        got = _device_blocks(pool, g, g.strides, new[off[0]:off[1]])
-        assert np.array_equal(got, dest_img), "wave %d" % wave
-        q = staging.numpy()[: int(off[1]) * g.S].reshape(int(off[1]), g.S)
-        assert np.array_equal(q, stage_img), "wave %d staging" % wave
-        done = k
-    assert done >= 16
+        for k, r in enumerate(sample):
+            got = _device_blocks(pool, g, g.strides, new[off[r]:off[r + 1]])
+            assert np.array_equal(got, dest_img[soff[k]:soff[k + 1]]), "wave %d request %d" % (wave, rows[r])
+            q = staging.numpy()[int(off[r]) * g.S: int(off[r + 1]) * g.S].reshape(-1, g.S)
+            assert np.array_equal(q, stage_img[soff[k]:soff[k + 1]]), "wave %d request %d staging" % (wave, rows[r])
+        done += len(rows)
+    assert done == 128 and len(waves) >= 9
     changed = DC.changed_blocks(pool, g, g.strides, wl.seed)
     assert np.array_equal(changed, np.flatnonzero(content != np.arange(g.N))), "a foreign block was touched"
     kp.close()
 
 
 def test_config5_fp8_scales_under_contention(gpu):
-    """fp8 KV with fp32 scales per (block, layer, K|V, head): 8 MiB + 8 KiB per block.  Swap-in
-    runs while another stream streams through HBM."""
+    """fp8 KV with fp32 scales per (block, layer, K|V, head): 8 MiB + 8 KiB per block.  All 512 requests (~515 GiB,
+    more than the GPU holds) go out and come back in waves through a 32 GiB arena; every fourth wave is swapped in
+    while another stream streams through HBM.  Data and scales: every moved block checked on the device, a seeded
+    sample of each wave through the oracle, the complement at the end."""
     import torch
     wl = W.config(5)
     g = wl.geom
@@ -284,76 +312,88 @@ def test_config5_fp8_scales_under_contention(gpu):
     sseed = wl.seed ^ 0x5CA1E
     lens = W.request_lengths(wl.seed, wl.n_requests, wl.length_dist)
     nb = W.blocks_for(lens, g.B)
+    assert wl.n_requests == 512 and int(nb.sum()) * g.S > 288 * 10**9
     pool = torch.empty(g.pool_bytes, dtype=torch.uint8, device=gpu)
     scale = torch.empty(g.scale_bytes, dtype=torch.uint8, device=gpu)
     W.fill_buffer_torch(wl.seed, pool, g.dtype)
     W.fill_buffer_torch(sseed, scale, "raw")
-    arena_slots = (16 << 30) // g.S
-    k = 0
-    while int(nb[:k + 1].sum()) <= arena_slots:
-        k += 1                                                   # first wave
-    rows = np.arange(k)
-    off, ids, free = W.block_tables(wl.seed, g.N, nb[rows])
-    total = int(off[-1])
-    new = free[:total]
-    rid = (rows + 1).astype(np.uint64)
-    staging = _pinned(torch, (total + 1) * g.S)
+    arena_slots = (32 << 30) // g.S
+    staging = _pinned(torch, (arena_slots + 1) * g.S)
     kp = kv.KVPool(g, pool, staging, scale=scale)
-    assert kp.swap_out(rid, off, ids, lens[rows]) == kv.KV_OK
-    assert kp.sync() == kv.KV_OK
-    sv = staging.numpy().reshape(total + 1, g.S)
-    assert (sv[total] == CANARY).all()
-    # sampled request through the oracle (data + scales)
-    srows = [0, k - 1]
-    soff, stage_img, dest_img = _oracle_on_sample(g, g.strides, wl.seed, srows, off, ids, lens[rows], new, sseed)
-    for q, r in enumerate(srows):
-        assert np.array_equal(sv[off[r]:off[r + 1]], stage_img[soff[q]:soff[q + 1]]), "request %d" % r
-    # closed form for the scale part of every request's first block
-    for i in range(k):
-        want = DC.host_blocks(g, g.scale_strides, sseed, [ids[off[i]]], dtype="raw", width=g.scale_chunk)[0]
-        assert np.array_equal(sv[off[i], g.block_bytes:], want)
-
-    # swap-in while a streaming kernel keeps HBM busy on another stream
+    sv = staging.numpy().reshape(arena_slots + 1, g.S)
     noise = torch.empty(8 << 30, dtype=torch.uint8, device=gpu)
     side = torch.cuda.Stream()
-    side.wait_stream(torch.cuda.current_stream())
-    with torch.cuda.stream(side):
-        for _ in range(40):
-            noise.add_(1)
-    assert kp.swap_in(rid, off, new) == kv.KV_OK
-    assert kp.sync() == kv.KV_OK
-    side.synchronize()
-    assert DC.count_wrong_blocks(pool, g, g.strides, wl.seed, new, ids) == 0
-    assert DC.count_wrong_blocks(scale, g, g.scale_strides, sseed, new, ids, dtype="raw", width=g.scale_chunk) == 0
-    assert np.array_equal(DC.changed_blocks(pool, g, g.strides, wl.seed), np.sort(new))
-    assert np.array_equal(DC.changed_blocks(scale, g, g.scale_strides, sseed, dtype="raw", width=g.scale_chunk),
-                          np.sort(new))
+    content = np.arange(g.N, dtype=np.int64)
+    waves = _waves(nb, arena_slots, limit_blocks=(g.N - 8) // 2)
+    done = 0
+    for wave, rows in enumerate(waves):
+        off, ids, free = W.block_tables(wl.seed + wave, g.N, nb[rows])
+        total = int(off[-1])
+        new = free[:total]
+        rid = (rows + 1).astype(np.uint64)
+        print("config 5: wave %d, requests %d..%d, %d blocks" % (wave, rows[0], rows[-1], total), flush=True)
+        assert kp.swap_out(rid, off, ids, lens[rows]) == kv.KV_OK
+        assert kp.sync() == kv.KV_OK
+        src_content = content[ids]
+        assert (sv[arena_slots] == CANARY).all()
+        # sampled requests through the oracle (data + scales)
+        sample = _sample_rows(wl.seed, wave, nb[rows], 24)
+        soff, stage_img, dest_img = _oracle_on_sample(g, g.strides, wl.seed, sample, off, src_content.astype(np.int32),
+                                                      lens[rows], new, sseed)
+        for q, r in enumerate(sample):
+            assert np.array_equal(sv[off[r]:off[r + 1]], stage_img[soff[q]:soff[q + 1]]), "wave %d request %d" % (wave, rows[r])
+        # closed form for the scale part of every request's first block
+        for i in range(len(rows)):
+            want = DC.host_blocks(g, g.scale_strides, sseed, [src_content[off[i]]], dtype="raw", width=g.scale_chunk)[0]
+            assert np.array_equal(sv[off[i], g.block_bytes:], want)
+        if wave % 4 == 0:      # this wave comes back while a streaming kernel keeps HBM busy on another stream
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                for _ in range(40):
+                    noise.add_(1)
+        assert kp.swap_in(rid, off, new) == kv.KV_OK
+        assert kp.sync() == kv.KV_OK
+        side.synchronize()
+        content[new] = src_content
+        assert DC.count_wrong_blocks(pool, g, g.strides, wl.seed, new, src_content) == 0, "wave %d" % wave
+        assert DC.count_wrong_blocks(scale, g, g.scale_strides, sseed, new, src_content, dtype="raw",
+                                     width=g.scale_chunk) == 0, "wave %d scales" % wave
+        done += len(rows)
+    assert done == 512
+    moved = np.flatnonzero(content != np.arange(g.N))
+    assert np.array_equal(DC.changed_blocks(pool, g, g.strides, wl.seed), moved)
+    assert np.array_equal(DC.changed_blocks(scale, g, g.scale_strides, sseed, dtype="raw", width=g.scale_chunk), moved)
     kp.close()
 
 
 @pytest.mark.gpu
 def test_bench_line_has_the_agreed_shape(gpu):
-    """bench.py on a half-size pool (same burst, same launches): one JSON line with the agreed fields."""
+    """bench.py on a small pool of the headline shape (same steps, same launches, two waves): one JSON line with the
+    agreed fields."""
     import json
     import subprocess
     import sys
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--blocks", "20000", "--steps", "2", "--warmup", "1",
-                        "--cpu-sample", "1"], capture_output=True, text=True, timeout=600)
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--blocks", "8000", "--steps", "2", "--warmup", "1",
+                        "--cpu-sample", "1", "--only", "headline,1", "--quick"], capture_output=True, text=True, timeout=600)
     assert r.returncode == 0, r.stderr[-2000:]
     lines = [ln for ln in r.stdout.splitlines() if ln.strip()]
     assert len(lines) == 1
     d = json.loads(lines[0])
     for k in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
-              "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+              "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline", "configs"):
         assert k in d, k
     assert d["n_gpus"] == 1 and d["steps"] == 2 and d["warmup"] == 1 and d["unit"] == "GB/s" and d["dtype"] == "u8"
     assert d["higher_is_better"] is True and d["vs_baseline"] is None and d["data"] == "synthetic"
-    assert "workload" in d["config"] and "model" not in d["config"]
+    assert "workload" in d["config"] and "model" not in d["config"] and d["config"]["workload"].startswith("configs[3]")
     rf = d["roofline"]
     assert rf["bound"] == "hbm" and rf["unit"] == "GB/s" and rf["peak"] == 8000.0
     assert abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-3 and 0.3 < rf["frac"] < 1.0
-    assert "traffic" in rf and rf["bytes_per_launch"] == 2 * 9083 * (2 << 20)
+    assert "traffic" in rf and rf["algorithmic_bytes_per_block"] == 2 * (5 << 20)
+    assert abs(rf["bytes_per_launch"] - rf["blocks_per_launch"] * rf["algorithmic_bytes_per_block"]) < 2 * (5 << 20)
+    assert rf["measured_scattered_copy_ceiling_gbps"] > 1000
     cb = d["cpu_baseline"]
     assert cb["kind"] == "oracle" and cb["cores"] == 1 and cb["unit"] == "GB/s" and cb["value"] > 0 and cb["sample"]
+    assert cb["all_cores"] >= 1 and cb["all_cores_value"] > 0
     assert 30.0 < d["value"] < 64.0 and 30.0 < d["legs"]["d2h_gbps"] < 64.0 and 30.0 < d["legs"]["h2d_gbps"] < 64.0
+    assert "configs[0]" in d["configs"]
