@@ -480,14 +480,32 @@ def test_bench_refuses_more_than_one_gpu():
 
 
 def test_bench_oracle_leg_runs_on_the_cpu():
-    """The cpu_baseline leg of bench.py is the oracle and nothing else: it runs here, on a tiny sample."""
+    """The cpu_baseline leg of bench.py is the oracle and nothing else: it runs here, on a tiny sample, on one core and
+    then once more with the sample's blocks cut over all cores."""
     import importlib.util
-    spec = importlib.util.spec_from_file_location("bench_module", os.path.join(ROOT, "bench.py"))
-    bench = importlib.util.module_from_spec(spec)
-    spec.loader.exec_module(bench)
-    wl = W.config(2)
-    lens = W.request_lengths(wl.seed, wl.n_requests, wl.length_dist)
-    off, ids, free = W.block_tables(wl.seed, wl.geom.N, W.blocks_for(lens, wl.geom.B))
-    out = bench.cpu_baseline(W, wl, lens, off, ids, 1)
+    spec = importlib.util.spec_from_file_location("bench_configs_module", os.path.join(ROOT, "bench_configs.py"))
+    bc = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bc)
+    g = W.Geometry(4, 8, 128, 16, "bf16", 64)
+    lens = np.array([300, 520], np.int32)
+    out = bc.oracle_rates(W, g, lens, W.blocks_for(lens, g.B), 2, 7, passes=2)
     assert out["kind"] == "oracle" and out["cores"] == 1 and out["unit"] == "GB/s" and out["value"] > 0
-    assert "first 1 of the 64 requests" in out["sample"]
+    assert "2 requests of the workload" in out["sample"]
+    assert out["all_cores"] == min(out["host_cores"], 19 + 33) and out["all_cores_value"] > 0
+
+
+def test_bench_waves_cover_every_request_once():
+    """The wave split of the headline: in order, every request exactly once, each wave within the arena and the free list."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("bench_configs_module", os.path.join(ROOT, "bench_configs.py"))
+    bc = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bc)
+    wl = W.config(4)
+    nb = W.blocks_for(W.request_lengths(wl.seed, wl.n_requests, wl.length_dist), wl.geom.B)
+    slots = (40 << 30) // wl.geom.S
+    waves = bc.waves_of(nb, slots, room_per_request=1, limit_blocks=9000)
+    assert np.array_equal(np.concatenate(waves), np.arange(128)) and len(waves) == 10
+    for rows in waves:
+        assert int((nb[rows] + 1).sum()) <= slots
+    with pytest.raises(ValueError):
+        bc.waves_of(nb, 100)
