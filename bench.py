@@ -42,7 +42,8 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # WRITE_SIZE runs of this script, each scaled on a plain copy of known size (summary, commands and scale factors:
 # profiles/kv_move_kernel_llama70b_waves.md, whose table holds these same numbers; tests/test_host_logic.py
 # compares the two).  KiB per block of 5 120 KiB: (read, written).
-MEASURED_KIB_PER_BLOCK = {"scatter_block_by_block": None, "scatter_plane_by_plane": None, "gather": None}
+MEASURED_KIB_PER_BLOCK = {"gather": (5120.1, 5119.8), "scatter_block_by_block": (5120.0, 5119.8),
+                          "scatter_plane_by_plane": (5120.1, 5119.8)}
 TRAFFIC_SOURCE = "profiles/kv_move_kernel_llama70b_waves.md"
 
 
@@ -69,7 +70,8 @@ def headline(kv, W, BC, torch, dev, args, arena, streams):
 
     BC.note("headline: allocating and filling the %.0f GiB pool" % (g.pool_bytes / 2**30))
     pool = torch.empty(g.pool_bytes, dtype=torch.uint8, device=dev)
-    W.fill_buffer_torch(wl.seed, pool, g.dtype)
+    if not args.no_fill:
+        W.fill_buffer_torch(wl.seed, pool, g.dtype)
     max_total = max(int(nb[r].sum()) for r in waves)
     dev_arena = torch.empty(max(max_total * g.S, 8 << 30), dtype=torch.uint8, device=dev)
     bounce = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
@@ -195,7 +197,7 @@ def headline(kv, W, BC, torch, dev, args, arena, streams):
     taken[F] = True
     pairs += [(int(p), int(p)) for p in rng.choice(np.flatnonzero(~taken), size=4)]      # blocks of foreign requests
     bad = 0
-    for holder, origin in pairs:
+    for holder, origin in (pairs if not args.no_fill else []):
         for l in (0, g.L // 2, g.L - 1):
             for c in (0, 1):
                 want = W.fill_bytes_torch(wl.seed, l * ls + c * ks + origin * bs, g.chunk, g.dtype, dev)
@@ -214,7 +216,7 @@ def headline(kv, W, BC, torch, dev, args, arena, streams):
     for name, order in (("block_by_block", 1), ("plane_by_plane", 2)):
         ok(kd.tune(kv.KV_TUNE_SCATTER_ORDER, order), "kv_pool_tune")
         gk, sk = [], []
-        for rep in range(4):
+        for rep in range(9):
             ok(kd.swap_out(t["rid"], t["off"], t["new"], t["lens"]), "kv_swap_out(device arena)")
             go = kd.stats()
             ok(kd.swap_in(t["rid"], t["off"], t["ids"]), "kv_swap_in(device arena)")
@@ -302,7 +304,7 @@ def headline(kv, W, BC, torch, dev, args, arena, streams):
         "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": r2(elapsed * 1e3 / steps),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u8", "data": "synthetic",
+        "dtype": "u8", "data": "synthetic" if not args.no_fill else "synthetic tables, pool content as allocated (--no-fill)",
         "config": {"workload": "configs[3]: Llama-3-70B-shaped KV bf16 L80 H8 D128 B16 (5 MiB blocks), %d-block pool (%.0f GB), %d "
                                "requests 1k-16k tokens (%d blocks, %.1f GiB per direction) on tables from a 50%% randomly freed pool, "
                                "preempted and resumed in %d waves through a %.0f GiB pinned arena; one step = one wave"
@@ -406,6 +408,7 @@ def compact(name, r):
         return {"both_directions_ceiling_gbps": r["measured_link_gbps"]["both_at_once"],
                 "zerocopy_ms": [r["zerocopy"]["serial_ms"], r["zerocopy"]["overlapped_ms"]],
                 "zerocopy_overlapped_gbps": r["zerocopy"]["overlapped_aggregate_gbps"],
+                "zerocopy_160_workgroups_overlapped_gbps": r["zerocopy_160_workgroups"]["overlapped_aggregate_gbps"],
                 "dma_ms": [r["dma"]["serial_ms"], r["dma"]["overlapped_ms"]],
                 "dma_overlapped_gbps": r["dma"]["overlapped_aggregate_gbps"],
                 "load_into_blocks_being_evicted_ms": {k: v["ms"] for k, v in r["load_into_blocks_being_evicted"].items()},
@@ -430,6 +433,9 @@ def main():
     ap.add_argument("--variant", type=int, default=0, help="0: the configuration's own seed; 1, 2: further seeds")
     ap.add_argument("--only", default="headline,1,2,3,5,6,8",
                     help="comma-separated parts to run: headline, 1, 2, 3, 5, 6 (load-evict overlap), 8 (general kernel builds)")
+    ap.add_argument("--no-fill", action="store_true",
+                    help="leave the headline pool's content as allocated and skip the content check (counter-collection runs, "
+                         "where the thousands of fill launches would take minutes; the swap moves bytes whatever they are)")
     ap.add_argument("--verbose", action="store_true", help="keep every field the per-configuration functions return")
     ap.add_argument("--quick", action="store_true", help="fewer isolated-latency requests and fewer waves of configs[4]")
     args = ap.parse_args()

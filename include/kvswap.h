@@ -210,6 +210,20 @@ int kv_swap_out_delta(kv_pool* p, int32_t n, const uint64_t* req_ids, const int3
 int kv_swap_in(kv_pool* p, int32_t n, const uint64_t* req_ids, const int32_t* offsets,
                const int32_t* new_block_ids, uint32_t flags, void* wait_event);
 
+/* Eviction and loading at once (Section 5.3: the two run concurrently, and blocks freed by the eviction are handed
+ * to the load).  The result is that of kv_swap_out(first set) followed by kv_swap_in(second set); the destination
+ * blocks of the load may be blocks of the requests being evicted.  The call is all-or-nothing as a whole: the load is
+ * checked before the eviction changes anything.  A request id may appear in one set only (KV_EINVAL).  On the
+ * zero-copy path the two transfers are cut into phases of KV_TUNE_PHASE_BYTES (256 MiB) and interleaved on the two
+ * streams so that one eviction kernel and one load kernel always start together, each load phase waiting only for
+ * the eviction phase that frees its blocks; per-request completion (kv_req_poll / kv_req_wait) follows the phases.
+ * On the copy-engine path and under KV_PLAN_ONLY it is the two calls one after the other.  kv_last_stats afterwards
+ * reports the load.
+ * Errors: those of kv_swap_out and kv_swap_in. */
+int kv_evict_and_load(kv_pool* p, int32_t n_out, const uint64_t* out_ids, const int32_t* out_offsets,
+                      const int32_t* out_block_ids, const int32_t* out_tokens, int32_t n_in, const uint64_t* in_ids,
+                      const int32_t* in_offsets, const int32_t* in_block_ids, uint32_t in_flags, void* wait_event);
+
 /* Blocks the calling thread until everything enqueued on this handle is done
  * (Section 6: completion is signalled through events). */
 int kv_sync(kv_pool* p);
@@ -341,7 +355,9 @@ int kv_swap_out_delta_timed(kv_pool* p, int32_t n, const uint64_t* req_ids, cons
 /* Launch-shape knobs: value 0 restores the default. */
 enum {
   KV_TUNE_MAX_WGS_DEVICE = 1, /* workgroup cap when both ends are in HBM */
-  KV_TUNE_MAX_WGS_LINK = 2,   /* workgroup cap when one end is host memory (CU budget) */
+  KV_TUNE_MAX_WGS_LINK = 2,   /* workgroup cap when one end is host memory (CU budget; default 64, which saturates the
+                                 link in one direction; a caller that keeps both directions busy with separate calls
+                                 gains 5-7 % aggregate with 128-160) */
   KV_TUNE_KERNEL_VARIANT = 3, /* 0 default; other values select experimental kernels */
   KV_TUNE_DMA_SLICE_BLOCKS = 4, /* blocks per gather+copy slice on the DMA path */
   KV_TUNE_SEGMENT_BYTES = 5,    /* smallest segment under KV_REQ_EVENTS (default 32 MiB) */
@@ -349,6 +365,11 @@ enum {
   KV_TUNE_SCATTER_ORDER = 8,    /* scatter of 1024 blocks and more with both ends in HBM: 0 default (the handle times
                                    both job orders on its first two such calls and keeps the faster), 1 always block
                                    by block, 2 plane by plane over descriptors sorted by destination block, whatever the size */
+  KV_TUNE_PHASE_BYTES = 9,      /* kv_evict_and_load: bytes of one phase per direction (default 256 MiB) */
+  KV_TUNE_PHASE_WGS_OUT = 10,   /* kv_evict_and_load: workgroups of an eviction phase (default 128) */
+  KV_TUNE_PHASE_WGS_IN = 11,    /* kv_evict_and_load: workgroups of a load phase (default 128: with both directions of
+                                   the link busy each kernel needs more requests in flight than alone, and the two do
+                                   best with equal counts) */
   KV_TUNE_SEGMENT_MAX_BYTES = 7 /* under KV_REQ_EVENTS: also cut a segment inside a long request once it reaches this
                                    many bytes (0, the default: only at request ends).  Smaller segments let a swap-in
                                    follow closer behind an eviction whose blocks it reuses, at one launch each */

@@ -346,6 +346,85 @@ int kv_swap_in(kv_pool* p, int32_t n, const uint64_t* req_ids, const int32_t* of
 }
 KV_CATCH(p)
 
+// Section 5.3 in one call: kv_swap_out of the first set followed by kv_swap_in of the second, planned together so that
+// the two transfers can be interleaved phase by phase on the two streams (see enqueue_in_phase).  Other paths than
+// zero-copy get the two calls one after the other, which the per-segment ordering already overlaps.
+int kv_evict_and_load(kv_pool* p, int32_t n_out, const uint64_t* out_ids, const int32_t* out_offsets,
+                      const int32_t* out_block_ids, const int32_t* out_tokens, int32_t n_in, const uint64_t* in_ids,
+                      const int32_t* in_offsets, const int32_t* in_block_ids, uint32_t in_flags, void* wait_event) try {
+  if (!p) return KV_EINVAL;
+  if (n_out < 0 || n_in < 0 || (n_out > 0 && !out_ids) || (n_in > 0 && !in_ids)) return KV_EINVAL;
+  {
+    std::lock_guard<std::mutex> g(p->mu);
+    if (p->broken) return KV_EHIP;
+    // a request is evicted or loaded, not both
+    std::unordered_map<uint64_t, int> seen;
+    for (int32_t i = 0; i < n_out; i++) seen.emplace(out_ids[i], 0);
+    for (int32_t i = 0; i < n_in; i++)
+      if (seen.count(in_ids[i])) return KV_EINVAL;
+    // the load is checked before the eviction changes anything: the call is all-or-nothing as a whole
+    int rc = p->planner.check_swap_in(n_in, in_ids, in_offsets, in_block_ids);
+    if (rc) return rc;
+    const bool in_phase = !p->plan_only && !use_dma(p, 1u << 30) && n_out > 0 && n_in > 0;
+    if (in_phase) {
+      const double t0 = now_us();
+      Plan po, pi;
+      rc = p->planner.plan_swap_out(n_out, out_ids, out_offsets, out_block_ids, out_tokens, &po);
+      if (rc) return rc;
+      rc = p->planner.plan_swap_in(n_in, in_ids, in_offsets, in_block_ids, in_flags, &pi);
+      if (rc) {  // cannot happen after check_swap_in; if it does, the eviction's bookkeeping is already committed
+        p->broken = true;
+        return rc;
+      }
+      for (int32_t i = 0; i < n_out; i++) p->wq.erase(out_ids[i]);
+      for (int32_t i = 0; i < n_in; i++) p->wq.erase(in_ids[i]);
+      p->last_plan = po.desc;
+      p->last_plan.insert(p->last_plan.end(), pi.desc.begin(), pi.desc.end());
+      const double t1 = now_us();
+      if (!po.desc.empty() && !pi.desc.empty()) {
+        const uint64_t dep_out = std::max(cross_stream(p, kEvict, po.wait_in_seq), pending_user(p, kEvict, po.fresh));
+        const uint64_t dep_in = cross_stream(p, kLoad, pi.wait_out_seq);
+        Call *co = nullptr, *ci = nullptr;
+        rc = open_call(p, kEvict, 1, dep_out, wait_event, 0, po.desc, &co);
+        if (rc) return rc;
+        rc = open_call(p, kLoad, 3, dep_in, wait_event, 1, pi.desc, &ci, /*do_retire=*/false);
+        if (rc) return rc;
+        fill_plan_stats(p, &co->st, 1, po.desc.size(), t1 - t0);
+        fill_plan_stats(p, &ci->st, 3, pi.desc.size(), t1 - t0);
+        rc = enqueue_in_phase(p, *co, po, *ci, pi);
+        if (rc) return rc;
+        if ((rc = close_call(p, *co)) || (rc = close_call(p, *ci))) return rc;
+        for (uint64_t id : po.touched)
+          if (kvswap::Req* r = p->planner.find_mut(id)) r->out_seq = co->seq;
+        for (uint64_t id : pi.touched)
+          if (kvswap::Req* r = p->planner.find_mut(id)) r->in_seq = ci->seq;
+        for (auto& f : pi.freed) p->pending.push_back({f.first, f.first + f.second, ci->seq});
+        co->st.enqueue_us = ci->st.enqueue_us = now_us() - t1;
+        return KV_OK;
+      }
+      // one side moves nothing: the plans are committed, enqueue them the ordinary way
+      rc = swap_out_common(p, 1, po, t0, wait_event);
+      if (rc) return rc;
+      if (pi.desc.empty() && !wait_event) return KV_OK;
+      const uint64_t dep_in = cross_stream(p, kLoad, pi.wait_out_seq);
+      Call* c = nullptr;
+      rc = open_call(p, kLoad, 3, dep_in, wait_event, 1, pi.desc, &c);
+      if (rc) return rc;
+      fill_plan_stats(p, &c->st, 3, pi.desc.size(), t1 - t0);
+      if ((rc = enqueue_transfer(p, *c, pi, false)) || (rc = close_call(p, *c))) return rc;
+      for (uint64_t id : pi.touched)
+        if (kvswap::Req* r = p->planner.find_mut(id)) r->in_seq = c->seq;
+      for (auto& f : pi.freed) p->pending.push_back({f.first, f.first + f.second, c->seq});
+      return KV_OK;
+    }
+  }
+  // plan-only handles, the copy-engine path, and calls with an empty side: the two calls one after the other
+  int rc = kv_swap_out(p, n_out, out_ids, out_offsets, out_block_ids, out_tokens, wait_event);
+  if (rc) return rc;
+  return kv_swap_in(p, n_in, in_ids, in_offsets, in_block_ids, in_flags, wait_event);
+}
+KV_CATCH(p)
+
 int kv_move_blocks(kv_pool* p, int64_t n, const int32_t* src_ids, const int32_t* dst_ids, void* wait_event) try {
   if (!p) return KV_EINVAL;
   KV_ENTER(p);
@@ -834,6 +913,15 @@ int kv_pool_tune(kv_pool* p, int32_t what, int64_t value) try {
       return KV_OK;
     case KV_TUNE_SEGMENT_MAX_BYTES:
       p->segment_max_bytes = value;
+      return KV_OK;
+    case KV_TUNE_PHASE_BYTES:
+      p->phase_bytes = value ? value : 256ll << 20;
+      return KV_OK;
+    case KV_TUNE_PHASE_WGS_OUT:
+      p->phase_wgs_out = value;
+      return KV_OK;
+    case KV_TUNE_PHASE_WGS_IN:
+      p->phase_wgs_in = value;
       return KV_OK;
     case KV_TUNE_SCATTER_ORDER:
       if (value > 2) return KV_EINVAL;

@@ -216,8 +216,8 @@ class Planner {
   }
 
   // Swap-in (Section 5, resume).  Extents are released here unless `keep`.
-  int plan_swap_in(int32_t n, const uint64_t* ids, const int32_t* off, const int32_t* blk, uint32_t flags,
-                   Plan* out) {
+  // Everything plan_swap_in checks, without changing anything.
+  int check_swap_in(int32_t n, const uint64_t* ids, const int32_t* off, const int32_t* blk) {
     int rc = check_call(n, ids, off, blk);
     if (rc || n == 0) return rc;
     for (int32_t i = 0; i < n; i++) {
@@ -226,6 +226,13 @@ class Planner {
       if ((int64_t)off[i + 1] - off[i] != r->staged) return KV_EINVAL;
     }
     if (has_duplicates(blk + off[0], (int64_t)off[n] - off[0])) return KV_EDUP;
+    return KV_OK;
+  }
+
+  int plan_swap_in(int32_t n, const uint64_t* ids, const int32_t* off, const int32_t* blk, uint32_t flags,
+                   Plan* out) {
+    int rc = check_swap_in(n, ids, off, blk);
+    if (rc || n == 0) return rc;
     for (int32_t i = 0; i < n; i++) {
       Req* r = find_mut(ids[i]);
       for (int64_t j = 0; j < r->staged; j++) out->desc.push_back({blk[off[i] + j], (int32_t)(r->base + j)});

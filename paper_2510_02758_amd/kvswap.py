@@ -27,9 +27,10 @@ KV_TUNE_SEGMENT_BYTES = 5
 KV_TUNE_SCALE_LDS = 6
 KV_TUNE_SEGMENT_MAX_BYTES = 7
 KV_TUNE_SCATTER_ORDER = 8
+KV_TUNE_PHASE_BYTES, KV_TUNE_PHASE_WGS_OUT, KV_TUNE_PHASE_WGS_IN = 9, 10, 11
 KV_F16, KV_BF16, KV_FP8_E4M3 = 0, 1, 2
 
-EXPORTS = ["kv_pool_create", "kv_pool_destroy", "kv_swap_out", "kv_swap_out_delta", "kv_swap_in", "kv_sync",
+EXPORTS = ["kv_pool_create", "kv_pool_destroy", "kv_swap_out", "kv_swap_out_delta", "kv_swap_in", "kv_evict_and_load", "kv_sync",
            "kv_move_blocks", "kv_move_blocks_noalloc", "kv_req_reserve", "kv_req_release", "kv_req_query", "kv_last_stats",
            "kv_slot_bytes", "kv_last_plan", "kv_pool_tune", "kv_last_hip_error", "kv_strerror",
            "kv_io_stats_get", "kv_budget_blocks", "kv_req_poll", "kv_req_wait", "kv_last_timeline",
@@ -84,6 +85,7 @@ _sig = {
     "kv_swap_out_delta": (C.c_int, [_vp, _i32, _vp, _vp, _vp, _vp, _i64, _u32, _vp, _vp]),
     "kv_swap_out_delta_timed": (C.c_int, [_vp, _i32, _vp, _vp, _vp, _vp, _vp, C.c_double, _u32, _vp, _vp, _vp]),
     "kv_swap_in": (C.c_int, [_vp, _i32, _vp, _vp, _vp, _u32, _vp]),
+    "kv_evict_and_load": (C.c_int, [_vp, _i32, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _u32, _vp]),
     "kv_sync": (C.c_int, [_vp]),
     "kv_move_blocks": (C.c_int, [_vp, _i64, _vp, _vp, _vp]),
     "kv_move_blocks_noalloc": (C.c_int, [_vp, _i64, _vp, _vp, _vp]),
@@ -214,6 +216,16 @@ def kv_swap_in(h, req_ids, offsets, new_block_ids, flags=0, wait_event=None):
     if not _csr_ok(len(r), o, b):
         return KV_EINVAL
     return _lib.kv_swap_in(h, len(r), _p(r), _p(o), _p(b), int(flags), wait_event)
+
+
+def kv_evict_and_load(h, out_ids, out_offsets, out_block_ids, out_tokens, in_ids, in_offsets, in_block_ids, in_flags=0,
+                      wait_event=None):
+    r, o, b, t = _u64a(out_ids), _i32a(out_offsets), _i32a(out_block_ids), _i32a(out_tokens)
+    r2, o2, b2 = _u64a(in_ids), _i32a(in_offsets), _i32a(in_block_ids)
+    if not _csr_ok(len(r), o, b, t) or not _csr_ok(len(r2), o2, b2):
+        return KV_EINVAL
+    return _lib.kv_evict_and_load(h, len(r), _p(r), _p(o), _p(b), _p(t), len(r2), _p(r2), _p(o2), _p(b2), int(in_flags),
+                                  wait_event)
 
 
 def kv_sync(h):
@@ -417,6 +429,11 @@ class KVPool:
 
     def move_blocks_noalloc(self, src_ids, dst_ids, wait_event=None):
         return kv_move_blocks_noalloc(self.h, src_ids, dst_ids, wait_event)
+
+    def evict_and_load(self, out_ids, out_offsets, out_block_ids, out_tokens, in_ids, in_offsets, in_block_ids, in_flags=0,
+                       wait_event=None):
+        return kv_evict_and_load(self.h, out_ids, out_offsets, out_block_ids, out_tokens, in_ids, in_offsets,
+                                 in_block_ids, in_flags, wait_event)
 
     def sync(self):
         return kv_sync(self.h)

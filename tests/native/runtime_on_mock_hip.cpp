@@ -197,6 +197,8 @@ int main(int argc, char** argv) {
     kv_pool_tune(kp, KV_TUNE_SEGMENT_BYTES, rnd(1, 3) * g.S);
     if (rnd(0, 1)) kv_pool_tune(kp, KV_TUNE_SEGMENT_MAX_BYTES, rnd(1, 4) * g.S);
   }
+  kv_pool_tune(kp, KV_TUNE_PHASE_BYTES, rnd(1, 3) * g.S);  // eviction and loading in one call: phases of one to three blocks
+  if (rnd(0, 1)) kv_pool_tune(kp, KV_TUNE_PHASE_WGS_IN, rnd(1, 6));
   if (rnd(0, 2) == 0) kv_pool_tune(kp, KV_TUNE_MAX_WGS_LINK, rnd(1, 5));
   if (rnd(0, 2) == 0) kv_pool_tune(kp, KV_TUNE_MAX_WGS_DEVICE, rnd(1, 7));
   if (mode == 1 && rnd(0, 1)) kv_pool_tune(kp, KV_TUNE_DMA_SLICE_BLOCKS, rnd(1, 3));
@@ -409,7 +411,7 @@ int main(int argc, char** argv) {
         (void)hipEventElapsedTime(&ms, never, never);
         hipEventDestroy(never);
       }
-      int op = (int)rnd(0, 13);
+      int op = (int)rnd(0, 14);
       if (op == 0 && !idle.empty() && free_list.size() > 8) {  // start
         const int r = idle[(size_t)rnd(0, (int64_t)idle.size() - 1)];
         cap[(size_t)r] = (int)rnd(3, cap_max);
@@ -479,6 +481,52 @@ int main(int argc, char** argv) {
           if (!keep && (rnd(0, 9) < 4 || !reserve(r, cap[(size_t)r], "re-reserve", chunk, step))) {
             // the request ends here, by choice or for want of room (the swap-in has already dropped its record):
             // its old slots stay in use by that swap-in until whoever reserves them next
+            give_up(r);
+            length[(size_t)r] = 0; state[(size_t)r] = 0;
+          }
+        }
+      } else if (op == 14 && !running.empty() && !out.empty()) {
+        // Eviction and loading in one call: one or two running requests are evicted cold while one or two others come
+        // back, and the blocks the evicted ones give up are the first the resumed ones are handed.
+        std::shuffle(running.begin(), running.end(), rng);
+        std::shuffle(out.begin(), out.end(), rng);
+        std::vector<int> ev, ld;
+        for (int r : running)
+          if (!table[(size_t)r].empty() && (int)ev.size() < (int)rnd(1, 2)) ev.push_back(r);
+        if (ev.empty()) continue;
+        std::vector<int32_t> avail;
+        for (int r : ev) avail.insert(avail.end(), table[(size_t)r].begin(), table[(size_t)r].end());
+        if (rnd(0, 1)) std::shuffle(avail.begin(), avail.end(), rng);  // in any order: a load phase may need a late eviction phase
+        size_t room = avail.size() + free_list.size(), need_blocks = 0;
+        for (int r : out) {
+          const size_t nb = (size_t)((length[(size_t)r] + g.B - 1) / g.B);
+          if ((int)ld.size() < 2 && need_blocks + nb <= room) { ld.push_back(r); need_blocks += nb; }
+        }
+        if (ld.empty()) continue;
+        std::vector<uint64_t> ids2;
+        std::vector<int32_t> off2, blk2, tok2;
+        csr(ev, ids, off, blk, tok);
+        size_t used = 0;
+        for (int r : ld) {
+          const size_t nb = (size_t)((length[(size_t)r] + g.B - 1) / g.B);
+          for (size_t q = 0; q < nb; q++) {
+            if (used < avail.size()) table[(size_t)r].push_back(avail[used++]);
+            else { table[(size_t)r].push_back(free_list.back()); free_list.pop_back(); }
+          }
+        }
+        csr(ld, ids2, off2, blk2, tok2);
+        const bool keep = rnd(0, 9) < 7;
+        const uint32_t fl = keep ? KV_KEEP_STAGING : 0;
+        int rc_ora = ora_swap_out(ora, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data());
+        if (rc_ora == 0) rc_ora = ora_swap_in(ora, (int32_t)ids2.size(), ids2.data(), off2.data(), blk2.data(), fl);
+        both(LIB(kv_evict_and_load(kp, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), (int32_t)ids2.size(),
+                                   ids2.data(), off2.data(), blk2.data(), fl, after_model)),
+             rc_ora, "evict and load", chunk, step);
+        for (int r : ev) { table[(size_t)r].clear(); state[(size_t)r] = 2; }
+        free_list.insert(free_list.end(), avail.begin() + (long)used, avail.end());  // what the load did not take
+        for (int r : ld) {
+          state[(size_t)r] = 1;
+          if (!keep && (rnd(0, 9) < 4 || !reserve(r, cap[(size_t)r], "re-reserve", chunk, step))) {
             give_up(r);
             length[(size_t)r] = 0; state[(size_t)r] = 0;
           }
@@ -673,6 +721,7 @@ int main(int argc, char** argv) {
         kv_swap_out_delta(kp, 1, &id, off1, blk1, tok1, 0, 0, moved1, nullptr) != KV_EHIP ||
         kv_swap_in(kp, 1, &id, off1, blk1, 0, nullptr) != KV_EHIP || kv_move_blocks(kp, 1, blk1, blk1 + 1, nullptr) != KV_EHIP ||
         kv_move_blocks_noalloc(kp, 1, blk1, blk1 + 1, nullptr) != KV_EHIP ||
+        kv_evict_and_load(kp, 1, &id, off1, blk1, tok1, 0, nullptr, nullptr, nullptr, 0, nullptr) != KV_EHIP ||
         kv_wq_post(kp, 1, &id, off1, blk1, tok1, nullptr) != KV_EHIP || kv_wq_drain(kp, 0, 4, 0, &a, &b, &c, nullptr) != KV_EHIP ||
         kv_sync(kp) != KV_EHIP || kv_pool_tune(kp, KV_TUNE_MAX_WGS_LINK, 8) != KV_EHIP)
       die("a call was accepted by a handle that had failed", -1, -1);

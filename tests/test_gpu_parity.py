@@ -344,6 +344,65 @@ def test_device_block_hazards_between_streams(gpu, events, seg_max, order, path)
     kp.close()
 
 
+@pytest.mark.parametrize("mode", ["zerocopy", "dma", "device_arena"])
+@pytest.mark.parametrize("order", ["same", "reverse", "shuffled"])
+def test_evict_and_load_in_one_call(gpu, mode, order):
+    """kv_evict_and_load: two requests are evicted while a third is loaded into the very blocks they give up, in the
+    order they are evicted, in the opposite order, or in any order; phases of 8 blocks.  Then a second call whose
+    load needs no block of its eviction, and calls with one side empty.  Expected: what the oracle reaches with
+    swap_out followed by swap_in; nothing waits on the host before the end."""
+    import torch
+    g = W.Geometry(32, 8, 128, 16, "bf16", 1400)             # 2 MiB blocks
+    a = HostPool(g, 0xE71C7, slots=1300)
+    ora = a.oracle()
+    pool = torch.from_numpy(a.pool.copy()).cuda()
+    if mode == "device_arena":
+        staging = torch.full((len(a.staging),), CANARY, dtype=torch.uint8, device="cuda")
+        kp = kv.KVPool(g, pool, staging, flags=kv.KV_STAGING_DEVICE)
+    elif mode == "dma":
+        staging = torch.full((len(a.staging),), CANARY, dtype=torch.uint8).pin_memory()
+        bounce = torch.zeros(2 * 24 * g.S, dtype=torch.uint8, device="cuda")
+        kp = kv.KVPool(g, pool, staging, bounce=bounce, flags=kv.KV_PATH_DMA)
+    else:
+        staging = torch.full((len(a.staging),), CANARY, dtype=torch.uint8).pin_memory()
+        kp = kv.KVPool(g, pool, staging, flags=kv.KV_PATH_ZEROCOPY)
+    assert kp.tune(kv.KV_TUNE_PHASE_BYTES, 8 * g.S) == kv.KV_OK
+    rng = np.random.default_rng(12)
+    perm = rng.permutation(g.N).astype(np.int32)
+    X, Y, Z, V = perm[:300], perm[300:600], perm[600:900], perm[900:1100]
+    offA = np.array([0, 100, 300], np.int32)
+    lensA = np.array([100 * g.B, 200 * g.B - 5], np.int32)
+    lensB = np.array([300 * g.B], np.int32)
+    Xw = {"same": X, "reverse": X[::-1].copy(), "shuffled": rng.permutation(X).astype(np.int32)}[order]
+
+    # B lives in Y and is swapped out first; A (two requests) lives in X
+    for o, OK in ((kp, kv.KV_OK), (ora, ko.OK)):
+        assert o.swap_out([7], [0, 300], Y, lensB) == OK
+    # 1. evict A while B is loaded into A's blocks
+    assert kp.evict_and_load([1, 2], offA, X, lensA, [7], [0, 300], Xw, kv.KV_KEEP_STAGING) == kv.KV_OK
+    assert ora.swap_out([1, 2], offA, X, lensA) == ko.OK and ora.swap_in([7], [0, 300], Xw, ko.KEEP_STAGING) == ko.OK
+    # 2. at once: evict a request that owns the blocks B has just been loaded into, while A comes back elsewhere
+    assert kp.evict_and_load([8], [0, 300], X, lensB, [1, 2], offA, Z) == kv.KV_OK
+    assert ora.swap_out([8], [0, 300], X, lensB) == ko.OK and ora.swap_in([1, 2], offA, Z) == ko.OK
+    # 3. one side empty
+    assert kp.evict_and_load([9], [0, 200], V, [200 * g.B], [], [0], []) == kv.KV_OK
+    assert ora.swap_out([9], [0, 200], V, [200 * g.B]) == ko.OK
+    assert kp.evict_and_load([], [0], [], [], [9], [0, 200], V[::-1].copy()) == kv.KV_OK
+    assert ora.swap_in([9], [0, 200], V[::-1].copy()) == ko.OK
+    # refusals leave everything as it was: a request in both sets, an unknown request to load (the eviction must not happen)
+    assert kp.evict_and_load([8], [0, 300], X, lensB, [8], [0, 300], Y) == kv.KV_EINVAL
+    assert kp.evict_and_load([1], [0, 100], Z[:100], [100 * g.B], [99], [0, 1], [5]) == kv.KV_ENOENT
+    assert kp.query(1)[0] == kv.KV_ENOENT                     # request 1 is resident and unknown to the arena: not evicted
+    assert kp.sync() == kv.KV_OK
+    host = staging.cpu().numpy() if mode == "device_arena" else staging.numpy()
+    assert np.array_equal(host, a.staging), "staging differs from the oracle"
+    assert np.array_equal(pool.cpu().numpy(), a.pool), "pool differs from the oracle: a load phase ran before its blocks were read"
+    for r in (1, 2, 7, 8, 9):
+        (rc_a, qa), (rc_b, qb) = kp.query(r), ora.query(r)
+        assert rc_a == rc_b and (rc_a != 0 or qa == qb), r
+    kp.close()
+
+
 def test_segments_cut_inside_a_request(gpu):
     """KV_TUNE_SEGMENT_MAX_BYTES: a long request goes out in pieces of that size (one launch each on the
     zero-copy path); its completion is that of its last piece; the bytes are the oracle's."""

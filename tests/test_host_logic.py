@@ -509,3 +509,21 @@ def test_bench_waves_cover_every_request_once():
         assert int((nb[rows] + 1).sum()) <= slots
     with pytest.raises(ValueError):
         bc.waves_of(nb, 100)
+
+
+def test_bench_traffic_constants_are_the_profile_summarys():
+    """bench.py reports `traffic` from per-block counter figures it carries as constants: they must be the numbers of the
+    committed rocprofv3 summary, not a copy that has drifted."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("bench_module", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    text = open(os.path.join(ROOT, bench.TRAFFIC_SOURCE)).read()
+    rows = {"gather": "gather, HBM to HBM", "scatter_block_by_block": "scatter block by block, HBM to HBM",
+            "scatter_plane_by_plane": "scatter plane by plane, HBM to HBM"}
+    for key, label in rows.items():
+        line = [ln for ln in text.splitlines() if label in ln and ln.startswith("| `kv_move_kernel")]
+        assert len(line) == 1, key
+        cells = [c.strip() for c in line[0].split("|")]
+        assert (float(cells[3]), float(cells[4])) == tuple(bench.MEASURED_KIB_PER_BLOCK[key]), key
+        assert abs((float(cells[3]) + float(cells[4])) / (2 * 5120) - 1) < 0.01      # nothing is moved twice

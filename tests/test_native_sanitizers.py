@@ -157,14 +157,16 @@ RUNTIME_MUTANTS = [
     ("staging_slot_waits_off", "  if (wait_seq) {", "  if (false && wait_seq) {"),
     ("callers_event_ignored", "  if (wait_event) HIPCHK(p, hipStreamWaitEvent(st, (hipEvent_t)wait_event, 0));", ""),
     ("stale_error_of_the_application_taken_for_a_failed_launch",
-     "  (void)hipGetLastError();\n  if (mode == 0)\n    launch_move<0>(u, grid, kind, st, a);",
-     "  if (mode == 0)\n    launch_move<0>(u, grid, kind, st, a);"),
+     "  (void)hipGetLastError();\n  const bool pipe = kind != 1 && pipelined_variant(p);",
+     "  const bool pipe = kind != 1 && pipelined_variant(p);"),
     ("newest_call_hides_the_other_stream",
      "s = std::max(s, cross_stream(p, stream, q.seq));", "s = std::max(s, q.seq);"),
     ("allocation_free_move_not_ordered_after_the_load_stream",
      "  HIPCHK(p, hipStreamWaitEvent(st, p->na_fence_ev, 0));", ""),
     ("load_stream_does_not_wait_for_an_allocation_free_move",
      "      HIPCHK(p, hipStreamWaitEvent(st, p->na_done_ev, 0));", ""),
+    ("load_phase_forgets_the_eviction_phase_that_frees_its_blocks",
+     "    if (it != reader.end()) need[i / m] = std::max(need[i / m], it->second);", "    (void)it;"),
     ("write_through_that_moves_nothing_forgets_the_pending_reader",
      "        if (kvswap::Req* r = p->planner.find_mut(id)) r->in_seq = std::max(r->in_seq, fresh_dep);", "        (void)id;"),
 ]
