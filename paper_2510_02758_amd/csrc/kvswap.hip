@@ -139,18 +139,18 @@ int kv_pool_create(const kv_pool_config* cfg, kv_pool** out) {
     // The kernels trust these extents: refuse a pool whose strides leave its allocation.
     const int64_t pool_need = (cfg->num_layers - 1) * cfg->layer_stride + cfg->kv_stride +
                               (cfg->num_blocks - 1) * cfg->block_stride + chunk;
-    bool ok = range_ok(cfg->pool_dev, pool_need);
+    bool ok = range_ok(cfg->pool_dev, pool_need, true);
     if (!ok) KVDBG("pool strides reach %lld bytes, past the end of the allocation", (long long)pool_need);
     if (ok && scales) {
       ok = range_ok(cfg->scale_dev, (cfg->num_layers - 1) * cfg->scale_layer_stride + cfg->scale_kv_stride +
-                                        (cfg->num_blocks - 1) * cfg->scale_block_stride + scale_chunk);
+                                        (cfg->num_blocks - 1) * cfg->scale_block_stride + scale_chunk, true);
       if (!ok) KVDBG("scale strides reach past the end of the allocation");
     }
-    if (ok && !range_ok(cfg->staging_host, cfg->staging_bytes)) {
+    if (ok && !range_ok(cfg->staging_host, cfg->staging_bytes, (cfg->flags & KV_STAGING_DEVICE) != 0)) {
       ok = false;
       KVDBG("staging_bytes reaches past the end of the arena allocation");
     }
-    if (ok && cfg->bounce_dev && !range_ok(cfg->bounce_dev, cfg->bounce_bytes)) {
+    if (ok && cfg->bounce_dev && !range_ok(cfg->bounce_dev, cfg->bounce_bytes, true)) {
       ok = false;
       KVDBG("bounce_bytes reaches past the end of the bounce allocation");
     }
@@ -199,7 +199,7 @@ int kv_pool_create(const kv_pool_config* cfg, kv_pool** out) {
         }
       }
     }
-    if (!rc) rc = grow_ring(p, (size_t)1 << 16);
+    if (!rc) rc = grow_ring(p, ring_entries_for(cfg->num_blocks));
     if (!rc) {
       p->blk_reader.assign((size_t)cfg->num_blocks, BlkMark{0, -1});
       p->blk_writer.assign((size_t)cfg->num_blocks, BlkMark{0, -1});
@@ -961,7 +961,7 @@ const char* kv_strerror(int code) {
 // copy, or < 0.
 double kv_bench_copy(void* dst_dev, const void* src_dev, int64_t bytes, int32_t grid, int32_t iters, void* stream) {
   if (!dst_dev || !src_dev || bytes <= 0 || bytes % 16384 || grid < 0 || iters <= 0) return -1.0;
-  if (!range_ok(dst_dev, bytes) || !range_ok(src_dev, bytes)) return -1.0;
+  if (!range_ok(dst_dev, bytes, true) || !range_ok(src_dev, bytes, true)) return -1.0;
   hipStream_t st = (hipStream_t)stream;
   hipEvent_t a, b;
   if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return -2.0;
@@ -998,7 +998,7 @@ double kv_bench_copy_scrambled(void* dst_dev, const void* src_dev, int64_t bytes
   if (!dst_dev || !src_dev || bytes <= 0 || bytes % 4096 || run_bytes < 16 || iters <= 0 || (which != 0 && which != 1)) return -1.0;
   const int64_t runs = bytes / run_bytes;
   if ((run_bytes & (run_bytes - 1)) || runs * run_bytes != bytes || runs < 1 || (runs & (runs - 1))) return -1.0;
-  if (!range_ok(dst_dev, bytes) || !range_ok(src_dev, bytes)) return -1.0;
+  if (!range_ok(dst_dev, bytes, true) || !range_ok(src_dev, bytes, true)) return -1.0;
   int shift = 0;
   while ((16ll << shift) < run_bytes) shift++;
   const int64_t chunks = runs;

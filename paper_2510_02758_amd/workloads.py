@@ -1,9 +1,15 @@
 """Seeded synthetic inputs shared by the tests, the smoke check and the benchmark.
 
 This module only *produces inputs*: KV geometries, request lengths, block
-tables and pool contents.  It contains nothing of the swap itself (no staging
-layout, no copy), imports neither the GPU binding nor the CPU oracle, and is
-the one piece both sides are fed from.
+tables and pool contents.  It contains nothing of the swap itself (no copy, no
+placement of extents, no address of anything inside the staging arena),
+imports neither the GPU binding nor the CPU oracle, and is the one piece both
+sides are fed from.  `Geometry` does carry the sizes the interface defines for
+a shape (bytes of a chunk, of a block, of a staging slot, the default strides):
+callers need them to allocate pools and arenas.  The library and the oracle
+each work these sizes out again from L, H, D, B and the element size, and so do
+the tests' closed forms (tests/hostpool.py), so nothing is checked against
+figures taken from here.
 
 Pool contents are "address coded": the 64-bit word at byte offset 8*w of a
 buffer is splitmix64(seed, w), a counter-based generator, so any part of a pool

@@ -2,11 +2,27 @@
 the closed-form index arithmetic the pins compare against.  No copy loop lives
 here: expected values are always gathered through index arrays computed from
 the layout formulas."""
+import collections
+
 import numpy as np
 
 from paper_2510_02758_amd import workloads as W
 
 CANARY = 0xA5
+
+_ELEM = {"f16": 2, "bf16": 2, "fp8_e4m3": 1}
+Sizes = collections.namedtuple("Sizes", "chunk block_bytes scale_chunk block_scale_bytes S")
+
+
+def sizes(geom):
+    """The sizes the interface header defines, worked out here from L, H, D, B and the element size alone, so that
+    the pins' closed forms do not lean on the module that also feeds the library its shapes."""
+    e = _ELEM[geom.dtype]
+    chunk = geom.B * geom.H * geom.D * e                 # K or V of one block in one layer
+    block_bytes = 2 * geom.L * chunk
+    scale_chunk = geom.H * 4 if geom.scales else 0       # one fp32 per head
+    block_scale_bytes = 2 * geom.L * scale_chunk
+    return Sizes(chunk, block_bytes, scale_chunk, block_scale_bytes, block_bytes + block_scale_bytes)
 
 
 def strides_for(geom, layout):
@@ -37,7 +53,8 @@ class HostPool:
             self.scale = W.fill_buffer_np(seed ^ 0x5CA1E, sbytes, "raw") if fill else np.zeros(sbytes, np.uint8)
         self.slots = geom.N if slots is None else slots
         # spare bytes after the last slot (less than a slot): they must stay canary too
-        self.staging = np.full(self.slots * geom.S + min(40, geom.S // 2), CANARY, dtype=np.uint8)
+        self.sz = sizes(geom)
+        self.staging = np.full(self.slots * self.sz.S + min(40, self.sz.S // 2), CANARY, dtype=np.uint8)
 
     def oracle(self, lib=None):
         """The C oracle over these arrays; `lib` may name another build of it, or be a
@@ -57,7 +74,7 @@ class HostPool:
         p = np.asarray(phys, dtype=np.int64)
         idx = (p[:, None, None, None] * bs + np.arange(g.L, dtype=np.int64)[None, :, None, None] * ls
                + np.arange(2, dtype=np.int64)[None, None, :, None] * ks
-               + np.arange(g.chunk, dtype=np.int64)[None, None, None, :])
+               + np.arange(self.sz.chunk, dtype=np.int64)[None, None, None, :])
         return idx.reshape(len(p), -1)
 
     def scale_index(self, phys):
@@ -66,7 +83,7 @@ class HostPool:
         p = np.asarray(phys, dtype=np.int64)
         idx = (p[:, None, None, None] * bs + np.arange(g.L, dtype=np.int64)[None, :, None, None] * ls
                + np.arange(2, dtype=np.int64)[None, None, :, None] * ks
-               + np.arange(g.scale_chunk, dtype=np.int64)[None, None, None, :])
+               + np.arange(self.sz.scale_chunk, dtype=np.int64)[None, None, None, :])
         return idx.reshape(len(p), -1)
 
     def block_image(self, phys, pool=None, scale=None):
@@ -80,4 +97,4 @@ class HostPool:
 
     def slots_view(self, staging=None):
         s = self.staging if staging is None else staging
-        return s[: self.slots * self.geom.S].reshape(self.slots, self.geom.S)
+        return s[: self.slots * self.sz.S].reshape(self.slots, self.sz.S)

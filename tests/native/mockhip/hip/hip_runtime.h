@@ -43,6 +43,9 @@ long deadlocks();
 // Calls so far that take or give back a resource on a real device: hipMalloc, hipHostMalloc, hipFree, hipHostFree,
 // event and stream creation and destruction.  An entry point that promises not to allocate leaves it unchanged.
 long resource_calls();
+// Calls of the CURRENT THREAD so far that block the host until device work has finished (hipStreamSynchronize,
+// hipEventSynchronize): an entry point that promises to be asynchronous leaves it unchanged.
+long host_waits();
 // Failure injection: the n-th call from now, counted over the calls that can fail on a real device (event
 // creation, record, wait, query and synchronisation, stream synchronisation, copies, kernel launches), returns
 // `code` and does nothing else; n <= 0 disarms.  failure_fired() tells whether it has happened.

@@ -158,6 +158,8 @@ long executed_ops() {
 }
 static std::atomic<long> n_resource{0};
 long resource_calls() { return n_resource.load(); }
+static thread_local long n_host_waits = 0;
+long host_waits() { return n_host_waits; }
 
 long deadlocks() {
   API_LOCK;
@@ -244,6 +246,7 @@ hipError_t hipStreamDestroy(hipStream_t s) {
   return hipSuccess;
 }
 hipError_t hipStreamSynchronize(hipStream_t s) {
+  n_host_waits++;
   {
     API_LOCK;
     if (injected()) return fail_code;
@@ -294,6 +297,7 @@ hipError_t hipEventQuery(hipEvent_t e) {
   return e->completed >= e->recorded ? hipSuccess : hipErrorNotReady;
 }
 hipError_t hipEventSynchronize(hipEvent_t e) {
+  n_host_waits++;
   uint64_t gen;
   {
     API_LOCK;

@@ -76,6 +76,17 @@ static int leave_lib(int rc) {
   return rc;
 }
 #define LIB(call) (g_in_lib = true, leave_lib(call))
+// The same for the entry points that only enqueue: they must come back without having waited for the device (the
+// descriptor ring is sized so that a burst never finds it full; nothing else in them waits).
+static int leave_async(int rc, long waits_before, const char* what) {
+  g_in_lib = false;
+  if (mockhip::host_waits() != waits_before) {
+    std::fprintf(stderr, "MISMATCH: %s waited for the device on the host\n", what);
+    std::exit(1);
+  }
+  return rc;
+}
+#define LIB_ASYNC(call) (g_in_lib = true, leave_async(call, mockhip::host_waits(), #call))
 
 namespace {
 
@@ -203,9 +214,10 @@ int main(int argc, char** argv) {
   if (rnd(0, 2) == 0) kv_pool_tune(kp, KV_TUNE_MAX_WGS_DEVICE, rnd(1, 7));
   if (mode == 1 && rnd(0, 1)) kv_pool_tune(kp, KV_TUNE_DMA_SLICE_BLOCKS, rnd(1, 3));
   if (mode == 2 && rnd(0, 1)) kv_pool_tune(kp, KV_TUNE_SCATTER_ORDER, 2);  // the plane-by-plane build of the scatter
+  if (seed < 192 && seed % 4 == 1 && mode != 0 && rnd(0, 1)) kv_pool_tune(kp, KV_TUNE_KERNEL_VARIANT, 101);  // 4 KiB chunks: the pipelined build
   if (seed >= 192 && rnd(0, 1)) {  // loads in flight per lane: every build of the kernel
-    const int64_t u[4] = {1, 2, 4, 8};
-    if (kv_pool_tune(kp, KV_TUNE_KERNEL_VARIANT, u[rnd(0, 3)]) != KV_OK) die("tune", -1, -1);
+    const int64_t u[7] = {1, 2, 4, 8, 101, 102, 104};  // 10x: resident pipelined workgroups, where the chunk allows
+    if (kv_pool_tune(kp, KV_TUNE_KERNEL_VARIANT, u[rnd(0, 6)]) != KV_OK) die("tune", -1, -1);
   }
 
   // ---- the serving history ----
@@ -299,7 +311,7 @@ int main(int argc, char** argv) {
       };
       auto cold_out = [&](int r) {
         csr({r}, ids, off, blk, tok);
-        both(LIB(kv_swap_out(kp, 1, ids.data(), off.data(), blk.data(), tok.data(), nullptr)),
+        both(LIB_ASYNC(kv_swap_out(kp, 1, ids.data(), off.data(), blk.data(), tok.data(), nullptr)),
              ora_swap_out(ora, 1, ids.data(), off.data(), blk.data(), tok.data()), "opening swap_out", 0, -1);
         give_up(r);
         state[(size_t)r] = 2;
@@ -315,7 +327,7 @@ int main(int argc, char** argv) {
           while ((int)table[(size_t)r].size() < blocks) { table[(size_t)r].push_back(free_list.back()); free_list.pop_back(); }
           length[(size_t)r] = tokens;
           csr({r}, ids, off, blk, tok);
-          both(LIB(kv_swap_out_delta(kp, 1, ids.data(), off.data(), blk.data(), tok.data(), 0, 0, mb.data(), nullptr)),
+          both(LIB_ASYNC(kv_swap_out_delta(kp, 1, ids.data(), off.data(), blk.data(), tok.data(), 0, 0, mb.data(), nullptr)),
                ora_swap_out_delta(ora, 1, ids.data(), off.data(), blk.data(), tok.data(), 0, 0, ma.data()), what, 0, -1);
           if (ma != mb) die("blocks_moved", 0, -1);
         };
@@ -324,7 +336,7 @@ int main(int argc, char** argv) {
           cold_out(r);
           for (int j = 0; j < n; j++) { table[(size_t)r].push_back(free_list.back()); free_list.pop_back(); }
           csr({r}, ids, off, blk, tok);
-          both(LIB(kv_swap_in(kp, 1, ids.data(), off.data(), blk.data(), 0, nullptr)), ora_swap_in(ora, 1, ids.data(), off.data(), blk.data(), 0),
+          both(LIB_ASYNC(kv_swap_in(kp, 1, ids.data(), off.data(), blk.data(), 0, nullptr)), ora_swap_in(ora, 1, ids.data(), off.data(), blk.data(), 0),
                "opening swap_in", 0, -1);
           held.insert(held.end(), table[(size_t)r].begin(), table[(size_t)r].end());
           table[(size_t)r].clear();
@@ -354,7 +366,7 @@ int main(int argc, char** argv) {
       cold_out(1);
       for (int j = 0; j < 4; j++) { table[1].push_back(free_list.back()); free_list.pop_back(); }
       csr({1}, ids, off, blk, tok);
-      both(LIB(kv_swap_in(kp, 1, ids.data(), off.data(), blk.data(), 0, nullptr)), ora_swap_in(ora, 1, ids.data(), off.data(), blk.data(), 0),
+      both(LIB_ASYNC(kv_swap_in(kp, 1, ids.data(), off.data(), blk.data(), 0, nullptr)), ora_swap_in(ora, 1, ids.data(), off.data(), blk.data(), 0),
            "opening swap_in", 0, -1);
       held.insert(held.end(), table[1].begin(), table[1].end());  // kept out of circulation until the chunk's comparison: what the swap-in wrote must still be there
       table[1].clear();
@@ -366,7 +378,7 @@ int main(int argc, char** argv) {
       fill(3, 7);
       csr({3}, ids, off, blk, tok);
       std::vector<int32_t> ma(1), mb(1);
-      both(LIB(kv_swap_out_delta(kp, 1, ids.data(), off.data(), blk.data(), tok.data(), 0, 0, mb.data(), nullptr)),
+      both(LIB_ASYNC(kv_swap_out_delta(kp, 1, ids.data(), off.data(), blk.data(), tok.data(), 0, 0, mb.data(), nullptr)),
            ora_swap_out_delta(ora, 1, ids.data(), off.data(), blk.data(), tok.data(), 0, 0, ma.data()), "opening delta", 0, -1);
       if (ma != mb) die("blocks_moved", 0, -1);
     }
@@ -437,7 +449,7 @@ int main(int argc, char** argv) {
           csr(with, ids, off, blk, tok);
           const int64_t budget = rnd(0, 5);
           std::vector<int32_t> ma(with.size(), -1), mb(with.size(), -1);
-          both(LIB(kv_swap_out_delta(kp, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), budget, 0, mb.data(), nullptr)),
+          both(LIB_ASYNC(kv_swap_out_delta(kp, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), budget, 0, mb.data(), nullptr)),
                ora_swap_out_delta(ora, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), budget, 0, ma.data()),
                "delta", chunk, step);
           if (ma != mb) die("blocks_moved", chunk, step);
@@ -450,11 +462,11 @@ int main(int argc, char** argv) {
         if (rs.empty()) continue;
         csr(rs, ids, off, blk, tok);
         if (op == 4) {
-          both(LIB(kv_swap_out(kp, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), nullptr)),
+          both(LIB_ASYNC(kv_swap_out(kp, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), nullptr)),
                ora_swap_out(ora, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data()), "swap_out", chunk, step);
         } else {
           std::vector<int32_t> ma(rs.size()), mb(rs.size());
-          both(LIB(kv_swap_out_delta(kp, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), 0, KV_DELTA_INCLUDE_TAIL, mb.data(), nullptr)),
+          both(LIB_ASYNC(kv_swap_out_delta(kp, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), 0, KV_DELTA_INCLUDE_TAIL, mb.data(), nullptr)),
                ora_swap_out_delta(ora, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), 0, KV_DELTA_INCLUDE_TAIL, ma.data()),
                "tail delta", chunk, step);
         }
@@ -474,7 +486,7 @@ int main(int argc, char** argv) {
         }
         csr(rs, ids, off, blk, tok);
         const bool keep = rnd(0, 9) < 7;
-        both(LIB(kv_swap_in(kp, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), keep ? KV_KEEP_STAGING : 0, after_model)),
+        both(LIB_ASYNC(kv_swap_in(kp, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), keep ? KV_KEEP_STAGING : 0, after_model)),
              ora_swap_in(ora, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), keep ? KV_KEEP_STAGING : 0), "swap_in", chunk, step);
         for (int r : rs) {
           state[(size_t)r] = 1;
@@ -519,7 +531,7 @@ int main(int argc, char** argv) {
         const uint32_t fl = keep ? KV_KEEP_STAGING : 0;
         int rc_ora = ora_swap_out(ora, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data());
         if (rc_ora == 0) rc_ora = ora_swap_in(ora, (int32_t)ids2.size(), ids2.data(), off2.data(), blk2.data(), fl);
-        both(LIB(kv_evict_and_load(kp, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), (int32_t)ids2.size(),
+        both(LIB_ASYNC(kv_evict_and_load(kp, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), (int32_t)ids2.size(),
                                    ids2.data(), off2.data(), blk2.data(), fl, after_model)),
              rc_ora, "evict and load", chunk, step);
         for (int r : ev) { table[(size_t)r].clear(); state[(size_t)r] = 2; }
@@ -545,7 +557,7 @@ int main(int argc, char** argv) {
                ora_move_blocks(ora, (int64_t)k, src.data(), dst.data()), "move without allocation", chunk, step);
           if (mockhip::resource_calls() != res0) die("kv_move_blocks_noalloc allocated", chunk, step);
         } else
-        both(LIB(kv_move_blocks(kp, (int64_t)k, src.data(), dst.data(), after_model)), ora_move_blocks(ora, (int64_t)k, src.data(), dst.data()),
+        both(LIB_ASYNC(kv_move_blocks(kp, (int64_t)k, src.data(), dst.data(), after_model)), ora_move_blocks(ora, (int64_t)k, src.data(), dst.data()),
              "move", chunk, step);
         std::copy(dst.begin(), dst.end(), table[(size_t)r].begin());
         free_list.insert(free_list.end(), src.begin(), src.end());
@@ -565,7 +577,7 @@ int main(int argc, char** argv) {
         csr(with, ids, off, blk, tok);
         std::vector<double> prio(with.size());
         for (auto& x : prio) x = (double)rnd(0, 3);  // few levels: ties keep the order of the post
-        both(LIB(kv_wq_post(kp, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), prio.data())), 0, "wq_post", chunk, step);
+        both(LIB_ASYNC(kv_wq_post(kp, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), prio.data())), 0, "wq_post", chunk, step);
         // what the queue promises: the same as one delta over the posted requests, highest priority first
         std::vector<int> order(with.size());
         for (size_t i = 0; i < order.size(); i++) order[i] = (int)i;
@@ -577,7 +589,7 @@ int main(int argc, char** argv) {
         int64_t written = -1, pending = -1, used = -1, expect = 0;
         if (rnd(0, 3) == 0) {
           // budget from a time interval: the library derives it from its own rate estimates and says what it used
-          const int rc = LIB(kv_wq_drain(kp, (double)rnd(1, 3000), 0, 0, &written, &pending, &used, nullptr));
+          const int rc = LIB_ASYNC(kv_wq_drain(kp, (double)rnd(1, 3000), 0, 0, &written, &pending, &used, nullptr));
           if ((rc == KV_EHIP && mockhip::failure_fired()) || (rc == KV_ENOMEM && g_new_fired)) throw Failed{rc};
           if (rc != KV_OK || used < 0) die("timed wq_drain", chunk, step);
           calls++;
@@ -589,7 +601,7 @@ int main(int argc, char** argv) {
             die("timed wq_drain: oracle", chunk, step);
         } else {
           const int64_t budget = rnd(1, 6);
-          both(LIB(kv_wq_drain(kp, 0.0, budget, 0, &written, &pending, &used, nullptr)),
+          both(LIB_ASYNC(kv_wq_drain(kp, 0.0, budget, 0, &written, &pending, &used, nullptr)),
                ora_swap_out_delta(ora, (int32_t)ids.size(), ids.data(), off.data(), blk.data(), tok.data(), budget, 0, ma.data()),
                "wq_drain", chunk, step);
           if (used != budget) die("wq_drain: budget", chunk, step);
@@ -618,7 +630,7 @@ int main(int argc, char** argv) {
         after_model = ev_compute;
         csr({r}, ids, off, blk, tok);
         std::vector<int32_t> ma(1), mb(1);
-        both(LIB(kv_swap_out_delta(kp, 1, ids.data(), off.data(), blk.data(), tok.data(), 0, KV_DELTA_INCLUDE_TAIL, mb.data(), ev_compute)),
+        both(LIB_ASYNC(kv_swap_out_delta(kp, 1, ids.data(), off.data(), blk.data(), tok.data(), 0, KV_DELTA_INCLUDE_TAIL, mb.data(), ev_compute)),
              ora_swap_out_delta(ora, 1, ids.data(), off.data(), blk.data(), tok.data(), 0, KV_DELTA_INCLUDE_TAIL, ma.data()),
              "delta after the model", chunk, step);
         if (ma != mb) die("blocks_moved", chunk, step);
@@ -645,17 +657,17 @@ int main(int argc, char** argv) {
           std::vector<int32_t> dst(nb, free_list.back());
           uint64_t id = (uint64_t)r;
           int32_t o2[2] = {0, (int32_t)nb};
-          same(LIB(kv_swap_in(kp, 1, &id, o2, dst.data(), 0, nullptr)), ora_swap_in(ora, 1, &id, o2, dst.data(), 0), "duplicate destination");
+          same(LIB_ASYNC(kv_swap_in(kp, 1, &id, o2, dst.data(), 0, nullptr)), ora_swap_in(ora, 1, &id, o2, dst.data(), 0), "duplicate destination");
         } else if (which == 1 && !running.empty() && !table[(size_t)running[0]].empty()) {  // a block id outside the pool
           const int r = running[0];
           csr({r}, ids, off, blk, tok);
           blk.back() = (int32_t)g.N;
-          same(LIB(kv_swap_out(kp, 1, ids.data(), off.data(), blk.data(), tok.data(), nullptr)),
+          same(LIB_ASYNC(kv_swap_out(kp, 1, ids.data(), off.data(), blk.data(), tok.data(), nullptr)),
                ora_swap_out(ora, 1, ids.data(), off.data(), blk.data(), tok.data()), "block id out of range");
         } else if (which == 2 && free_list.size() > 2) {  // resuming a request nobody has heard of
           uint64_t id = 999;
           int32_t o2[2] = {0, 1}, dst[1] = {free_list.back()};
-          same(LIB(kv_swap_in(kp, 1, &id, o2, dst, 0, nullptr)), ora_swap_in(ora, 1, &id, o2, dst, 0), "swap-in of an unknown request");
+          same(LIB_ASYNC(kv_swap_in(kp, 1, &id, o2, dst, 0, nullptr)), ora_swap_in(ora, 1, &id, o2, dst, 0), "swap-in of an unknown request");
         } else if (which == 3 && !out.empty()) {  // writing through what is out
           const int r = out[0];
           int64_t o = 0;
@@ -665,7 +677,7 @@ int main(int argc, char** argv) {
           std::vector<int32_t> src(nb, 0);
           uint64_t id = (uint64_t)r;
           int32_t o2[2] = {0, (int32_t)nb}, t2[1] = {length[(size_t)r]}, ma[1], mb[1];
-          same(LIB(kv_swap_out_delta(kp, 1, &id, o2, src.data(), t2, 0, 0, mb, nullptr)),
+          same(LIB_ASYNC(kv_swap_out_delta(kp, 1, &id, o2, src.data(), t2, 0, 0, mb, nullptr)),
                ora_swap_out_delta(ora, 1, &id, o2, src.data(), t2, 0, 0, ma), "delta of a swapped-out request");
         }
       } else if (op == 10 && events && !running.empty()) {  // a control thread's poll: must not disturb anything

@@ -21,7 +21,7 @@ import os
 import numpy as np
 import pytest
 
-from hostpool import CANARY, HostPool
+from hostpool import CANARY, HostPool, sizes
 from oracle import kv_oracle as ko
 from paper_2510_02758_amd import workloads as W
 
@@ -55,7 +55,7 @@ def pin_closed_form(gname, layout, lib=None):
     for i in range(len(rid)):
         row = ids[off[i]:off[i + 1]]
         rc, q = ora.query(rid[i])
-        assert rc == ko.OK and q["offset"] == bases[i] * g.S and q["staged"] == len(row)
+        assert rc == ko.OK and q["offset"] == bases[i] * sizes(g).S and q["staged"] == len(row)
         assert q["wm"] == lens[i] // g.B and q["swapped"] == 1 and q["cap"] == len(row)
         got = sv[bases[i]: bases[i] + len(row)]
         assert np.array_equal(got, hp.block_image(row, pool0))
@@ -70,12 +70,12 @@ def pin_closed_form(gname, layout, lib=None):
         j, l, c = int(rng.integers(len(row))), int(rng.integers(g.L)), int(rng.integers(2))
         t, h, d = int(rng.integers(g.B)), int(rng.integers(g.H)), int(rng.integers(g.D))
         inner = ((t * g.H + h) * g.D + d) * g.e
-        st = (bases[i] + j) * g.S + (l * 2 + c) * g.chunk + inner
+        st = (bases[i] + j) * sizes(g).S + (l * 2 + c) * sizes(g).chunk + inner
         src = l * ls + c * ks + int(row[j]) * bs + inner
         assert np.array_equal(hp.staging[st:st + g.e], pool0[src:src + g.e])
         if g.scales:
             sls, sks, sbs = hp.scale_strides
-            st = (bases[i] + j) * g.S + g.block_bytes + (l * 2 + c) * g.H * 4 + h * 4
+            st = (bases[i] + j) * sizes(g).S + sizes(g).block_bytes + (l * 2 + c) * g.H * 4 + h * 4
             src = l * sls + c * sks + int(row[j]) * sbs + h * 4
             assert np.array_equal(hp.staging[st:st + 4], hp.scale[src:src + 4])
 
@@ -96,7 +96,7 @@ def pin_round_trip(gname, layout, lib=None):
     total = off[-1]
     assert ora.swap_out(rid, off, ids, lens) == ko.OK
     # arena: everything outside the extents is still canary
-    used = total * g.S
+    used = total * sizes(g).S
     assert (hp.staging[used:] == CANARY).all()
     # swap in to the SAME blocks: whole pool unchanged
     hp.pool[:] ^= 0  # no-op, keeps the array writable check honest
@@ -311,12 +311,12 @@ def pin_memcpy_case(gname, lib=None):
     ora = hp.oracle(lib)
     nb = 9
     assert ora.swap_out([77], [0, nb], np.arange(nb), [nb * g.B]) == ko.OK
-    n = nb * g.block_bytes
+    n = nb * sizes(g).block_bytes
     assert hp.staging[:n].tobytes() == hp.pool[:n].tobytes()  # one memcpy
     assert (hp.staging[n:] == CANARY).all()
     # and the way back: move the image somewhere else with one slice assignment
     expect = hp.pool.copy()
-    expect[20 * g.block_bytes: 20 * g.block_bytes + n] = hp.pool[:n]
+    expect[20 * sizes(g).block_bytes: 20 * sizes(g).block_bytes + n] = hp.pool[:n]
     assert ora.swap_in([77], [0, nb], np.arange(20, 20 + nb)) == ko.OK
     assert np.array_equal(hp.pool, expect)
 
@@ -388,9 +388,9 @@ def pin_errors(lib=None):
     assert ora.swap_out_delta([2], [0, 3], [10, 11, 12], [3 * B], budget=-1)[0] == ko.EINVAL and unchanged()
     # growth in place: request 2 owns slots 2..4; slot 5 is free, so 4 blocks fit ...
     assert ora.swap_out_delta([2], [0, 4], [10, 11, 12, 13], [4 * B])[0] == ko.OK
-    assert ora.query(2)[1] == dict(offset=2 * g.S, cap=4, staged=4, wm=4, swapped=0)
+    assert ora.query(2)[1] == dict(offset=2 * sizes(g).S, cap=4, staged=4, wm=4, swapped=0)
     # ... but once request 3 sits right behind it, it cannot grow further
-    assert ora.reserve(3, 1) == ko.OK and ora.query(3)[1]["offset"] == 6 * g.S
+    assert ora.reserve(3, 1) == ko.OK and ora.query(3)[1]["offset"] == 6 * sizes(g).S
     snap = _snapshot(hp, ora, known)
     assert ora.swap_out_delta([2], [0, 5], [10, 11, 12, 13, 14], [5 * B])[0] == ko.ENOSPC and unchanged()
     # move_blocks
@@ -464,7 +464,7 @@ def _run_script(path, lib=None):
             assert rc == ko.OK, line
         else:
             assert rc == ko.OK, line
-            assert ora.query(int(a[0]))[1]["offset"] == int(want) * g.S, line
+            assert ora.query(int(a[0]))[1]["offset"] == int(want) * sizes(g).S, line
 
 
 def pin_first_fit(lib=None):
@@ -522,3 +522,16 @@ PINS = [
     (pin_brute_force, (2, 2)), (pin_memcpy_case, ("tiny",)), (pin_errors, ()), (pin_move_blocks, ()),
     (pin_first_fit, ()), (pin_cycles, ()),
 ]
+
+
+def test_the_pins_sizes_and_the_generators_shapes_agree():
+    """The pins work out chunk, block and slot sizes themselves (hostpool.sizes); the input generator carries the same
+    definitions for the library's benefit.  A slip in either shows here."""
+    for g in (W.Geometry(2, 4, 64, 16, "f16", 10), W.Geometry(32, 8, 128, 16, "bf16", 10),
+              W.Geometry(32, 32, 128, 32, "fp8_e4m3", 10, scales=True), W.Geometry(80, 1, 128, 1, "bf16", 10)):
+        z = sizes(g)
+        assert (z.chunk, z.block_bytes, z.scale_chunk, z.block_scale_bytes, z.S) == \
+               (g.chunk, g.block_bytes, g.scale_chunk, g.block_scale_bytes, g.S)
+    assert sizes(W.Geometry(32, 8, 128, 16, "bf16", 10)).S == 2 << 20          # "2 MiB per block across layers, K+V"
+    assert sizes(W.Geometry(80, 8, 128, 16, "bf16", 10)).S == 5 << 20
+    assert sizes(W.Geometry(32, 32, 128, 32, "fp8_e4m3", 10, scales=True)).S == (8 << 20) + (8 << 10)
