@@ -127,7 +127,7 @@ def test_pipelined_resident_workgroups(gpu, variant, layout):
     """The experimental build with resident, software-pipelined workgroups (both ends in HBM, chunks that are a
     multiple of the piece): a workgroup cap of 7 makes every workgroup walk many pieces, 3 requests of a few blocks
     leave some workgroups with a single piece, and a launch with fewer pieces than workgroups leaves some with none."""
-    g = W.Geometry(3, 4, 64, 32, "bf16", 300)   # chunk = 32*4*64*2 = 16 KiB: 4, 2 or 1 pieces
+    g = W.Geometry(3, 4, 64, 32, "bf16", 700)   # chunk = 32*4*64*2 = 16 KiB: 4, 2 or 1 pieces
     assert g.chunk == 16384
     tune = ((kv.KV_TUNE_KERNEL_VARIANT, variant), (kv.KV_TUNE_SCATTER_ORDER, 1))
     run_both(g, 0x91BE + variant, layout, "device", 9, 32, 32 * 40, 6, tune=tune + ((kv.KV_TUNE_MAX_WGS_DEVICE, 7),))
