@@ -81,6 +81,7 @@ def headline(kv, W, BC, torch, dev, args, arena, streams):
     kp = kv.KVPool(g, pool, staging, bounce=bounce if args.path == "dma" else None, flags=flags,
                    evict_stream=evict, load_stream=load)
     kd = kv.KVPool(g, pool, dev_arena, flags=kv.KV_STAGING_DEVICE, evict_stream=evict, load_stream=load)
+    ok(kd.tune(kv.KV_TUNE_KERNEL_EVENTS, 1), "kv_pool_tune")      # ms_kernel of the on-device launches: the kernel alone
     torch.cuda.synchronize()
 
     # ---- ceilings, measured in this run ----

@@ -229,6 +229,7 @@ def config2(kv, W, torch, dev, args, arena=None, streams=None, steps=3):
     staging = pinned(torch, (total + n) * g.S, arena)
     kp = kv.KVPool(g, pool, staging, **skw)
     kd = kv.KVPool(g, pool, dev_arena, flags=kv.KV_STAGING_DEVICE, **skw)
+    ok(kv, kd.tune(kv.KV_TUNE_KERNEL_EVENTS, 1), "kv_pool_tune")
     link = ceilings(kv, torch, staging, dev)
     P = total * g.S
     acc = {k: [] for k in ("out", "in", "delta")}
@@ -779,15 +780,17 @@ def config8(kv, W, torch, dev, args, arena=None, streams=None):
     shapes = [
         ("fp8_scales", "configs[4] shape: fp8 + fp32 scales, L32 H32 D128 B32 (128 KiB chunks, 128-byte scale pieces): the build with "
                        "scale jobs, scatter of the side band through LDS", W.Geometry(32, 32, 128, 32, "fp8_e4m3", 6144, scales=True), 2048),
-        ("one_kv_head_4KiB_chunks", "a tensor-parallel shard of the 70B shape: bf16 L80 H1 D128 B16 (4 KiB chunks, one piece each)",
+        ("one_kv_head_4KiB_chunks", "a tensor-parallel shard of the 70B shape: bf16 L80 H1 D128 B16 (4 KiB chunks, one piece each: the lean build at its smallest chunk)",
          W.Geometry(80, 1, 128, 16, "bf16", 98304), 24576),
-        ("token_level_256B_chunks", "a token-level pool: bf16 L32 H1 D128 B1 (256-byte chunks, 16 chunks per workgroup pass)",
+        ("token_level_256B_chunks", "a token-level pool: bf16 L32 H1 D128 B1 (256-byte chunks, four groups of 16 chunks per workgroup)",
          W.Geometry(32, 1, 128, 1, "bf16", 1 << 20), 1 << 18),
     ]
     out = {"config": 8, "peak_gbps": HBM_PEAK_GBS, "kernels": {}}
     warm = torch.empty(8 << 30, dtype=torch.uint8, device=dev)
     kv.kv_bench_copy(warm[4 << 30:].data_ptr(), warm.data_ptr(), 4 << 30, 0, 40)     # memory clocks up
+    builds = {"fp8_scales": "1,0,false,false", "one_kv_head_4KiB_chunks": "1,0,true,false", "token_level_256B_chunks": "4,0,false,false"}
     for name, what, g, nblk in shapes:
+        build = builds[name]
         pool = torch.empty(g.pool_bytes, dtype=torch.uint8, device=dev)
         scale = torch.empty(g.scale_bytes, dtype=torch.uint8, device=dev) if g.scales else None
         W.fill_buffer_torch(0x5EED0800, pool, g.dtype)
@@ -799,6 +802,8 @@ def config8(kv, W, torch, dev, args, arena=None, streams=None):
         rid = np.array([1], np.uint64)
         lens = np.array([nblk * g.B], np.int32)
         kd = kv.KVPool(g, pool, arena_d, scale=scale, flags=kv.KV_STAGING_DEVICE, **skw)
+        ok(kv, kd.tune(kv.KV_TUNE_KERNEL_EVENTS, 1), "kv_pool_tune")     # ms_kernel: the kernel alone, no descriptor upload
+        ok(kv, kd.tune(kv.KV_TUNE_SCATTER_ORDER, 1), "kv_pool_tune")     # one job order throughout
         gk, sk = [], []
         for it in range(6):
             ok(kv, kd.swap_out(rid, off, ids, lens), "kv_swap_out(device arena)")
@@ -811,16 +816,16 @@ def config8(kv, W, torch, dev, args, arena=None, streams=None):
                 sk.append(si["ms_kernel"])
         P = nblk * g.S
         # scrambled plain copy over the largest power-of-two part of the same buffers
-        run = max(4096, g.chunk)
+        run = g.chunk                                  # a power of two for the three shapes
         nbytes = 1 << int(np.floor(np.log2(min(P, pool.numel()))))
         src_c = kv.kv_bench_copy_scrambled(arena_d.data_ptr(), pool.data_ptr(), nbytes, run, 0, 3)
         dst_c = kv.kv_bench_copy_scrambled(pool.data_ptr(), arena_d.data_ptr(), nbytes, run, 1, 3)
         gg, ss = 2 * P / float(np.mean(gk)) / 1e6, 2 * P / float(np.mean(sk)) / 1e6
         out["kernels"][name] = {
             "what": what, "blocks": nblk, "payload_gib": round(P / 2**30, 2), "bytes_per_launch": 2 * P,
-            "gather": {"kernel": "kv_move_kernel<0,1,0,false,false>", "launch_ms": round(float(np.mean(gk)), 3),
+            "gather": {"kernel": "kv_move_kernel<0,%s>" % build, "launch_ms": round(float(np.mean(gk)), 3),
                        "achieved": round(gg, 1), "frac": round(gg / HBM_PEAK_GBS, 4)},
-            "scatter": {"kernel": "kv_move_kernel<1,1,0,false,false>", "launch_ms": round(float(np.mean(sk)), 3),
+            "scatter": {"kernel": "kv_move_kernel<1,%s>" % build, "launch_ms": round(float(np.mean(sk)), 3),
                         "achieved": round(ss, 1), "frac": round(ss / HBM_PEAK_GBS, 4)},
             "scrambled_copy_ceiling_gbps": {"run_bytes": run, "source_scrambled": round(2 * nbytes / src_c / 1e6, 1),
                                             "destination_scrambled": round(2 * nbytes / dst_c / 1e6, 1)}}

@@ -370,6 +370,9 @@ enum {
   KV_TUNE_PHASE_WGS_IN = 11,    /* kv_evict_and_load: workgroups of a load phase (default 128: with both directions of
                                    the link busy each kernel needs more requests in flight than alone, and the two do
                                    best with equal counts) */
+  KV_TUNE_KERNEL_EVENTS = 12,   /* 1: every data kernel is bracketed by its own pair of events, so that kv_stats.ms_kernel
+                                   is the kernel alone also for a call that is a single launch (otherwise such a call
+                                   reports its whole stream time, descriptor upload included); for measurements */
   KV_TUNE_SEGMENT_MAX_BYTES = 7 /* under KV_REQ_EVENTS: also cut a segment inside a long request once it reaches this
                                    many bytes (0, the default: only at request ends).  Smaller segments let a swap-in
                                    follow closer behind an eviction whose blocks it reuses, at one launch each */

@@ -914,6 +914,9 @@ int kv_pool_tune(kv_pool* p, int32_t what, int64_t value) try {
     case KV_TUNE_SEGMENT_MAX_BYTES:
       p->segment_max_bytes = value;
       return KV_OK;
+    case KV_TUNE_KERNEL_EVENTS:
+      p->kernel_events = value ? 1 : 0;
+      return KV_OK;
     case KV_TUNE_PHASE_BYTES:
       p->phase_bytes = value ? value : 256ll << 20;
       return KV_OK;
