@@ -141,7 +141,10 @@ typedef struct {
   void* bounce_dev; /* optional, for KV_PATH_DMA; first half serves swap-out, second swap-in */
   int64_t bounce_bytes;
   void* evict_stream; /* hipStream_t; NULL: the library creates and owns one */
-  void* load_stream;  /* hipStream_t; NULL: the library creates and owns one */
+  void* load_stream;  /* hipStream_t; NULL: the library creates and owns one.  Eviction and loading overlap (Section 5.3)
+                         only when the two streams sit on different hardware queues.  HIP gives a process a small number of
+                         them (GPU_MAX_HW_QUEUES, four by default) and lets further streams share: a process that has
+                         created other streams before should pass two streams it created, and used, early */
   uint32_t flags;
 } kv_pool_config;
 
@@ -384,7 +387,8 @@ const char* kv_strerror(int code);
 
 /* ------------------------------------------------------------ measurement helpers
  * Ceilings the swap is compared against (the paper prints no bandwidth figure; Section 5.2 only asks that
- * writes use the link fully, so the link's own measured rate is the yardstick); no pool handle needed.  All four are synchronous and return the mean milliseconds per iteration, or
+ * writes use the link fully, so the link's own measured rate is the yardstick); no pool handle needed.  All four are
+ * synchronous and return the mean milliseconds per iteration, or
  * a negative number for bad arguments (-1), a failed HIP resource (-2) or a failed wait (-3).
  *   kv_bench_copy        contiguous device-to-device copy kernel of `bytes` (multiple of 16 KiB) on `stream`:
  *                        the HBM copy ceiling.  grid 0: one workgroup per 4 KiB piece (the launch shape of
