@@ -373,6 +373,9 @@ enum {
   KV_TUNE_PHASE_WGS_IN = 11,    /* kv_evict_and_load: workgroups of a load phase (default 128: with both directions of
                                    the link busy each kernel needs more requests in flight than alone, and the two do
                                    best with equal counts) */
+  KV_TUNE_HOST_STORES = 13,     /* zero-copy gather into the host arena: 0 (default) each lane writes 64 consecutive bytes with
+                                   ordinary stores that L2 merges into full lines; 1 whole 128-byte lines per store instruction,
+                                   non-temporal */
   KV_TUNE_KERNEL_EVENTS = 12,   /* 1: every data kernel is bracketed by its own pair of events, so that kv_stats.ms_kernel
                                    is the kernel alone also for a call that is a single launch (otherwise such a call
                                    reports its whole stream time, descriptor upload included); for measurements */

@@ -914,6 +914,10 @@ int kv_pool_tune(kv_pool* p, int32_t what, int64_t value) try {
     case KV_TUNE_SEGMENT_MAX_BYTES:
       p->segment_max_bytes = value;
       return KV_OK;
+    case KV_TUNE_HOST_STORES:
+      if (value > 1) return KV_EINVAL;
+      p->host_stores_nt = value;
+      return KV_OK;
     case KV_TUNE_KERNEL_EVENTS:
       p->kernel_events = value ? 1 : 0;
       return KV_OK;

@@ -211,6 +211,7 @@ int main(int argc, char** argv) {
   kv_pool_tune(kp, KV_TUNE_PHASE_BYTES, rnd(1, 3) * g.S);  // eviction and loading in one call: phases of one to three blocks
   if (rnd(0, 1)) kv_pool_tune(kp, KV_TUNE_PHASE_WGS_IN, rnd(1, 6));
   if (rnd(0, 2) == 0) kv_pool_tune(kp, KV_TUNE_MAX_WGS_LINK, rnd(1, 5));
+  if (mode == 0 && rnd(0, 1)) kv_pool_tune(kp, KV_TUNE_HOST_STORES, 1);  // the other lane layout of the gather into the host arena
   if (rnd(0, 2) == 0) kv_pool_tune(kp, KV_TUNE_MAX_WGS_DEVICE, rnd(1, 7));
   if (mode == 1 && rnd(0, 1)) kv_pool_tune(kp, KV_TUNE_DMA_SLICE_BLOCKS, rnd(1, 3));
   if (mode == 2 && rnd(0, 1)) kv_pool_tune(kp, KV_TUNE_SCATTER_ORDER, 2);  // the plane-by-plane build of the scatter

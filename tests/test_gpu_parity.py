@@ -121,6 +121,17 @@ def test_every_piece_size(gpu, path, unroll):
     run_both(g, 0xBEE + unroll, "layer", path, 5, 4, 40, 3, tune=tune)
 
 
+@pytest.mark.parametrize("unroll", [0, 1, 2, 8])
+def test_whole_line_host_stores(gpu, unroll):
+    """KV_TUNE_HOST_STORES 1: the gather into the host arena writes whole 128-byte lines per store instruction with
+    non-temporal stores instead of 64 consecutive bytes per lane; ragged pieces, every piece size, small chunks."""
+    tune = ((kv.KV_TUNE_HOST_STORES, 1),) + (((kv.KV_TUNE_KERNEL_VARIANT, unroll),) if unroll else ())
+    run_both(W.Geometry(2, 2, 1160, 8, "bf16", 80), 0x7057 + unroll, "layer", "zerocopy", 5, 4, 40, 3, tune=tune)
+    run_both(W.Geometry(3, 1, 5132, 2, "bf16", 96), 0x7058 + unroll, "padded", "zerocopy", 6, 2, 24, 4,
+             tune=tune + ((kv.KV_TUNE_MAX_WGS_LINK, 3),))
+    run_both(W.Geometry(7, 2, 64, 4, "bf16", 300), 0x7059 + unroll, "layer", "zerocopy", 9, 4, 100, 6, tune=tune)
+
+
 @pytest.mark.parametrize("variant", [101, 102, 104])
 @pytest.mark.parametrize("layout", ["layer", "padded"])
 def test_pipelined_resident_workgroups(gpu, variant, layout):
