@@ -373,6 +373,8 @@ enum {
   KV_TUNE_PHASE_WGS_IN = 11,    /* kv_evict_and_load: workgroups of a load phase (default 128: with both directions of
                                    the link busy each kernel needs more requests in flight than alone, and the two do
                                    best with equal counts) */
+  KV_TUNE_LINK_IN_WGS = 14,     /* workgroups of the scatter out of the host arena alone (0: as KV_TUNE_MAX_WGS_LINK) */
+  KV_TUNE_LINK_IN_UNROLL = 15,  /* 16-byte loads in flight per lane of that scatter: 1, 2, 4, 8 (0: by chunk size) */
   KV_TUNE_HOST_STORES = 13,     /* zero-copy gather into the host arena: 0 (default) each lane writes 64 consecutive bytes with
                                    ordinary stores that L2 merges into full lines; 1 whole 128-byte lines per store instruction,
                                    non-temporal */

@@ -914,6 +914,13 @@ int kv_pool_tune(kv_pool* p, int32_t what, int64_t value) try {
     case KV_TUNE_SEGMENT_MAX_BYTES:
       p->segment_max_bytes = value;
       return KV_OK;
+    case KV_TUNE_LINK_IN_WGS:
+      p->link_in_wgs = std::min<int64_t>(value, 1 << 30);
+      return KV_OK;
+    case KV_TUNE_LINK_IN_UNROLL:
+      if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8) return KV_EINVAL;
+      p->link_in_unroll = value;
+      return KV_OK;
     case KV_TUNE_HOST_STORES:
       if (value > 1) return KV_EINVAL;
       p->host_stores_nt = value;

@@ -30,6 +30,7 @@ KV_TUNE_SCATTER_ORDER = 8
 KV_TUNE_PHASE_BYTES, KV_TUNE_PHASE_WGS_OUT, KV_TUNE_PHASE_WGS_IN = 9, 10, 11
 KV_TUNE_KERNEL_EVENTS = 12
 KV_TUNE_HOST_STORES = 13
+KV_TUNE_LINK_IN_WGS, KV_TUNE_LINK_IN_UNROLL = 14, 15
 KV_F16, KV_BF16, KV_FP8_E4M3 = 0, 1, 2
 
 EXPORTS = ["kv_pool_create", "kv_pool_destroy", "kv_swap_out", "kv_swap_out_delta", "kv_swap_in", "kv_evict_and_load", "kv_sync",
