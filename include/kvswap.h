@@ -220,8 +220,8 @@ int kv_swap_in(kv_pool* p, int32_t n, const uint64_t* req_ids, const int32_t* of
  * zero-copy path the two transfers are cut into phases of KV_TUNE_PHASE_BYTES (256 MiB) and interleaved on the two
  * streams so that one eviction kernel and one load kernel always start together, each load phase waiting only for
  * the eviction phase that frees its blocks; per-request completion (kv_req_poll / kv_req_wait) follows the phases.
- * On the copy-engine path and under KV_PLAN_ONLY it is the two calls one after the other.  kv_last_stats afterwards
- * reports the load.
+ * On the copy-engine path and under KV_PLAN_ONLY it is the two calls one after the other.  kv_last_stats and
+ * kv_last_plan afterwards report the load.
  * Errors: those of kv_swap_out and kv_swap_in. */
 int kv_evict_and_load(kv_pool* p, int32_t n_out, const uint64_t* out_ids, const int32_t* out_offsets,
                       const int32_t* out_block_ids, const int32_t* out_tokens, int32_t n_in, const uint64_t* in_ids,

@@ -378,8 +378,7 @@ int kv_evict_and_load(kv_pool* p, int32_t n_out, const uint64_t* out_ids, const 
       }
       for (int32_t i = 0; i < n_out; i++) p->wq.erase(out_ids[i]);
       for (int32_t i = 0; i < n_in; i++) p->wq.erase(in_ids[i]);
-      p->last_plan = po.desc;
-      p->last_plan.insert(p->last_plan.end(), pi.desc.begin(), pi.desc.end());
+      p->last_plan = pi.desc;  // as after the two calls made one after the other: the load's list
       const double t1 = now_us();
       if (!po.desc.empty() && !pi.desc.empty()) {
         const uint64_t dep_out = std::max(cross_stream(p, kEvict, po.wait_in_seq), pending_user(p, kEvict, po.fresh));

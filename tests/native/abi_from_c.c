@@ -1,5 +1,6 @@
 /* The C ABI used from plain C99, without a GPU: a plan-only pool (no HIP call is made), one swap-out,
- * a budgeted write-through, a swap-in, and one scheduling round.  Built and run by
+ * a budgeted write-through, a swap-in, eviction and loading in one call, the allocation-free move,
+ * and one scheduling round.  Built and run by
  * tests/test_native_sanitizers.py; exits 0 when every call answers as the headers say. */
 #include <stdio.h>
 #include <string.h>
@@ -59,6 +60,27 @@ int main(void) {
       CHECK(kv_swap_in(p, 1, ids, roff, dst_dup, 0, NULL) == KV_EDUP);
       CHECK(kv_swap_in(p, 1, ids, roff, dst, 0, NULL) == KV_OK);
       CHECK(kv_req_query(p, 7, NULL, NULL, NULL, NULL, NULL) == KV_ENOENT);
+    }
+    {
+      /* eviction and loading in one call: request 9 goes out while request 8, swapped out first, comes back into the
+       * blocks request 9 gives up; the load is checked before the eviction changes anything */
+      const uint64_t nine = 9, eight = 8, nobody = 77;
+      const int32_t off9[2] = {0, 3}, blk9[3] = {20, 21, 22}, tok9[1] = {12};
+      const int32_t off8[2] = {0, 3};
+      const int32_t src[2] = {4, 4}, dst[2] = {10, 11}, dst_bad[2] = {10, 4};
+      CHECK(kv_swap_out(p, 1, ids + 1, off + 1, blk, tok + 1, NULL) == KV_OK);
+      CHECK(kv_evict_and_load(p, 1, &nine, off9, blk9, tok9, 1, &nobody, off8, blk9, 0, NULL) == KV_ENOENT);
+      CHECK(kv_req_query(p, 9, NULL, NULL, NULL, NULL, NULL) == KV_ENOENT);
+      CHECK(kv_evict_and_load(p, 1, &nine, off9, blk9, tok9, 1, &nine, off9, blk9, 0, NULL) == KV_EINVAL);
+      CHECK(kv_evict_and_load(p, 1, &nine, off9, blk9, tok9, 1, &eight, off8, blk9, KV_KEEP_STAGING, NULL) == KV_OK);
+      CHECK(kv_last_plan(p, phys, slot, 8) == 3 && phys[0] == 20 && phys[2] == 22);
+      CHECK(kv_req_query(p, 9, NULL, NULL, &staged, &wm, &swapped) == KV_OK && staged == 3 && swapped == 1);
+      CHECK(kv_req_query(p, 8, NULL, NULL, &staged, &wm, &swapped) == KV_OK && staged == 3 && swapped == 0);
+      /* the move for callers that cannot allocate: same checks as kv_move_blocks, and a limit of its own */
+      CHECK(kv_move_blocks_noalloc(p, 2, src, dst, NULL) == KV_OK);
+      CHECK(kv_move_blocks_noalloc(p, 2, src, dst_bad, NULL) == KV_EDUP);
+      CHECK(kv_move_blocks_noalloc(p, (int64_t)KV_NOALLOC_MAX_BLOCKS + 1, src, dst, NULL) == KV_E2BIG);
+      CHECK(kv_move_blocks(p, 2, src, dst_bad, NULL) == KV_EDUP);
     }
     CHECK(kv_sync(p) == KV_OK);
     CHECK(strcmp(kv_strerror(KV_ENOSPC), "staging arena full") == 0);
