@@ -240,8 +240,8 @@ int kv_move_blocks(kv_pool* p, int64_t n, const int32_t* src_ids, const int32_t*
 
 /* kv_move_blocks for callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses
  * that forbid hipMalloc.  Same arguments, same result in the pool, same kernel.  The call makes no hipMalloc,
- * hipFree, hipHostMalloc, event or stream creation and no host-heap allocation: its descriptors travel through a
- * pinned buffer the handle owns since kv_pool_create into a fixed device array that is part of the library's code
+ * hipFree, hipHostMalloc, event or stream creation and no host-heap allocation: its descriptors travel inside the
+ * arguments of small fill launches (448 per launch) into a fixed device array that is part of the library's code
  * object (KV_NOALLOC_MAX_BLOCKS descriptors of 8 bytes = 512 KiB per GPU, held until the process ends).
  *   - n > KV_NOALLOC_MAX_BLOCKS returns KV_E2BIG and does nothing; split the list.
  *   - Runs on the evict stream after everything enqueued on either stream of this handle before it; load-stream
@@ -250,8 +250,7 @@ int kv_move_blocks(kv_pool* p, int64_t n, const int32_t* src_ids, const int32_t*
  *     Calls through DIFFERENT handles on the same GPU that overlap in time race for the array: the caller must
  *     order them (kv_sync, events).  The array keeps the last call's descriptors; each call overwrites the part
  *     it reads, nothing has to start at zero.
- *   - The host may wait inside the call for the descriptor upload of the call before the previous one (two
- *     pinned buffers take turns), never for a kernel.
+ *   - The call never waits for the device on the host.
  *   - kv_last_stats afterwards reports blocks, bytes, grid and host times, no stream times (no events are taken).
  * Errors: KV_EINVAL, KV_ERANGE, KV_EDUP as kv_move_blocks; KV_E2BIG; KV_EHIP. */
 #define KV_NOALLOC_MAX_BLOCKS 65536

@@ -53,16 +53,12 @@ hipError_t scratch_on_current_device(Desc** out, int* dev_out) {
 }  // namespace
 
 // Everything kv_move_blocks_noalloc will need, taken once when the handle is created: the address of the
-// descriptor array on this GPU, two pinned upload buffers, four events and the duplicate bitmap.
+// descriptor array on this GPU, two events and the duplicate bitmap.
 static int noalloc_setup(kv_pool* p) {
   hipError_t e = scratch_on_current_device(&p->na_dev, &p->device);
   if (e != hipSuccess) {
     p->last_hip = (int)e;
     return KV_EHIP;
-  }
-  for (int i = 0; i < 2; i++) {
-    HIPCHK(p, hipHostMalloc((void**)&p->na_host[i], (size_t)KV_NOALLOC_MAX_BLOCKS * sizeof(Desc), hipHostMallocDefault));
-    HIPCHK(p, hipEventCreate(&p->na_up_ev[i]));
   }
   HIPCHK(p, hipEventCreate(&p->na_fence_ev));
   HIPCHK(p, hipEventCreate(&p->na_done_ev));
@@ -227,10 +223,6 @@ int kv_pool_destroy(kv_pool* p) try {
     for (auto ev : p->ev_free) (void)hipEventDestroy(ev);
     if (p->ring_host) (void)hipHostFree(p->ring_host);
     if (p->ring_dev) (void)hipFree(p->ring_dev);
-    for (int i = 0; i < 2; i++) {
-      if (p->na_host[i]) (void)hipHostFree(p->na_host[i]);
-      if (p->na_up_ev[i]) (void)hipEventDestroy(p->na_up_ev[i]);
-    }
     if (p->na_fence_ev) (void)hipEventDestroy(p->na_fence_ev);
     if (p->na_done_ev) (void)hipEventDestroy(p->na_done_ev);
     for (int s = 0; s < 2; s++)
@@ -455,10 +447,9 @@ int kv_move_blocks(kv_pool* p, int64_t n, const int32_t* src_ids, const int32_t*
 KV_CATCH(p)
 
 // kv_move_blocks for callers that cannot allocate.  Uses only what kv_pool_create set up: no hipMalloc, hipFree,
-// hipHostMalloc, event or stream creation, and no host heap either (the descriptors are written straight into a
-// pinned buffer of the handle, duplicates are found with the handle's bitmap).  The kernel is the one
-// kv_move_blocks launches; it reads its descriptors from the library's fixed device array instead of the
-// growable ring.
+// hipHostMalloc, event or stream creation, and no host heap either (the descriptors travel inside kernel
+// arguments, duplicates are found with the handle's bitmap).  The kernel is the one kv_move_blocks launches; it
+// reads its descriptors from the library's fixed device array instead of the growable ring.
 int kv_move_blocks_noalloc(kv_pool* p, int64_t n, const int32_t* src_ids, const int32_t* dst_ids, void* wait_event) try {
   if (!p) return KV_EINVAL;
   KV_ENTER(p);
@@ -500,15 +491,17 @@ int kv_move_blocks_noalloc(kv_pool* p, int64_t n, const int32_t* src_ids, const 
   hipEvent_t callers = (hipEvent_t)wait_event;
   if (callers) HIPCHK(p, hipStreamWaitEvent(st, callers, 0));
   if (n > 0) {
-    const int slot = (int)(p->na_calls++ & 1);
-    if (p->na_up_used[slot]) HIPCHK(p, hipEventSynchronize(p->na_up_ev[slot]));  // the upload of two calls ago has left this buffer
-    Desc* h = p->na_host[slot];
-    for (int64_t i = 0; i < n; i++) h[i] = {src_ids[i], dst_ids[i]};
-    // the array keeps the previous call's descriptors: [0, n) is overwritten here, in stream order behind the
-    // previous call's kernel, and nothing beyond n is read
-    HIPCHK(p, hipMemcpyAsync(p->na_dev, h, (size_t)n * sizeof(Desc), hipMemcpyHostToDevice, st));
-    HIPCHK(p, hipEventRecord(p->na_up_ev[slot], st));
-    p->na_up_used[slot] = true;
+    // The descriptors go into the fixed array in batches that travel as kernel arguments: nothing on the host has to
+    // outlive this call, so it never waits for an earlier one.  The array keeps the previous call's descriptors:
+    // [0, n) is overwritten here, in stream order behind the previous call's kernel, and nothing beyond n is read.
+    (void)hipGetLastError();
+    DescPack pack;
+    for (int64_t at = 0; at < n; at += kDescPack) {
+      const int m = (int)std::min<int64_t>(kDescPack, n - at);
+      for (int i = 0; i < m; i++) pack.d[i] = {src_ids[at + i], dst_ids[at + i]};
+      hipLaunchKernelGGL(kv_desc_fill_kernel, dim3(1), dim3(512), 0, st, p->na_dev, at, m, pack);
+    }
+    HIPCHK(p, hipGetLastError());
     MoveArgs a;
     int u = 1;
     const int grid = build_move_args(p, 2, (size_t)n, nullptr, 0, false, &a, &u);

@@ -554,7 +554,7 @@ int main(int argc, char** argv) {
           // the entry point for callers that cannot allocate: same result, and the HIP runtime is asked for no memory,
           // event or stream while it runs (the stand-in's own queues use the host heap, so that is not counted)
           const long res0 = mockhip::resource_calls();
-          both(LIB(kv_move_blocks_noalloc(kp, (int64_t)k, src.data(), dst.data(), after_model)),
+          both(LIB_ASYNC(kv_move_blocks_noalloc(kp, (int64_t)k, src.data(), dst.data(), after_model)),
                ora_move_blocks(ora, (int64_t)k, src.data(), dst.data()), "move without allocation", chunk, step);
           if (mockhip::resource_calls() != res0) die("kv_move_blocks_noalloc allocated", chunk, step);
         } else

@@ -1,7 +1,8 @@
 """Random serving histories on the GPU with no host synchronisation inside them.
 
 A seeded driver plays a few hundred operations (growth with budgeted write-through, cold and warm
-preemption, resumption into the most recently freed blocks, compaction moves, releases) against the
+preemption, resumption into the most recently freed blocks, eviction and loading in one call, compaction moves
+with and without allocation, releases) against the
 library, enqueuing everything back to back; blocks given up by one call are handed to the next one at
 once, so that almost every call depends on unfinished work of the other stream.  The oracle runs the
 same history call by call.  Pool and arena must be equal byte for byte at the end of every chunk of the
@@ -44,7 +45,7 @@ class History:
         out = [r for r in self.table if self.state[r] == "out"]
         idle = [r for r in self.table if self.state[r] == "idle"]
         op = rng.choice(["start", "grow", "grow", "preempt_warm", "preempt_cold", "resume", "resume", "move", "finish",
-                         "preempt_many", "resume_many"])
+                         "preempt_many", "resume_many", "evict_and_load", "evict_and_load", "move_noalloc"])
         if op == "start" and idle and len(self.free) > 8:
             r = int(rng.choice(idle))
             both(lambda o: o.reserve(r, self.cap))
@@ -113,14 +114,44 @@ class History:
             both(lambda o: o.swap_in(rs, off, blk, kv.KV_KEEP_STAGING))
             for r in rs:
                 self.state[r] = "running"
-        elif op == "move" and running:
+        elif op == "evict_and_load" and out and [r for r in running if self.table[r]]:
+            # one or two running requests are evicted cold and, in the same call, one or two others come back: the
+            # blocks the evicted ones give up are the first the resumed ones get, in any order
+            ev = [int(r) for r in rng.permutation([r for r in running if self.table[r]])[: int(rng.integers(1, 3))]]
+            avail = [b for r in ev for b in self.table[r]]
+            if rng.random() < 0.5:
+                avail = [int(x) for x in rng.permutation(avail)]
+            ld, need = [], 0
+            for r in rng.permutation(out):
+                nb = -(-self.length[int(r)] // g.B)
+                if len(ld) < 2 and need + nb <= len(avail) + len(self.free):
+                    ld.append(int(r))
+                    need += nb
+            if not ld:
+                return
+            off_o, blk_o = self.csr(ev)
+            tok_o = [self.length[r] for r in ev]
+            for r in ld:
+                nb = -(-self.length[r] // g.B)
+                self.table[r] = [avail.pop(0) if avail else self.free.pop() for _ in range(nb)]
+            off_i, blk_i = self.csr(ld)
+            both(lambda o: o.evict_and_load(ev, off_o, blk_o, tok_o, ld, off_i, blk_i, kv.KV_KEEP_STAGING))
+            self.free.extend(avail)                          # what the load did not take
+            for r in ev:
+                self.table[r], self.state[r] = [], "out"
+            for r in ld:
+                self.state[r] = "running"
+        elif op in ("move", "move_noalloc") and running:
             r = int(rng.choice(running))
             k = min(len(self.table[r]), len(self.free), int(rng.integers(1, 5)))
             if k == 0:
                 return
             src = self.table[r][:k]
             dst = [self.free.pop() for _ in range(k)]
-            both(lambda o: o.move_blocks(np.array(src, np.int32), np.array(dst, np.int32)))
+            if op == "move_noalloc":
+                both(lambda o: o.move_blocks_noalloc(np.array(src, np.int32), np.array(dst, np.int32)))
+            else:
+                both(lambda o: o.move_blocks(np.array(src, np.int32), np.array(dst, np.int32)))
             self.table[r][:k] = dst
             self.free.extend(src)
         elif op == "finish" and (running or out):
@@ -136,7 +167,7 @@ class Both:
     the library has been handed all of it: nothing on the host slows the enqueuing down."""
 
     def __init__(self, kp, ora):
-        self.kp, self.ora, self.calls, self.todo = _Lib(kp), ora, 0, []
+        self.kp, self.ora, self.calls, self.todo = _Lib(kp), _Ora(ora), 0, []
 
     def __call__(self, fn):
         rc = fn(self.kp)
@@ -175,6 +206,30 @@ class _Lib:
     def move_blocks(self, src, dst):
         return self.kp.move_blocks(src, dst)
 
+    def move_blocks_noalloc(self, src, dst):
+        return self.kp.move_blocks_noalloc(src, dst)
+
+    def evict_and_load(self, *a):
+        return self.kp.evict_and_load(*a)
+
+
+class _Ora:
+    """The oracle, with the two calls that are defined through others written out: eviction and loading in one call
+    is swap-out followed by swap-in, the allocation-free move is the move."""
+
+    def __init__(self, ora):
+        self.ora = ora
+
+    def __getattr__(self, name):
+        return getattr(self.ora, name)
+
+    def move_blocks_noalloc(self, src, dst):
+        return self.ora.move_blocks(src, dst)
+
+    def evict_and_load(self, ev, off_o, blk_o, tok_o, ld, off_i, blk_i, flags):
+        rc = self.ora.swap_out(ev, off_o, blk_o, tok_o)
+        return rc if rc else self.ora.swap_in(ld, off_i, blk_i, flags)
+
 
 @pytest.mark.parametrize("seed", [1, 3])
 @pytest.mark.parametrize("mode", ["zerocopy", "dma", "events", "dma_events", "device_events"])
@@ -201,6 +256,7 @@ def test_random_history_without_host_sync(gpu, mode, seed):
     t1.record()
     t1.synchronize()
     spin = int(150.0 / max(t0.elapsed_time(t1), 1e-3) * 20_000_000)
+    assert kp.tune(kv.KV_TUNE_PHASE_BYTES, 2 * g.S) == kv.KV_OK      # eviction and loading in one call: phases of two blocks
     if "events" in mode:
         assert kp.tune(kv.KV_TUNE_SEGMENT_BYTES, 2 * g.S) == kv.KV_OK
         assert kp.tune(kv.KV_TUNE_SEGMENT_MAX_BYTES, 3 * g.S) == kv.KV_OK

@@ -37,7 +37,7 @@ def test_noalloc_move_equals_move_blocks(gpu, shape):
     host_scale = W.fill_buffer_np(seed ^ 0x5CA1E, g.scale_bytes, "raw") if g.scales else None
     rng = np.random.default_rng(11)
     first = _moves(rng, g.N, 700 if g.N >= 1500 else 400)
-    second = _moves(rng, g.N, 37)                            # smaller, and above the 8 descriptors that travel inline
+    second = _moves(rng, g.N, 37)                            # smaller: the array still holds the tail of the first list
 
     # the oracle, one call after the other
     ora_pool = host_pool.copy()
