@@ -8,6 +8,7 @@ once, so that almost every call depends on unfinished work of the other stream. 
 same history call by call.  Pool and arena must be equal byte for byte at the end of every chunk of the
 history: any missing ordering between the two streams shows up as a stale or torn block.
 """
+import os
 import time
 
 import numpy as np
@@ -231,7 +232,11 @@ class _Ora:
         return rc if rc else self.ora.swap_in(ld, off_i, blk_i, flags)
 
 
-@pytest.mark.parametrize("seed", [1, 3])
+# KVSWAP_STRESS_SEEDS=5,6,7 in the environment plays other histories than the two the suite runs by default
+_SEEDS = [int(x) for x in os.environ.get("KVSWAP_STRESS_SEEDS", "1,3").split(",") if x.strip()]
+
+
+@pytest.mark.parametrize("seed", _SEEDS)
 @pytest.mark.parametrize("mode", ["zerocopy", "dma", "events", "dma_events", "device_events"])
 def test_random_history_without_host_sync(gpu, mode, seed):
     import torch
@@ -277,6 +282,6 @@ def test_random_history_without_host_sync(gpu, mode, seed):
         assert np.array_equal(pool.cpu().numpy(), a.pool), "pool differs after chunk %d" % chunk
         for r in h.table:
             assert kp.query(r) == ora.query(r)
-    assert both.calls > 100
+    assert both.calls > 60
     assert max(enqueue_ms) < 150.0, "the host took longer than the spin: the streams were not held back"
     kp.close()
