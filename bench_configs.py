@@ -778,17 +778,18 @@ def config8(kv, W, torch, dev, args, arena=None, streams=None):
     streams = streams or Streams(torch)
     skw = streams.kw()
     shapes = [
-        ("fp8_scales", "configs[4] shape: fp8 + fp32 scales, L32 H32 D128 B32 (128 KiB chunks, 128-byte scale pieces): the build with "
-                       "scale jobs, scatter of the side band through LDS", W.Geometry(32, 32, 128, 32, "fp8_e4m3", 6144, scales=True), 2048),
+        ("fp8_scales", "configs[4] shape: fp8 + fp32 scales, L32 H32 D128 B32 (128 KiB chunks, 128-byte scale pieces): two launches, the "
+                       "lean build over the data and the general build over the scale jobs (scatter of the side band through LDS)", W.Geometry(32, 32, 128, 32, "fp8_e4m3", 6144, scales=True), 2048),
         ("one_kv_head_4KiB_chunks", "a tensor-parallel shard of the 70B shape: bf16 L80 H1 D128 B16 (4 KiB chunks, one piece each: the lean build at its smallest chunk)",
          W.Geometry(80, 1, 128, 16, "bf16", 98304), 24576),
-        ("token_level_256B_chunks", "a token-level pool: bf16 L32 H1 D128 B1 (256-byte chunks, four groups of 16 chunks per workgroup)",
+        ("token_level_256B_chunks", "a token-level pool: bf16 L32 H1 D128 B1 (256-byte chunks, four groups of 16 chunks per workgroup: the small-chunk kernel)",
          W.Geometry(32, 1, 128, 1, "bf16", 1 << 20), 1 << 18),
     ]
     out = {"config": 8, "peak_gbps": HBM_PEAK_GBS, "kernels": {}}
     warm = torch.empty(8 << 30, dtype=torch.uint8, device=dev)
     kv.kv_bench_copy(warm[4 << 30:].data_ptr(), warm.data_ptr(), 4 << 30, 0, 40)     # memory clocks up
-    builds = {"fp8_scales": "1,0,false,false", "one_kv_head_4KiB_chunks": "1,0,true,false", "token_level_256B_chunks": "4,0,false,false"}
+    builds = {"fp8_scales": "kv_move_kernel<%d,1,0,true,false> + kv_move_kernel<%d,1,0,false,false> (scale jobs)",
+              "one_kv_head_4KiB_chunks": "kv_move_kernel<%d,1,0,true,false>", "token_level_256B_chunks": "kv_move_small_kernel<%d,4,0>"}
     for name, what, g, nblk in shapes:
         build = builds[name]
         pool = torch.empty(g.pool_bytes, dtype=torch.uint8, device=dev)
@@ -823,9 +824,9 @@ def config8(kv, W, torch, dev, args, arena=None, streams=None):
         gg, ss = 2 * P / float(np.mean(gk)) / 1e6, 2 * P / float(np.mean(sk)) / 1e6
         out["kernels"][name] = {
             "what": what, "blocks": nblk, "payload_gib": round(P / 2**30, 2), "bytes_per_launch": 2 * P,
-            "gather": {"kernel": "kv_move_kernel<0,%s>" % build, "launch_ms": round(float(np.mean(gk)), 3),
+            "gather": {"kernel": build.replace("%d", "0"), "launch_ms": round(float(np.mean(gk)), 3),
                        "achieved": round(gg, 1), "frac": round(gg / HBM_PEAK_GBS, 4)},
-            "scatter": {"kernel": "kv_move_kernel<1,%s>" % build, "launch_ms": round(float(np.mean(sk)), 3),
+            "scatter": {"kernel": build.replace("%d", "1"), "launch_ms": round(float(np.mean(sk)), 3),
                         "achieved": round(ss, 1), "frac": round(ss / HBM_PEAK_GBS, 4)},
             "scrambled_copy_ceiling_gbps": {"run_bytes": run, "source_scrambled": round(2 * nbytes / src_c / 1e6, 1),
                                             "destination_scrambled": round(2 * nbytes / dst_c / 1e6, 1)}}

@@ -451,6 +451,7 @@ void run_grid(dim3 g, dim3 b, size_t lds_bytes, const std::function<void()>& lan
   if (fb.stack.size() < n) {
     fb.sp.resize(n);
     fb.state.resize(n);
+    fb.stack.reserve(n);  // first, so that a push_back that cannot allocate does not drop a stack it was just handed
     while (fb.stack.size() < n) fb.stack.push_back((char*)std::malloc(kLaneStack));  // reused by every later launch
   }
   fb.body = &lane;

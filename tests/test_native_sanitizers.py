@@ -209,6 +209,9 @@ KERNEL_MUTANTS = [
     ("ragged_last_piece_not_clipped", "        const int mine = left - lane0;", "        const int mine = left;"),
     ("k_and_v_planes_swapped", "      const int64_t plane = (int64_t)(k >> 1) * a.ls + (int64_t)(k & 1) * a.ks;",
      "      const int64_t plane = (int64_t)(k >> 1) * a.ls + (int64_t)((k & 1) ^ 1) * a.ks;"),
+    ("small_chunks_k_and_v_planes_swapped", "  auto plane_of = [&](int k) { return (int64_t)(k >> 1) * a.ls + (int64_t)(k & 1) * a.ks; };",
+     "  auto plane_of = [&](int k) { return (int64_t)(k >> 1) * a.ls + (int64_t)((k & 1) ^ 1) * a.ks; };"),
+    ("scale_jobs_launched_from_the_wrong_job", "    side.first_job = a.n_data_jobs;", "    side.first_job = a.n_data_jobs + 1;"),
     ("plane_by_plane_scatter_in_the_wrong_plane", "        k = (int)(job / a.per_plane);", "        k = (int)(job / a.per_plane) ^ 1;"),
     ("half_the_scale_vectors", "      const int vecs = a.scale_words >> 2;", "      const int vecs = a.scale_words >> 3;"),
     ("staging_slot_of_the_wrong_block", "        dst = a.contig + (int64_t)(uint32_t)ds.b * a.S + (int64_t)k * a.chunk;",
