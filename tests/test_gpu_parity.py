@@ -92,11 +92,12 @@ def run_both(g, seed, layout, path, n_req, lo, hi, n_victims, tune=(), bounce_sl
     gpu.close()
 
 
+@pytest.mark.parametrize("variant", [0, 1, 2], ids=["seed", "seed+1", "seed+2"])
 @pytest.mark.parametrize("path", list(PATHS))
-def test_config1_tiny_fp16(gpu, path):
+def test_config1_tiny_fp16(gpu, path, variant):
     """BASELINE config 1: fp16, L=2, H=4, D=64, B=16, 1024 blocks; 8 requests of 16-256 tokens;
-    3 swapped out, then swapped into different free blocks."""
-    wl = W.config(1)
+    3 swapped out, then swapped into different free blocks.  The configuration's own seed and two further ones."""
+    wl = W.config(1, variant=variant)
     run_both(wl.geom, wl.seed, "layer", path, wl.n_requests, 16, 256, wl.n_preempt)
 
 
