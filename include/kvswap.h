@@ -169,6 +169,9 @@ typedef struct {
 
 /* Create a handle over caller-owned memory.  Validates geometry, alignment and
  * capacity; allocates only the library's own descriptor rings and events.
+ * The GPU that holds pool_dev must be the current device of the calling thread
+ * (the handle's streams and descriptor memory are created there; KV_EINVAL
+ * otherwise).
  * Section 3.1 (separate CPU and GPU pools), Section 6 (dedicated streams). */
 int kv_pool_create(const kv_pool_config* cfg, kv_pool** out);
 

@@ -158,6 +158,13 @@ int kv_pool_create(const kv_pool_config* cfg, kv_pool** out) {
         KVDBG("pool_dev is not device memory (hip error %d, memory type %d)", (int)er, er == hipSuccess ? (int)at.type : -1);
       }
       (void)hipGetLastError();
+      // The handle's streams, events and descriptor memory belong to the device that is current now: the pool must
+      // live there too.
+      int cur = -1;
+      if (ok && (hipGetDevice(&cur) != hipSuccess || at.device != cur)) {
+        ok = false;
+        KVDBG("pool_dev lives on device %d, the current device is %d: make the pool's device current first", at.device, cur);
+      }
       if (ok) {
         er = hipPointerGetAttributes(&at, cfg->staging_host);
         if (er != hipSuccess) {

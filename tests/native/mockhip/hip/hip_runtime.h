@@ -24,7 +24,7 @@ enum { hipHostMallocDefault = 0 };
 enum hipMemcpyKind { hipMemcpyHostToDevice = 1, hipMemcpyDeviceToHost = 2, hipMemcpyDeviceToDevice = 3 };
 enum hipMemoryType { hipMemoryTypeHost = 1, hipMemoryTypeDevice = 2 };
 typedef void* hipDeviceptr_t;
-struct hipPointerAttribute_t { int type; void* devicePointer; void* hostPointer; };
+struct hipPointerAttribute_t { int type; int device; void* devicePointer; void* hostPointer; };
 struct hipDeviceProp_t { int multiProcessorCount; };
 struct dim3 { unsigned x, y, z; dim3(unsigned a = 1, unsigned b = 1, unsigned c = 1) : x(a), y(b), z(c) {} };
 

@@ -223,6 +223,7 @@ hipError_t hipPointerGetAttributes(hipPointerAttribute_t* at, const void* p) {
   auto* a = find_alloc(p);
   if (!a) return last_error = hipErrorInvalidValue;
   at->type = a->second.type;
+  at->device = 0;
   at->devicePointer = (void*)p;
   at->hostPointer = a->second.type == hipMemoryTypeHost ? (void*)p : nullptr;
   return hipSuccess;
