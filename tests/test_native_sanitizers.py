@@ -78,28 +78,30 @@ def _common_objects(flags):
     key = tuple(flags)
     if key not in _COMMON:
         import tempfile
+        from concurrent.futures import ThreadPoolExecutor
         d = tempfile.mkdtemp(prefix="mockhip_obj_")
-        objs = []
-        subprocess.check_call(["gcc", "-std=c99", "-c"] + flags + ["-o", os.path.join(d, "kv_oracle.o"),
-                               os.path.join(ROOT, "oracle", "kv_oracle.c")])
-        objs.append(os.path.join(d, "kv_oracle.o"))
+        jobs = [(["gcc", "-std=c99", "-c"] + flags, os.path.join(ROOT, "oracle", "kv_oracle.c"), os.path.join(d, "kv_oracle.o"))]
         for src in (os.path.join(MOCK, "mockhip.cpp"), os.path.join(HERE, "native", "runtime_on_mock_hip.cpp")):
-            obj = os.path.join(d, os.path.basename(src) + ".o")
-            subprocess.check_call([CLANGXX, "-std=c++17", "-Wall", "-pthread", "-c"] + flags +
-                                  ["-I", MOCK, "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "native"),
-                                   src, "-o", obj])
-            objs.append(obj)
-        _COMMON[key] = objs
+            jobs.append(([CLANGXX, "-std=c++17", "-Wall", "-pthread", "-c"] + flags +
+                         ["-I", MOCK, "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "native")],
+                         src, os.path.join(d, os.path.basename(src) + ".o")))
+        with ThreadPoolExecutor(max_workers=len(jobs)) as pool:     # three translation units, three compilers
+            list(pool.map(lambda j: subprocess.check_call(j[0] + [j[1], "-o", j[2]]), jobs))
+        _COMMON[key] = [j[2] for j in jobs]
     return _COMMON[key]
 
 
 def _build_on_mock(out_dir, name, csrc_dir, flags):
+    from concurrent.futures import ThreadPoolExecutor
     exe = os.path.join(out_dir, name)
     lib = os.path.join(out_dir, name + "_kvswap.o")
-    subprocess.check_call([CLANGXX, "-std=c++17", "-Wall", "-pthread", "-c"] + flags +
-                          ["-I", MOCK, "-I", os.path.join(ROOT, "include"), "-x", "c++", os.path.join(csrc_dir, "kvswap.hip"),
-                           "-o", lib])
-    subprocess.check_call([CLANGXX, "-pthread"] + flags + [lib] + _common_objects(flags) + ["-o", exe])
+    with ThreadPoolExecutor(max_workers=1) as pool:   # the library compiles while the common objects do (if they still have to)
+        compiling = pool.submit(subprocess.check_call, [CLANGXX, "-std=c++17", "-Wall", "-pthread", "-c"] + flags +
+                                ["-I", MOCK, "-I", os.path.join(ROOT, "include"), "-x", "c++",
+                                 os.path.join(csrc_dir, "kvswap.hip"), "-o", lib])
+        common = _common_objects(flags)
+        compiling.result()
+    subprocess.check_call([CLANGXX, "-pthread"] + flags + [lib] + common + ["-o", exe])
     return exe
 
 
@@ -189,10 +191,10 @@ def _mutated_sources(tmp_path, name, find, repl):
 
 
 @pytest.mark.parametrize("name,find,repl", RUNTIME_MUTANTS, ids=[m[0] for m in RUNTIME_MUTANTS])
-def test_a_missing_ordering_rule_is_noticed(tmp_path, name, find, repl):
+def test_a_missing_ordering_rule_is_noticed(name, find, repl):
     if not os.path.exists(CLANGXX):
         pytest.skip("no host clang++ for the kernel source")
-    exe = _build_on_mock(str(tmp_path), "mutant", _mutated_sources(tmp_path, name, find, repl), ["-O1"])
+    exe = _mutant_exe(name)
     failed_at = None
     for seed in range(48, 400):
         r = subprocess.run([exe, str(seed), "6"], capture_output=True, text=True, timeout=300)
@@ -219,11 +221,38 @@ KERNEL_MUTANTS = [
 ]
 
 
+_MUTANT_EXES = {}   # name -> path of the executable, or the exception its build raised
+
+
+def _mutant_exe(name):
+    """All mutants are built on first use, several compilers at a time (one translation unit each, seconds apiece)."""
+    if not _MUTANT_EXES:
+        import pathlib
+        import tempfile
+        from concurrent.futures import ThreadPoolExecutor
+        top = pathlib.Path(tempfile.mkdtemp(prefix="mockhip_mutants_"))
+        _common_objects(["-O1"])      # once, before the workers would race for it
+
+        def build(m):
+            d = top / m[0]
+            d.mkdir()
+            try:
+                return m[0], _build_on_mock(str(d), "mutant", _mutated_sources(d, *m), ["-O1"])
+            except Exception as e:    # reported by the test of this mutant, not by whichever test came first
+                return m[0], e
+        with ThreadPoolExecutor(max_workers=max(1, min(6, os.cpu_count() or 1))) as pool:
+            _MUTANT_EXES.update(pool.map(build, RUNTIME_MUTANTS + KERNEL_MUTANTS))
+    exe = _MUTANT_EXES[name]
+    if isinstance(exe, Exception):
+        raise exe
+    return exe
+
+
 @pytest.mark.parametrize("name,find,repl", KERNEL_MUTANTS, ids=[m[0] for m in KERNEL_MUTANTS])
-def test_a_mistake_in_the_kernel_arithmetic_is_noticed(tmp_path, name, find, repl):
+def test_a_mistake_in_the_kernel_arithmetic_is_noticed(name, find, repl):
     if not os.path.exists(CLANGXX):
         pytest.skip("no host clang++ for the kernel source")
-    exe = _build_on_mock(str(tmp_path), "kmutant", _mutated_sources(tmp_path, name, find, repl), ["-O1"])
+    exe = _mutant_exe(name)
     for seed in list(range(0, 48)) + list(range(192, 240)):
         r = subprocess.run([exe, str(seed), "4"], capture_output=True, text=True, timeout=300)
         if r.returncode != 0:   # a byte difference, or the wild access ended the process
