@@ -157,6 +157,14 @@ def test_scatter_plane_by_plane(gpu, layout):
     run_both(g, 0x9A7F, layout, "device", 3, 16, 48, 2, tune=((kv.KV_TUNE_SCATTER_ORDER, 2), (kv.KV_TUNE_MAX_WGS_DEVICE, 5)))
 
 
+def test_scatter_plane_by_plane_with_scales(gpu):
+    """A pool with scales has the same two job orders for its data; its scale jobs follow in a launch of their own."""
+    g = W.Geometry(4, 32, 128, 32, "fp8_e4m3", 128, scales=True)   # 128 KiB chunks, 128-byte scale pieces
+    run_both(g, 0x5CA7, "layer", "device", 6, 32, 256, 4, tune=((kv.KV_TUNE_SCATTER_ORDER, 2),))
+    g2 = W.Geometry(2, 8, 64, 16, "fp8_e4m3", 300, scales=True)    # 8 KiB chunks
+    run_both(g2, 0x5CA8, "padded", "device", 9, 16, 300, 5, tune=((kv.KV_TUNE_SCATTER_ORDER, 2), (kv.KV_TUNE_MAX_WGS_DEVICE, 5)))
+
+
 def test_scatter_order_is_chosen_by_timing(gpu):
     """1024 blocks and more, both ends in HBM: the first such swap-in goes block by block, the second plane by plane,
     the later ones use whichever has the better rate so far (kv_stats.scatter_order says which; with launches as
