@@ -393,6 +393,9 @@ def compact(name, r):
                 "preempt_after_write_through_ms_per_request": r["preempt_32_after_write_through"]["ms_per_request"],
                 "preempt_cold_ms_per_request": r["preempt_32_cold"]["ms_per_request"],
                 "resume_ms_per_request": r["resume_32"]["ms_per_request"],
+                "step_next_to_compute": {k: ([v["call_to_sync_us_p50"], v["call_to_sync_us_p99"], v["co_runner_traffic_gbps"]]
+                                             if isinstance(v, dict) else v)
+                                         for k, v in r["delta_step_next_to_compute"].items()},
                 "d2h_gbps": r["d2h_gbps"], "h2d_gbps": r["h2d_gbps"]}
     if name == "configs[4]":
         c = r["contended"]

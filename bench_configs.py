@@ -374,6 +374,49 @@ def config3(kv, W, torch, dev, args, arena=None, streams=None):
     cold_ms = (time.perf_counter() - a) * 1e3
     vbytes = len(vflat) * g.S
     mean_blocks = float(np.mean(step_blocks))
+    kp.close()
+
+    # (c) the same 64 write-through steps next to compute (Section 5.2: the writes of a decode iteration overlap the
+    # next one): a read-modify-write kernel streams through 2 GiB on a third stream all the while.  Once with the
+    # zero-copy kernels, once through the bounce buffer and the copy engines.
+    class FineSideLoad(SideLoad):
+        GROUP = 1
+    co = FineSideLoad(torch, dev, streams.side, nbytes=2 << 30)
+    co.feed(200)
+    co.rate_gbps()
+    co.reset()
+    co.feed(200)
+    co_alone, _ = co.rate_gbps()
+    bounce = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+    busy = {"co_runner_alone_traffic_gbps": round(co_alone, 1)}
+    for name, flags, kw in (("zerocopy", kv.KV_PATH_ZEROCOPY, {}), ("copy_engines", kv.KV_PATH_DMA, {"bounce": bounce})):
+        kq = kv.KVPool(g, pool, staging, flags=flags, **kw, **skw)
+        for i in range(n):
+            ok(kv, kq.reserve(rid[i], int(final_nb[i])), "kv_req_reserve")
+        c2 = lens.copy()
+        o, flat = tables(c2)
+        rc, moved = kq.swap_out_delta(rid, o, flat, c2)
+        ok(kv, rc, "kv_swap_out_delta")
+        ok(kv, kq.sync(), "kv_sync")
+        torch.cuda.synchronize()
+        co.reset()
+        us, blocks = [], 0
+        for s_ in range(steps):
+            c2 += 1
+            o, flat = tables(c2)
+            co.feed(40)                                # ~0.7 ms a pass alone: the stream never runs dry during a step
+            a = time.perf_counter()
+            rc, moved = kq.swap_out_delta(rid, o, flat, c2)
+            ok(kv, rc, "kv_swap_out_delta")
+            ok(kv, kq.sync(), "kv_sync")
+            us.append((time.perf_counter() - a) * 1e6)
+            blocks += int(moved.sum())
+        co.mark()
+        rate, _ = co.rate_gbps()
+        busy[name] = {"call_to_sync_us_p50": pct(us, 50), "call_to_sync_us_p99": pct(us, 99),
+                      "gbps_mean": round(blocks * g.S / (sum(us) * 1e-6) / 1e9, 2), "co_runner_traffic_gbps": round(rate, 1)}
+        kq.close()
+    del bounce, co
     res = {"config": 3, "workload": "configs[2]: 8B shape, 256 requests log-normal (median 1k), 64 decode steps, then 32 preempted + resumed",
            "measured_link_gbps": {"d2h": link[0], "h2d": link[1]},
            "priming_delta": {"blocks": prime_blocks, "gib": round(prime_blocks * g.S / 2**30, 2),
@@ -389,11 +432,11 @@ def config3(kv, W, torch, dev, args, arena=None, streams=None):
                                "gbps": round(vbytes / cold_ms / 1e6, 2)},
            "resume_32": {"blocks": len(vflat), "ms": round(resume_ms, 3), "ms_per_request": round(resume_ms / len(victims), 3),
                          "gbps": round(vbytes / resume_ms / 1e6, 2)},
+           "delta_step_next_to_compute": busy,
            "d2h_gbps": round(vbytes / cold_ms / 1e6, 2), "h2d_gbps": round(vbytes / resume_ms / 1e6, 2),
            "p50_preempt_ms": round(warm_ms / len(victims), 4), "p50_resume_ms": round(resume_ms / len(victims), 3),
            "latency_def": "per request inside the 32-request calls: preempt = tail flush after write-through (Section 5.1; "
                           "cold, the same call takes preempt_32_cold), resume = full swap-in"}
-    kp.close()
     del pool
     release(torch)
     return res
