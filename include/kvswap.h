@@ -108,7 +108,7 @@ enum {
 
 /* kv_pool_config.flags */
 enum {
-  KV_PATH_AUTO = 0u,      /* zero-copy, except: with a bounce buffer, transfers of 32 MiB and more
+  KV_PATH_AUTO = 0u,      /* zero-copy, except: with a bounce buffer, transfers of 8 MiB and more
                              go through it and the copy engines (robust next to running compute) */
   KV_PATH_DMA = 1u,       /* gather into bounce_dev, then hipMemcpyAsync (needs bounce_dev) */
   KV_PATH_ZEROCOPY = 2u,  /* kernels store to / load from the mapped host arena directly */

@@ -497,7 +497,7 @@ def test_wait_event_orders_after_producer(gpu):
 
 
 def test_auto_path_choice(gpu):
-    """KV_PATH_AUTO: zero-copy without a bounce buffer; with one, transfers of 32 MiB and more go
+    """KV_PATH_AUTO: zero-copy without a bounce buffer; with one, transfers of 8 MiB and more go
     through the copy engines.  Either way the bytes are the oracle's."""
     import torch
     g = W.Geometry(8, 8, 128, 16, "bf16", 400)             # block = 512 KiB
